@@ -1,0 +1,308 @@
+"""CPU oracle for the schedule side: building blocks, repetition, pass orders, lifetime accounting.
+
+TEST INFRASTRUCTURE ONLY.  Nothing in the product path may import this file; the C++ schedule
+generator in the library is a separate implementation and the two share no code.
+
+Follows the paper's construction (Section 2): lay out the passes of ONE microbatch on a
+device x time grid (the building block), repeat the block every T cells for the next microbatch
+(legal only if no two passes land in one cell), and keep each device's pass order when bubbles are
+squeezed out.  T is the number of unit passes a device runs per microbatch: 6 here (2 F, 2 B, 2 W).
+
+V-shape blocks (Section 3, Section 3.1, Appendix A notation, Appendix F tables): the model is cut
+into 2d chunks; device i holds chunk i ("chunk 0" of the device) and chunk 2d-1-i ("chunk 1").
+Adjacent F passes of the first half are delta0 cells apart, of the second half delta1 cells apart;
+B passes of the second half (which run device 0 -> d-1) use delta0 and B passes of the first half
+use delta1.  Three same-device offsets complete the block: F turn-around on the last device, F->B
+turn-around on the first device, B turn-around on the last device.  W passes then take, in the
+order of their B passes, the first cell after their own B that is still free modulo T.
+
+Readings where the paper is unclear (all listed in the design notes of the repository):
+ * Appendix F's tables label the two B columns the other way round from Section 3.1's text; the
+   text is followed (the literal table reading collides for every d).
+ * The same-device offsets of V-ZB are found by brute force in the paper and never printed;
+   (1, 1, 1) is used.  best_vzb_offsets() below repeats the brute force and is pinned to that.
+ * The optional reordering step of Section 2 is not applied.
+ * A 1F1B stage is two consecutive chunks with B and W fused per chunk, upper chunk first.
+
+Parity pins (tests/test_oracle_schedule.py): Section 3.2's exact peak formulas for every d, Table
+1's peaks for 1F1B and V-ZB, Equation 1 as an upper bound, independence of n, balance across
+devices, Table 1's bubble column, the bubble rate formula of Appendix D.3 for 1F1B.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from itertools import product
+
+T = 6
+KINDS = ("1f1b", "vzb", "vhalf", "vmin")
+
+
+@dataclass(frozen=True)
+class Pass:
+    time: int      # cell index of the pass in the repeated (unsqueezed) grid
+    device: int
+    op: str        # "F", "B" or "W"
+    chunk: int     # 0 or 1: which of the device's two chunks
+    mb: int        # microbatch
+
+    @property
+    def key(self):
+        return (self.op, self.chunk, self.mb)
+
+
+def model_chunk(kind: str, d: int, device: int, chunk: int) -> int:
+    """Position of a device's chunk in the model (0 .. 2d-1)."""
+    if kind == "1f1b":
+        return 2 * device + chunk
+    return device if chunk == 0 else 2 * d - 1 - device
+
+
+def vshape_params(kind: str, d: int):
+    """(delta0, delta1, F turn on last device, F->B turn on first device, B turn on last device)."""
+    if kind == "vmin":      # Table 1 row V-Min; Appendix F first table
+        return 1, 1, 1, (3 if d % 3 == 0 else 1), 1
+    if kind == "vhalf":     # Table 1 row V-Half; Appendix F second table
+        return 2, 1, 2, (4 if d % 2 == 0 else 1), 1
+    if kind == "vzb":       # Table 1 row V-ZB; same-device offsets not printed
+        return 4, 2, 1, 1, 1
+    raise ValueError(kind)
+
+
+def vshape_block(d: int, delta0: int, delta1: int, a: int, b: int, c: int):
+    """Cell index of each pass of one microbatch: dict (op, chunk) -> list over devices.
+    Returns None if repeating the block every T cells would put two F/B passes in one cell."""
+    tF0 = [i * delta0 for i in range(d)]
+    tF1 = [0] * d
+    tF1[d - 1] = tF0[d - 1] + a
+    for i in range(d - 2, -1, -1):
+        tF1[i] = tF1[i + 1] + delta1
+    tB1 = [0] * d
+    tB1[0] = tF1[0] + b
+    for i in range(1, d):
+        tB1[i] = tB1[i - 1] + delta0
+    tB0 = [0] * d
+    tB0[d - 1] = tB1[d - 1] + c
+    for i in range(d - 2, -1, -1):
+        tB0[i] = tB0[i + 1] + delta1
+    tW1, tW0 = [0] * d, [0] * d
+    for i in range(d):
+        used = {tF0[i] % T, tF1[i] % T, tB1[i] % T, tB0[i] % T}
+        if len(used) != 4:
+            return None
+        for tB, tW in ((tB1, tW1), (tB0, tW0)):     # chunk 1's B comes first on every device
+            t = tB[i] + 1
+            while t % T in used:
+                t += 1
+            used.add(t % T)
+            tW[i] = t
+    return {("F", 0): tF0, ("F", 1): tF1, ("B", 1): tB1, ("B", 0): tB0, ("W", 1): tW1, ("W", 0): tW0}
+
+
+def one_f_one_b_block(d: int):
+    """1F1B at chunk granularity: a stage's F covers two cells (lower chunk first), its fused
+    backward four cells (B, W of the upper chunk, then B, W of the lower chunk).  Adjacent stages'
+    forwards are 2 cells apart and backwards 4 cells apart (Table 1)."""
+    tF = [2 * i for i in range(d)]
+    tBW = [2 * d + 4 * (d - 1 - i) for i in range(d)]
+    return {("F", 0): tF, ("F", 1): [t + 1 for t in tF],
+            ("B", 1): tBW, ("W", 1): [t + 1 for t in tBW],
+            ("B", 0): [t + 2 for t in tBW], ("W", 0): [t + 3 for t in tBW]}
+
+
+def block(kind: str, d: int):
+    if d < 1:
+        raise ValueError("d must be positive")
+    if kind == "1f1b":
+        return one_f_one_b_block(d)
+    blk = vshape_block(d, *vshape_params(kind, d))
+    if blk is None:
+        raise ValueError(f"{kind} block collides for d={d}")
+    return blk
+
+
+def repeat(blk, d: int, n: int):
+    """All passes of n microbatches: microbatch j's block is shifted by j*T.  Checks that no cell
+    of any device is used twice."""
+    passes = []
+    seen = set()
+    for (op, chunk), times in blk.items():
+        for i in range(d):
+            for j in range(n):
+                t = times[i] + j * T
+                if (i, t) in seen:
+                    raise ValueError("collision")
+                seen.add((i, t))
+                passes.append(Pass(t, i, op, chunk, j))
+    return passes
+
+
+def device_orders(passes, d: int):
+    """Per-device pass order: by cell index (squeezing keeps it)."""
+    return [sorted((p for p in passes if p.device == i), key=lambda p: p.time) for i in range(d)]
+
+
+def global_order(passes):
+    """One-stream replay order: by cell index, ties between devices by device index.  Every
+    dependency of a pass sits in a strictly earlier cell, so this is a topological order."""
+    return sorted(passes, key=lambda p: (p.time, p.device))
+
+
+def build(kind: str, d: int, n: int):
+    return repeat(block(kind, d), d, n)
+
+
+# --------------------------------------------------------------------------- lifetime accounting
+
+def peak_units(kind: str, d: int, n: int):
+    """Peak number of live activation units per device (Section 2.2: a unit is allocated when its
+    F starts and retained until both its B and W are done).  For 1F1B the unit of allocation is the
+    stage: both chunks' units are taken when the stage's F starts and returned when its fused
+    backward ends."""
+    peaks = []
+    for order in device_orders(build(kind, d, n), d):
+        live = peak = 0
+        for p in order:
+            if kind == "1f1b":
+                if p.op == "F" and p.chunk == 0:
+                    live += 2
+                elif p.op == "W" and p.chunk == 0:
+                    peak = max(peak, live)
+                    live -= 2
+            else:
+                if p.op == "F":
+                    live += 1
+                elif p.op == "W":
+                    peak = max(peak, live)
+                    live -= 1
+            peak = max(peak, live)
+        peaks.append(peak)
+    return peaks
+
+
+def peak_bytes(kind: str, d: int, n: int, unit_bytes: int, stats_bytes: int):
+    """Per device: (peak pool bytes, peak tensor bytes).
+
+    Pool bytes count whole units of unit_bytes from F start to W end.  Tensor bytes follow the
+    tensor table at pass boundaries: a unit weighs unit_bytes until its B has ended and
+    unit_bytes - stats_bytes (the fp32 statistics are dead) from then until its W ends."""
+    out = []
+    units = peak_units(kind, d, n)
+    for i, order in enumerate(device_orders(build(kind, d, n), d)):
+        live = peak = 0
+        for p in order:
+            if kind == "1f1b":
+                if p.op == "F" and p.chunk == 0:
+                    live += 2 * unit_bytes
+                elif p.op == "B":
+                    peak = max(peak, live)
+                    live -= stats_bytes
+                elif p.op == "W" and p.chunk == 0:
+                    live -= 2 * (unit_bytes - stats_bytes)
+            else:
+                if p.op == "F":
+                    live += unit_bytes
+                elif p.op == "B":
+                    peak = max(peak, live)
+                    live -= stats_bytes
+                elif p.op == "W":
+                    live -= unit_bytes - stats_bytes
+            peak = max(peak, live)
+        assert live == 0
+        out.append((units[i] * unit_bytes, peak))
+    return out
+
+
+def lifespans(blk, d: int):
+    """Per device, per chunk: cells from the start of F to the end of W."""
+    return [[blk[("W", c)][i] + 1 - blk[("F", c)][i] for c in (0, 1)] for i in range(d)]
+
+
+def equation1_bound(kind: str, d: int):
+    """Equation 1: per device, sum over its chunks of ceil(lifespan / T) units.  For 1F1B the two
+    chunks of a stage live from the stage's F start to the end of its fused backward."""
+    blk = block(kind, d)
+    out = []
+    for i in range(d):
+        if kind == "1f1b":
+            l = blk[("W", 0)][i] + 1 - blk[("F", 0)][i]
+            out.append(2 * -(-l // T))
+        else:
+            out.append(sum(-(-l // T) for l in lifespans(blk, d)[i]))
+    return out
+
+
+# --------------------------------------------------------------------------- squeezing (unit times)
+
+def _asap_finish(passes, kind: str, d: int, dur):
+    """Run every device's order as early as dependencies allow and return the finish time.
+
+    Dependencies: F of a model chunk needs F of the previous chunk (same microbatch); B needs B of
+    the next chunk (the last chunk's B needs its own F); W needs its own B; a device runs one pass
+    at a time in its fixed order.  In 1F1B a stage's backward is one fused pass, so the stage
+    before it waits for the end of that pass."""
+    orders = device_orders(passes, d)
+    end = {}
+    nxt = [0] * d
+    free_at = [0.0] * d
+    remaining = len(passes)
+    last = 2 * d - 1
+    while remaining:
+        progressed = False
+        for i in range(d):
+            while nxt[i] < len(orders[i]):
+                p = orders[i][nxt[i]]
+                mc = model_chunk(kind, d, p.device, p.chunk)
+                if p.op == "F":
+                    deps = [("F", mc - 1, p.mb)] if mc > 0 else []
+                elif p.op == "B":
+                    deps = [("B", mc + 1, p.mb)] if mc < last else [("F", mc, p.mb)]
+                    if kind == "1f1b" and p.chunk == 1 and mc < last:
+                        # B and W are one fused pass: the next stage hands its gradient over
+                        # only when that whole pass (which ends with its lower chunk's W) is done
+                        deps = [("W", mc + 1, p.mb)]
+                else:
+                    deps = [("B", mc, p.mb)]
+                if any(dep not in end for dep in deps):
+                    break
+                start = max([free_at[i]] + [end[dep] for dep in deps])
+                end[(p.op, mc, p.mb)] = free_at[i] = start + dur[p.op]
+                nxt[i] += 1
+                remaining -= 1
+                progressed = True
+        if not progressed:
+            raise RuntimeError("deadlock: orders contradict dependencies")
+    return max(free_at)
+
+
+def squeezed_makespan(kind: str, d: int, n: int, tf: float = 1.0, tb: float = 1.0, tw: float = 1.0):
+    """Finish time of the squeezed schedule with the given pass durations."""
+    return _asap_finish(build(kind, d, n), kind, d, {"F": tf, "B": tb, "W": tw})
+
+
+def bubbles(kind: str, d: int, n: int):
+    """Unit-time idle cells per device after squeezing: makespan minus the 6n cells of work."""
+    return squeezed_makespan(kind, d, n) - T * n
+
+
+def best_vzb_offsets(d: int, n: int | None = None):
+    """The brute force of Section 3.1 for V-ZB's same-device offsets: among collision-free
+    (a, b, c) below the repeating interval, those with the least (max peak units, squeezed
+    makespan at unit pass times); returned sorted."""
+    n = n or 4 * d
+    scored = []
+    for a, b, c in product(range(1, T), repeat=3):
+        blk = vshape_block(d, 4, 2, a, b, c)
+        if blk is None:
+            continue
+        passes = repeat(blk, d, n)
+        peak = 0
+        for order in device_orders(passes, d):
+            live = 0
+            for p in order:
+                live += p.op == "F"
+                peak = max(peak, live)
+                live -= p.op == "W"
+        span = _asap_finish(passes, "vzb", d, {"F": 1, "B": 1, "W": 1})
+        scored.append(((peak, span), (a, b, c)))
+    best = min(s for s, _ in scored)
+    return sorted(t for s, t in scored if s == best)

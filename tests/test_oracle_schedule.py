@@ -1,0 +1,198 @@
+"""Pins for oracle/schedule.py against what the paper prints and what the construction implies."""
+import json
+import math
+import os
+
+import pytest
+
+from oracle import schedule as S
+
+GOLD = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "paper_tables.json")))
+
+
+@pytest.mark.parametrize("d", list(range(2, 13)) + [16, 24, 32])
+def test_exact_peak_formulas(d):
+    """Section 3.2: V-Min ceil((d+2)/3) M/d, V-Half ceil((d+1)/2) M/d; M/d = 2 units."""
+    n = 4 * d
+    for kind in ("vmin", "vhalf"):
+        g = GOLD["exact_peak"][kind]
+        want = 2 * math.ceil((d + g["numerator_add"]) / g["divisor"])
+        assert max(S.peak_units(kind, d, n)) == want
+
+
+@pytest.mark.parametrize("d", [2, 3, 4, 5, 8, 16])
+def test_table1_peaks_1f1b_vzb(d):
+    """Table 1: 1F1B and V-ZB peak at M = 2d units; 1F1B's bottleneck is the first device and
+    decreases down the pipeline, V-ZB is balanced (Section 3, Figure 3 caption)."""
+    n = 4 * d
+    assert S.peak_units("1f1b", d, n) == [2 * (d - i) for i in range(d)]
+    assert S.peak_units("vzb", d, n) == [2 * d] * d
+
+
+@pytest.mark.parametrize("kind", ["vzb", "vhalf", "vmin"])
+@pytest.mark.parametrize("d", [2, 3, 4, 5, 6, 7, 8, 9, 12])
+def test_block_offsets_follow_tables(kind, d):
+    """Table 1's delta0/delta1 between devices and Appendix F's same-device offsets."""
+    blk = S.block(kind, d)
+    t1 = GOLD["table1"][kind]
+    F0, F1, B1, B0 = blk[("F", 0)], blk[("F", 1)], blk[("B", 1)], blk[("B", 0)]
+    for i in range(d - 1):
+        assert F0[i + 1] - F0[i] == t1["delta0"]
+        assert F1[i] - F1[i + 1] == t1["delta1"]
+        assert B1[i + 1] - B1[i] == t1["delta0"]
+        assert B0[i] - B0[i + 1] == t1["delta1"]
+    if kind in GOLD["appendix_f"]:
+        g = GOLD["appendix_f"][kind]
+        row = g["rows"]["0"] if d % g["d_mod"] == 0 else g["rows"]["other"]
+        assert [F1[d - 1] - F0[d - 1], B1[0] - F1[0], B0[d - 1] - B1[d - 1]] == row
+
+
+@pytest.mark.parametrize("kind", S.KINDS)
+@pytest.mark.parametrize("d", [2, 3, 4, 6, 8])
+def test_legality_and_orders(kind, d):
+    n = 3 * d
+    passes = S.build(kind, d, n)
+    assert len(passes) == 6 * n * d
+    assert len({(p.device, p.time) for p in passes}) == len(passes)          # no collision
+    for i, order in enumerate(S.device_orders(passes, d)):
+        assert len(order) == GOLD["repeat_interval"]["T"] * n
+        pos = {p.key: k for k, p in enumerate(order)}
+        for c in (0, 1):
+            for j in range(n):
+                assert pos[("F", c, j)] < pos[("B", c, j)] < pos[("W", c, j)]
+            for op in "FBW":                                                  # microbatches in order
+                idx = [pos[(op, c, j)] for j in range(n)]
+                assert idx == sorted(idx)
+    # the one-stream order respects every cross-device dependency
+    seen = set()
+    last = 2 * d - 1
+    for p in S.global_order(passes):
+        mc = S.model_chunk(kind, d, p.device, p.chunk)
+        if p.op == "F" and mc > 0:
+            assert ("F", mc - 1, p.mb) in seen
+        if p.op == "B":
+            assert ("F", mc, p.mb) in seen
+            if mc < last:
+                assert ("B", mc + 1, p.mb) in seen
+        if p.op == "W":
+            assert ("B", mc, p.mb) in seen
+        seen.add((p.op, mc, p.mb))
+    S.squeezed_makespan(kind, d, n)   # raises on deadlock
+
+
+def test_placement():
+    """Section 3: 2d chunks, second half placed in reverse device order."""
+    d = 4
+    assert [S.model_chunk("vhalf", d, i, 0) for i in range(d)] == [0, 1, 2, 3]
+    assert [S.model_chunk("vhalf", d, i, 1) for i in range(d)] == [7, 6, 5, 4]
+    assert [S.model_chunk("1f1b", d, i, c) for i in range(d) for c in (0, 1)] == list(range(8))
+
+
+@pytest.mark.parametrize("kind", S.KINDS)
+@pytest.mark.parametrize("d", [2, 3, 4, 5, 6, 8, 9])
+def test_equation1_bounds_replayed_peak(kind, d):
+    """Equation 1: peak <= sum over the device's stages of ceil(lifespan / T) units."""
+    peaks = S.peak_units(kind, d, 5 * d)
+    bound = S.equation1_bound(kind, d)
+    assert all(p <= b for p, b in zip(peaks, bound))
+    assert max(b - p for p, b in zip(peaks, bound)) <= 1
+
+
+@pytest.mark.parametrize("kind", S.KINDS)
+def test_peak_independent_of_n_once_steady(kind):
+    """Table 4's activation-memory rows do not change with the number of microbatches."""
+    d = 4
+    base = S.peak_units(kind, d, 2 * d)
+    for n in (3 * d, 8 * d, 16 * d):
+        assert S.peak_units(kind, d, n) == base
+
+
+def test_asymptotic_ratios():
+    """Abstract / Table 1: V-Half tends to 1/2 and V-Min to 1/3 of 1F1B's peak."""
+    d, n = 64, 256
+    base = max(S.peak_units("1f1b", d, n))
+    assert base == 2 * d
+    assert max(S.peak_units("vhalf", d, n)) / base == pytest.approx(66 / 128)
+    assert max(S.peak_units("vmin", d, n)) / base == pytest.approx(44 / 128)
+    assert abs(max(S.peak_units("vhalf", d, n)) / base - 0.5) < 0.02
+    assert abs(max(S.peak_units("vmin", d, n)) / base - 1 / 3) < 0.02
+
+
+def test_config_ratios():
+    """Exact ratios at the replay configurations: d=2 gives no saving, d=4 gives 3/4 and 1/2."""
+    assert S.peak_units("1f1b", 2, 4) == [4, 2]
+    assert S.peak_units("vhalf", 2, 4) == [4, 4]
+    assert S.peak_units("vmin", 2, 4) == [2, 4]
+    assert S.peak_units("vzb", 2, 4) == [4, 4]
+    assert S.peak_units("vhalf", 4, 16) == [6] * 4
+    assert S.peak_units("vmin", 4, 16) == [4] * 4
+    assert S.peak_units("vzb", 4, 16) == [8] * 4
+    assert S.peak_units("1f1b", 4, 16) == [8, 6, 4, 2]
+
+
+@pytest.mark.parametrize("d", [4, 8, 16, 32])
+def test_table1_bubbles(d):
+    """Table 1's bubble column (unit pass times, small constants ignored): 1F1B ~6d, V-Min ~4d,
+    V-Half ~3d, V-ZB ~0 (a constant's worth per device, never growing with n)."""
+    n = 6 * d
+    b = {k: S.bubbles(k, d, n) for k in S.KINDS}
+    assert b["1f1b"] == 6 * (d - 1)
+    assert abs(b["vmin"] - 4 * d) <= 6
+    assert abs(b["vhalf"] - 3 * d) <= 6 if d <= 8 else abs(b["vhalf"] / d - 3) < 0.6
+    assert b["vzb"] < b["vhalf"] < b["vmin"] < b["1f1b"] or d == 4
+    assert b["vzb"] <= 2 * d
+    assert S.bubbles("vzb", d, 12 * d) == b["vzb"]          # does not grow with n
+
+
+@pytest.mark.parametrize("p,n", [(4, 8), (8, 32), (16, 64)])
+def test_1f1b_bubble_rate(p, n):
+    """Appendix D.3: 1F1B bubble rate (p-1)/(p+n-1) with equal-length F and BW stage passes
+    (here a stage pass is 2 F cells and 4 BW cells, so the rate is taken on the 6-cell unit)."""
+    span = S.squeezed_makespan("1f1b", p, n)
+    assert (span - 6 * n) / span == pytest.approx((p - 1) / (p + n - 1))
+
+
+@pytest.mark.parametrize("kind", S.KINDS)
+@pytest.mark.parametrize("d", [4, 8])
+def test_runtime_lower_bound(kind, d):
+    """Appendix E.2: with peak k*m and unit times the runtime is at least 6n + 6d - 3k - 1."""
+    n = 4 * d
+    k = max(S.peak_units(kind, d, n))
+    assert S.squeezed_makespan(kind, d, n) >= 6 * n + 6 * d - 3 * k - 1
+
+
+@pytest.mark.parametrize("d", [2, 3, 4, 5, 6, 8])
+def test_vzb_offsets_brute_force(d):
+    """Section 3.1's brute force over same-device offsets: (1, 1, 1) is optimal for V-ZB."""
+    assert (1, 1, 1) in S.best_vzb_offsets(d)
+
+
+def test_appendix_f_literal_header_collides():
+    """The reading NOT taken: with the two B offsets swapped (B of the second half using delta1)
+    V-Half's block collides, which is why the text of Section 3.1 is followed."""
+    for d in range(3, 10):
+        a, b, c = (2, 4 if d % 2 == 0 else 1, 1)
+        tF0 = [2 * i for i in range(d)]
+        tF1 = [0] * d
+        tF1[d - 1] = tF0[d - 1] + a
+        for i in range(d - 2, -1, -1):
+            tF1[i] = tF1[i + 1] + 1
+        tB1 = [tF1[0] + b + 1 * i for i in range(d)]          # literal header: delta B^1 = 1
+        tB0 = [0] * d
+        tB0[d - 1] = tB1[d - 1] + c
+        for i in range(d - 2, -1, -1):
+            tB0[i] = tB0[i + 1] + 2                           # literal header: delta B^0 = 2
+        assert any(len({tF0[i] % 6, tF1[i] % 6, tB1[i] % 6, tB0[i] % 6}) < 4 for i in range(d))
+
+
+def test_peak_bytes_table():
+    """Bytes follow units: pool bytes = units * m; tensor bytes differ only by dead statistics."""
+    from oracle.layer import chunk_activation_bytes, chunk_stats_bytes
+    m = chunk_activation_bytes(2, 4096, 32, 2048, 2)
+    st = chunk_stats_bytes(2, 32, 2048)
+    assert m == 537460736                      # 2 * (16*2048*4096*2 + 36*2048*4)
+    for kind, units in (("1f1b", [8, 6, 4, 2]), ("vzb", [8] * 4), ("vhalf", [6] * 4), ("vmin", [4] * 4)):
+        got = S.peak_bytes(kind, 4, 16, m, st)
+        assert [g[0] for g in got] == [u * m for u in units]
+        for (pool, tensor), u in zip(got, units):
+            assert pool - u * st <= tensor <= pool

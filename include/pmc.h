@@ -1,0 +1,243 @@
+/*
+ * pmc.h - C ABI of the pipeline-stage library ("pipeline parallelism with controllable memory").
+ *
+ * One pipeline stage's work for one microbatch is split, as in Section 2.1 of the paper, into
+ *   F  forward pass,
+ *   B  backward for the activations (gradient w.r.t. the stage input),
+ *   W  backward for the weights (may be deferred),
+ * and a schedule is the per-device order of such passes obtained by repeating a building block
+ * (Section 2).  This library runs F, B and W of a chunk of pre-LayerNorm GPT layers as HIP kernels
+ * for gfx950, generates the 1F1B / V-ZB / V-Half / V-Min orders (Section 3, Table 1, Appendix F),
+ * and replays a whole schedule on one GPU stream while an activation pool does the lifetime
+ * bookkeeping of Section 2.2 (a unit is allocated when F starts and retained until both B and W
+ * have consumed it).
+ *
+ * Conventions
+ *  - Every function returns PMC_OK (0) or a negative pmc_status; nothing throws or aborts.
+ *    pmc_last_error() returns a thread-local, human-readable description of the last failure.
+ *  - Pointers named "device" are GPU memory, BORROWED from the caller: the library never allocates
+ *    or frees device memory.  Everything else is host memory.
+ *  - Work is enqueued on the HIP stream given to pmc_create and is asynchronous unless stated.
+ *  - Tensors are row-major.  Activations are [tokens, hidden] with tokens = microbatch * seq
+ *    (sequences of one microbatch stored back to back).  Storage type is float (PMC_F32) or
+ *    bfloat16 (PMC_BF16; all accumulation in fp32).  Gradients of parameters are always fp32.
+ *  - Layer (Section 4.1 says GPT-like; details are this library's stated reading): pre-LN block,
+ *    LayerNorm with biased variance and eps inside the root, tanh-form GeLU, biases on the four
+ *    linear maps, optional causal mask, no dropout.  Packed qkv columns are [q | k | v], each with
+ *    the heads' slices side by side.
+ *  - Parameter order per layer (PMC_PARAMS_PER_LAYER pointers, layer after layer):
+ *      0 ln1_gain[h] 1 ln1_bias[h] 2 w_qkv[h,3h] 3 b_qkv[3h] 4 w_o[h,h] 5 b_o[h]
+ *      6 ln2_gain[h] 7 ln2_bias[h] 8 w_1[h,ffn] 9 b_1[ffn] 10 w_2[ffn,h] 11 b_2[h]
+ *    Weights are stored [in, out].  Gradient buffers have the same shapes in fp32 and are
+ *    ACCUMULATED into (never cleared) by B (LayerNorm gain/bias) and W (weights and biases).
+ */
+#ifndef PMC_H
+#define PMC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PMC_PARAMS_PER_LAYER 12
+
+typedef enum pmc_status {
+  PMC_OK = 0,
+  PMC_ERR_INVALID = -1,     /* bad argument or unsupported shape                              */
+  PMC_ERR_STATE = -2,       /* pass order violated: B before F, W before B, live id reused    */
+  PMC_ERR_NOMEM = -3,       /* activation pool or workspace too small / exhausted             */
+  PMC_ERR_HIP = -4,         /* a HIP runtime call failed                                      */
+  PMC_ERR_ILLEGAL_BLOCK = -5 /* building block collides when repeated (Section 2.3)           */
+} pmc_status;
+
+typedef enum pmc_dtype { PMC_F32 = 0, PMC_BF16 = 1 } pmc_dtype;
+typedef enum pmc_kind { PMC_1F1B = 0, PMC_VZB = 1, PMC_VHALF = 2, PMC_VMIN = 3 } pmc_kind;
+typedef enum pmc_op { PMC_F = 0, PMC_B = 1, PMC_W = 2 } pmc_op;
+
+typedef struct pmc_ctx pmc_ctx;
+typedef struct pmc_chunk pmc_chunk;
+typedef struct pmc_schedule pmc_schedule;
+
+typedef struct pmc_chunk_cfg {
+  int32_t layers, hidden, heads, ffn, seq, microbatch;
+  int32_t dtype;  /* pmc_dtype */
+  int32_t causal; /* 1 = causal mask */
+  float ln_eps;
+} pmc_chunk_cfg;
+
+/* One pass of a schedule.  `chunk` is 0 or 1 (which of the device's two chunks), `model_chunk`
+ * its position in the model (0 .. 2d-1), `time` its cell in the repeated, unsqueezed grid. */
+typedef struct pmc_pass {
+  int32_t time, device, op, chunk, mb, model_chunk;
+} pmc_pass;
+
+typedef struct pmc_device_peak {
+  int64_t peak_live_units;   /* paper's unit count (Section 2.2)                               */
+  int64_t peak_live_bytes;   /* pool bytes: units * unit size                                  */
+  int64_t peak_tensor_bytes; /* bytes of tensors alive at pass boundaries (fp32 statistics die
+                                when B ends, the rest when W ends)                             */
+} pmc_device_peak;
+
+typedef struct pmc_replay_report {
+  double ms_total;          /* wall time of the replayed iteration on the stream               */
+  double ms_f, ms_b, ms_w;  /* summed per-pass times (only with PMC_REPLAY_TIME_PASSES)        */
+  int32_t passes;           /* number of chunk passes executed                                 */
+  int32_t devices;          /* d                                                               */
+  int64_t transit_peak_bytes; /* inter-chunk activation/gradient buffers in flight (workspace) */
+} pmc_replay_report;
+
+#define PMC_REPLAY_TIME_PASSES 1u
+
+const char* pmc_last_error(void);
+
+/* ---- context, pool, workspace --------------------------------------------------------------- */
+
+/* Creates a context bound to `hip_stream` (a hipStream_t, borrowed; NULL = default stream) on
+ * the current device.  Host-only call. */
+int pmc_create(void* hip_stream, pmc_ctx** out);
+void pmc_destroy(pmc_ctx* ctx);
+
+/* Attaches the activation pool: `arena` (device, >= 256-byte aligned, borrowed) of `bytes` bytes is
+ * cut into slabs of `slab_bytes` (rounded up to 256).  One slab holds everything one
+ * (chunk, microbatch) keeps between its F and its W (Section 2.2's activation unit, Section 3.1's
+ * m).  Fails with PMC_ERR_STATE if slabs are in use. */
+int pmc_pool_attach(pmc_ctx* ctx, void* arena, size_t bytes, size_t slab_bytes);
+/* Slabs in use / high-water mark since attach (or since the last pmc_pool_reset_peak). */
+int64_t pmc_pool_live_slabs(const pmc_ctx* ctx);
+int64_t pmc_pool_peak_slabs(const pmc_ctx* ctx);
+void pmc_pool_reset_peak(pmc_ctx* ctx);
+
+/* Attaches scratch memory (device, 256-byte aligned, borrowed) used for transient tensors inside
+ * a pass and for the replayer's inter-chunk buffers.  Contents are undefined between calls. */
+int pmc_workspace_attach(pmc_ctx* ctx, void* workspace, size_t bytes);
+
+/* ---- chunks ------------------------------------------------------------------------------- */
+
+/* m: bytes one (chunk, microbatch) unit holds from F to W: per layer 16 [tokens, hidden] tensors of
+ * the storage type plus fp32 statistics (4 + heads values per token).  Returns 0 on a bad cfg. */
+size_t pmc_activation_bytes(const pmc_chunk_cfg* cfg);
+/* The fp32-statistics part of the above (dead once B has run). */
+size_t pmc_activation_stats_bytes(const pmc_chunk_cfg* cfg);
+/* Scratch bytes one pass of such a chunk needs in the workspace. */
+size_t pmc_pass_workspace_bytes(const pmc_chunk_cfg* cfg);
+
+/* Creates a chunk of cfg->layers identical layers.  Constraints: hidden % heads == 0, head size
+ * 64 or 128 in bf16 mode (any multiple of 4 up to 128 in fp32 mode), hidden, ffn multiples of 64
+ * in bf16 mode.  Host-only call. */
+int pmc_chunk_create(pmc_ctx* ctx, const pmc_chunk_cfg* cfg, pmc_chunk** out);
+void pmc_chunk_destroy(pmc_chunk* chunk);
+/* Binds parameters and gradient accumulators: arrays of layers * PMC_PARAMS_PER_LAYER device
+ * pointers (params in the storage type, grads fp32), both borrowed until the chunk is destroyed. */
+int pmc_chunk_bind(pmc_chunk* chunk, const void* const* params, void* const* grads_fp32);
+
+/* F (Section 2.1): y = chunk(x) for microbatch id `mb`; takes one slab from the pool at its start.
+ * x, y: device, [tokens, hidden], storage type.  PMC_ERR_STATE if `mb` is already live in this
+ * chunk, PMC_ERR_NOMEM if the pool has no free slab. */
+int stage_forward(pmc_chunk* chunk, int32_t mb, const void* x, void* y);
+/* As stage_forward, but the caller names the simulated device the slab is charged to. */
+int stage_forward_on(pmc_chunk* chunk, int32_t mb, const void* x, void* y, int32_t device);
+
+/* B (Section 2.1): dx = d loss / d x given dy = d loss / d y, for a microbatch whose F has run.
+ * Adds the LayerNorm gain/bias gradients into the bound accumulators and leaves in the slab what
+ * W needs.  PMC_ERR_STATE if F has not run or B already has. */
+int stage_backward_input(pmc_chunk* chunk, int32_t mb, const void* dy, void* dx);
+
+/* W (Section 2.1): adds the weight and bias gradients of the `count` listed microbatches (each
+ * must have had its B) into the bound fp32 accumulators, in list order, and returns their slabs
+ * to the pool.  count > 1 is the deferred, queued case. */
+int stage_backward_weight(pmc_chunk* chunk, const int32_t* mbs, int32_t count);
+
+/* ---- schedules (host only; no GPU needed) --------------------------------------------------- */
+
+/* Builds the pass orders of `kind` for d devices and n microbatches by laying out the building
+ * block (Table 1 offsets; Appendix F same-device offsets; V-ZB's same-device offsets, which the
+ * paper finds by brute force and does not print, are (1,1,1)), checking that it repeats every 6
+ * cells without collision (Section 2.3) and repeating it n times (Section 2).  d >= 1, n >= 1. */
+int pmc_schedule_build(int32_t kind, int32_t d, int32_t n, pmc_schedule** out);
+/* As above for an arbitrary V-shape block: cross-device offsets delta0, delta1 (Section 3.1) and
+ * the three same-device offsets (F turn on the last device, F->B turn on the first device, B turn
+ * on the last device).  PMC_ERR_ILLEGAL_BLOCK if it collides. */
+int pmc_schedule_build_vshape(int32_t d, int32_t n, int32_t delta0, int32_t delta1, int32_t turn_f,
+                              int32_t turn_fb, int32_t turn_b, pmc_schedule** out);
+void pmc_schedule_destroy(pmc_schedule* s);
+int32_t pmc_schedule_devices(const pmc_schedule* s);
+int32_t pmc_schedule_microbatches(const pmc_schedule* s);
+int32_t pmc_schedule_num_passes(const pmc_schedule* s); /* 6 * n * d */
+/* Cell index of each pass of microbatch 0: out[6][d] in the row order F0, F1, B1, B0, W1, W0. */
+int pmc_schedule_block(const pmc_schedule* s, int32_t* out, int32_t capacity);
+/* One device's order (6n passes), sorted by cell; squeezing keeps this order (Section 2). */
+int pmc_schedule_device_order(const pmc_schedule* s, int32_t device, pmc_pass* out, int32_t capacity);
+/* The one-stream replay order: all passes by (cell, device). */
+int pmc_schedule_global_order(const pmc_schedule* s, pmc_pass* out, int32_t capacity);
+/* Lifetime accounting without running anything (Section 2.2): out[d]. */
+int pmc_schedule_account(const pmc_schedule* s, int64_t unit_bytes, int64_t stats_bytes,
+                         pmc_device_peak* out, int32_t capacity);
+/* Finish time when every device runs its order as early as dependencies allow, with the given
+ * pass durations (Section 2 "squeezing"; Appendix E). */
+int pmc_schedule_makespan(const pmc_schedule* s, double t_f, double t_b, double t_w, double* out);
+
+/* ---- replay ---------------------------------------------------------------------------------- */
+
+/* Workspace bytes schedule_replay needs for chunks of this shape (pass scratch + the largest
+ * number of inter-chunk buffers the order ever has in flight). */
+size_t pmc_replay_workspace_bytes(const pmc_schedule* s, const pmc_chunk_cfg* cfg);
+
+/* Runs one training iteration of the schedule on the context's stream: every pass of the global
+ * order, chunk by chunk, with activations handed from chunk to chunk through workspace buffers.
+ *   chunks     2d chunks in model order, all of one shape, bound to their parameters
+ *   x          n device pointers: input of model chunk 0 per microbatch
+ *   dy_last    n device pointers: gradient w.r.t. the last chunk's output per microbatch
+ *   y_last     n device pointers or NULL: receives the last chunk's output
+ *   dx_first   n device pointers or NULL: receives the gradient w.r.t. x
+ *   peaks      d entries: per simulated device, measured from the pool's own alloc/free calls
+ * Synchronises the stream before returning.  A 1F1B stage takes both its chunks' slabs when its F
+ * starts and returns them when its fused backward ends. */
+int schedule_replay(pmc_ctx* ctx, const pmc_schedule* s, pmc_chunk* const* chunks,
+                    const void* const* x, const void* const* dy_last, void* const* y_last,
+                    void* const* dx_first, uint32_t flags, pmc_replay_report* report,
+                    pmc_device_peak* peaks, int32_t peaks_capacity);
+
+/* ---- single operations (unit parity tests and kernel timing) --------------------------------- */
+
+typedef enum pmc_epilogue {
+  PMC_EPI_NONE = 0,        /* C = A.B                                                         */
+  PMC_EPI_BIAS = 1,        /* C = A.B + bias[n]                                               */
+  PMC_EPI_BIAS_RESID = 2,  /* C = A.B + bias[n] + resid[m,n]                                  */
+  PMC_EPI_BIAS_GELU = 3,   /* C = A.B + bias[n]; aux = gelu(C)                                */
+  PMC_EPI_DGELU = 4,       /* C = (A.B) * gelu'(aux[m,n])  (C may alias aux)                  */
+  PMC_EPI_ACCUM_F32 = 5    /* C(fp32) += A.B                                                  */
+} pmc_epilogue;
+
+/* C[M,N] = op(A)[M,K] . op(B)[K,N] with the epilogue above.  trans_a = 0: A stored [M,K]
+ * (row pitch lda); 1: stored [K,M].  trans_b = 0: B stored [K,N]; 1: stored [N,K].  All device.
+ * bf16 mode needs M, N, K multiples of 64 and pitches multiples of 8. */
+int pmc_gemm(pmc_ctx* ctx, int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32_t N,
+             int32_t K, const void* A, int32_t lda, const void* B, int32_t ldb, void* C, int32_t ldc,
+             int32_t epilogue, const void* bias, const void* resid, void* aux);
+
+/* y = LayerNorm(x) over rows of length h; mean and rstd are fp32 [rows]. x_copy may be NULL. */
+int pmc_layernorm_forward(pmc_ctx* ctx, int32_t dtype, int32_t rows, int32_t h, const void* x,
+                          const void* gain, const void* bias, float eps, void* y, float* mean,
+                          float* rstd, void* x_copy);
+/* dx = resid + LayerNorm input-gradient of dy; dgain/dbias (fp32 [h]) are accumulated into.
+ * Needs 2 * h * 4 * ceil(rows / 32) bytes ... of workspace. dx may alias x. */
+int pmc_layernorm_backward(pmc_ctx* ctx, int32_t dtype, int32_t rows, int32_t h, const void* dy,
+                           const void* x, const void* gain, const float* mean, const float* rstd,
+                           const void* resid, void* dx, float* dgain, float* dbias);
+/* Fused attention on packed qkv [batch*seq, 3h]: o [batch*seq, h], lse fp32 [batch, heads, seq]. */
+int pmc_attention_forward(pmc_ctx* ctx, int32_t dtype, int32_t batch, int32_t seq, int32_t heads,
+                          int32_t head_dim, int32_t causal, const void* qkv, void* o, float* lse);
+/* dqkv (same layout as qkv; may alias qkv) from d_o; uses the workspace. */
+int pmc_attention_backward(pmc_ctx* ctx, int32_t dtype, int32_t batch, int32_t seq, int32_t heads,
+                           int32_t head_dim, int32_t causal, const void* qkv, const void* o,
+                           const float* lse, const void* d_o, void* dqkv);
+/* out[n] += column sums of a [rows, n] (fp32 out). */
+int pmc_column_sum(pmc_ctx* ctx, int32_t dtype, int32_t rows, int32_t n, const void* a, int32_t lda,
+                   float* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PMC_H */

@@ -218,14 +218,16 @@ def accumulate(grads, *parts):
                 gl[k] += v
 
 
-def chunk_activation_bytes(layers, hidden, heads, seq, elem_bytes, microbatch=1):
+def chunk_activation_bytes(layers, hidden, heads, seq, elem_bytes, microbatch=1, ffn=None):
     """Bytes of activation one (chunk, microbatch) unit holds from F until W, by tensor:
-    x, LN1 out, qkv (3), attention out, x_mid, LN2 out, u (4), g (4) = 16 [s, h] tensors in the
-    storage type, plus fp32 LayerNorm statistics (2 + 2 per row) and the attention log-sum-exp
-    (heads per row).  After B the nine tensors x, qkv, x_mid, u are replaced one for one by the
-    nine gradient tensors W needs (dx_out, d qkv, dx_mid, du), so the count stays 16."""
+    x, LN1 out, qkv (3), attention out, x_mid, LN2 out (8 [tokens, hidden] tensors) and u, g
+    (2 [tokens, ffn] tensors; with ffn = 4 hidden that is 16 [tokens, hidden] in all) in the storage
+    type, plus fp32 LayerNorm statistics (2 + 2 per token) and the attention log-sum-exp (heads per
+    token).  After B the tensors x, qkv, x_mid, u are replaced one for one by the gradient tensors
+    W needs (dx_out, d qkv, dx_mid, du), so the count stays the same."""
     tokens = seq * microbatch
-    return layers * (16 * tokens * hidden * elem_bytes + (4 + heads) * tokens * 4)
+    ffn = 4 * hidden if ffn is None else ffn
+    return layers * ((8 * hidden + 2 * ffn) * tokens * elem_bytes + (4 + heads) * tokens * 4)
 
 
 def chunk_stats_bytes(layers, heads, seq, microbatch=1):

@@ -1,0 +1,553 @@
+// Host side of the library: context, activation pool, workspace, chunks and the three passes
+// F / B / W of a chunk (paper Section 2.1), plus the single-operation entry points.
+//
+// What one (chunk, microbatch) keeps between its F and its W lives in ONE slab of the pool
+// (Section 2.2: allocated when F starts, retained until B and W have both consumed it).  Per
+// layer the slab holds, in the storage type,
+//     X  A  QKV  O  XMID  C  U  G        (h, h, 3h, h, h, h, ffn, ffn columns)
+// and after all layers the fp32 statistics (LayerNorm mean/rstd twice, attention log-sum-exp).
+// B overwrites what only it needs with what W needs, one for one:
+//     U <- dU (GeLU' epilogue, in place),  XMID <- dX_mid,  QKV <- dQKV,
+//     X[l+1] <- dX of layer l+1 (= dX_out of layer l),  X[0] <- dY of the chunk,
+// so the slab never grows.  Tensors that exist only inside B (dC, dO, dA, the dQ staging buffer,
+// partial sums) live in the workspace.
+#include <algorithm>
+#include <cstring>
+#include <set>
+
+#include "kernels.h"
+
+namespace pmc {
+
+namespace {
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+}  // namespace
+
+struct Pool {
+  char* base = nullptr;
+  size_t slab_bytes = 0;
+  int64_t slabs = 0;
+  std::set<int64_t> free_list;  // lowest index first: placement is deterministic
+  int64_t live = 0, peak = 0;
+  struct Dev {
+    int64_t units = 0, peak_units = 0, tensor_bytes = 0, peak_tensor_bytes = 0;
+  };
+  std::map<int, Dev> dev;
+
+  void* take(int device, int64_t unit_bytes) {
+    if (free_list.empty()) return nullptr;
+    int64_t i = *free_list.begin();
+    free_list.erase(free_list.begin());
+    ++live;
+    peak = std::max(peak, live);
+    Dev& d = dev[device];
+    d.units += 1;
+    d.tensor_bytes += unit_bytes;
+    d.peak_units = std::max(d.peak_units, d.units);
+    d.peak_tensor_bytes = std::max(d.peak_tensor_bytes, d.tensor_bytes);
+    return base + (size_t)i * slab_bytes;
+  }
+  void shrink(int device, int64_t bytes) { dev[device].tensor_bytes -= bytes; }
+  void give(void* p, int device, int64_t remaining_bytes) {
+    free_list.insert(((char*)p - base) / (int64_t)slab_bytes);
+    --live;
+    Dev& d = dev[device];
+    d.units -= 1;
+    d.tensor_bytes -= remaining_bytes;
+  }
+  void reset_peaks() {
+    peak = live;
+    for (auto& kv : dev) {
+      kv.second.peak_units = kv.second.units;
+      kv.second.peak_tensor_bytes = kv.second.tensor_bytes;
+    }
+  }
+};
+
+}  // namespace pmc
+
+struct pmc_ctx {
+  hipStream_t stream = nullptr;
+  pmc::Pool pool;
+  char* ws = nullptr;
+  size_t ws_bytes = 0;
+  int chunks_alive = 0;
+};
+
+namespace pmc {
+
+enum MbState { kReserved = 0, kForwardDone = 1, kBackwardDone = 2 };
+
+struct Micro {
+  char* slab = nullptr;
+  int state = kReserved;
+  int device = 0;
+};
+
+struct LayerOffsets {  // byte offsets inside the slab
+  size_t x, a, qkv, o, xmid, c, u, g;
+  size_t mean1, rstd1, mean2, rstd2, lse;
+};
+
+struct WorkspaceLayout {
+  size_t t_h, attn, partial, total;
+};
+
+}  // namespace pmc
+
+struct pmc_chunk {
+  pmc_ctx* ctx = nullptr;
+  pmc_chunk_cfg cfg{};
+  int tokens = 0, head_dim = 0;
+  size_t esz = 0;
+  size_t unit_bytes = 0, stats_bytes = 0;
+  std::vector<pmc::LayerOffsets> off;
+  pmc::WorkspaceLayout wsl{};
+  std::vector<const void*> params;
+  std::vector<float*> grads;
+  bool bound = false;
+  std::map<int32_t, pmc::Micro> live;
+};
+
+namespace pmc {
+namespace {
+
+int check_cfg(const pmc_chunk_cfg* c) {
+  if (!c) return fail(PMC_ERR_INVALID, "cfg is NULL");
+  if (c->layers < 1 || c->hidden < 1 || c->heads < 1 || c->ffn < 1 || c->seq < 1 || c->microbatch < 1)
+    return fail(PMC_ERR_INVALID, "cfg: all sizes must be positive");
+  if (c->dtype != PMC_F32 && c->dtype != PMC_BF16) return fail(PMC_ERR_INVALID, "cfg: dtype %d", c->dtype);
+  if (c->hidden % c->heads) return fail(PMC_ERR_INVALID, "cfg: hidden %d not divisible by heads %d", c->hidden, c->heads);
+  const int dh = c->hidden / c->heads;
+  const int64_t tokens = (int64_t)c->seq * c->microbatch;
+  if (tokens > (1 << 24)) return fail(PMC_ERR_INVALID, "cfg: too many tokens");
+  if (c->dtype == PMC_BF16) {
+    if (c->hidden % 8 || c->ffn % 8 || tokens % 8)
+      return fail(PMC_ERR_INVALID, "cfg: bf16 mode needs hidden, ffn and tokens to be multiples of 8");
+    if (dh > 128) return fail(PMC_ERR_INVALID, "cfg: head size %d > 128", dh);
+  } else {
+    if (c->hidden % 4 || c->ffn % 4 || tokens % 4)
+      return fail(PMC_ERR_INVALID, "cfg: fp32 mode needs hidden, ffn and tokens to be multiples of 4");
+    if (dh > 128) return fail(PMC_ERR_INVALID, "cfg: head size %d > 128", dh);
+  }
+  if (!(c->ln_eps >= 0.f)) return fail(PMC_ERR_INVALID, "cfg: ln_eps must be >= 0");
+  return PMC_OK;
+}
+
+size_t esize(const pmc_chunk_cfg& c) { return c.dtype == PMC_F32 ? 4 : 2; }
+
+size_t unit_bytes_of(const pmc_chunk_cfg& c) {
+  const size_t t = (size_t)c.seq * c.microbatch;
+  return (size_t)c.layers * ((size_t)(8 * (size_t)c.hidden + 2 * (size_t)c.ffn) * t * esize(c) + (size_t)(4 + c.heads) * t * 4);
+}
+size_t stats_bytes_of(const pmc_chunk_cfg& c) {
+  return (size_t)c.layers * (size_t)(4 + c.heads) * c.seq * c.microbatch * 4;
+}
+
+WorkspaceLayout workspace_of(const pmc_chunk_cfg& c) {
+  const int t = c.seq * c.microbatch;
+  const size_t e = esize(c);
+  WorkspaceLayout w;
+  size_t at = 0;
+  w.t_h = at;
+  at += align256((size_t)t * c.hidden * e);
+  w.attn = at;
+  at += k::attention_backward_scratch_bytes(c.dtype, c.microbatch, c.seq, c.heads, c.hidden / c.heads);
+  w.partial = at;
+  const int widest = std::max(3 * c.hidden, c.ffn);
+  const size_t pf = std::max(k::layernorm_backward_scratch_floats(t, c.hidden), k::column_sum_scratch_floats(t, widest));
+  at += align256(pf * sizeof(float));
+  w.total = at;
+  return w;
+}
+
+#define PMC_TRY(expr)          \
+  do {                         \
+    int rc_ = (expr);          \
+    if (rc_ != PMC_OK) return rc_; \
+  } while (0)
+
+const void* P(const pmc_chunk* ch, int layer, int idx) { return ch->params[(size_t)layer * PMC_PARAMS_PER_LAYER + idx]; }
+float* G(const pmc_chunk* ch, int layer, int idx) { return ch->grads[(size_t)layer * PMC_PARAMS_PER_LAYER + idx]; }
+enum { LN1_G, LN1_B, W_QKV, B_QKV, W_O, B_O, LN2_G, LN2_B, W_1, B_1, W_2, B_2 };
+
+int ready(const pmc_chunk* ch, const char* what) {
+  if (!ch) return fail(PMC_ERR_INVALID, "%s: chunk is NULL", what);
+  if (!ch->bound) return fail(PMC_ERR_STATE, "%s: parameters are not bound", what);
+  const pmc_ctx* ctx = ch->ctx;
+  if (!ctx->pool.base) return fail(PMC_ERR_STATE, "%s: no activation pool attached", what);
+  if (ctx->pool.slab_bytes < ch->unit_bytes)
+    return fail(PMC_ERR_NOMEM, "%s: pool slabs of %zu bytes cannot hold a unit of %zu bytes", what, ctx->pool.slab_bytes,
+                ch->unit_bytes);
+  if (!ctx->ws || ctx->ws_bytes < ch->wsl.total)
+    return fail(PMC_ERR_NOMEM, "%s: workspace of %zu bytes, pass needs %zu", what, ctx->ws_bytes, ch->wsl.total);
+  return PMC_OK;
+}
+
+k::GemmArgs gemm_args(const pmc_chunk* ch, bool ta, bool tb, int M, int N, int K, const void* A, int lda, const void* B,
+                      int ldb, void* C, int ldc, int epi, const void* bias = nullptr, const void* resid = nullptr,
+                      void* aux = nullptr) {
+  k::GemmArgs g;
+  g.dtype = ch->cfg.dtype;
+  g.trans_a = ta; g.trans_b = tb;
+  g.M = M; g.N = N; g.K = K;
+  g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc;
+  g.epilogue = epi; g.bias = bias; g.resid = resid; g.aux = aux;
+  return g;
+}
+
+}  // namespace
+
+// Takes the slab for (chunk, mb) without running anything (1F1B: a stage takes both its chunks'
+// units when its F starts).
+int chunk_reserve(pmc_chunk* ch, int32_t mb, int device) {
+  PMC_TRY(ready(ch, "reserve"));
+  if (ch->live.count(mb)) return fail(PMC_ERR_STATE, "microbatch %d is already live in this chunk", mb);
+  void* slab = ch->ctx->pool.take(device, (int64_t)ch->unit_bytes);
+  if (!slab) return fail(PMC_ERR_NOMEM, "activation pool exhausted (%lld slabs in use)", (long long)ch->ctx->pool.live);
+  Micro m;
+  m.slab = (char*)slab;
+  m.state = kReserved;
+  m.device = device;
+  ch->live[mb] = m;
+  return PMC_OK;
+}
+
+int chunk_forward(pmc_chunk* ch, int32_t mb, const void* x, void* y, int device) {
+  PMC_TRY(ready(ch, "stage_forward"));
+  if (!x || !y) return fail(PMC_ERR_INVALID, "stage_forward: NULL tensor");
+  auto it = ch->live.find(mb);
+  if (it != ch->live.end() && it->second.state != kReserved)
+    return fail(PMC_ERR_STATE, "stage_forward: microbatch %d is already live in this chunk", mb);
+  if (it == ch->live.end()) {
+    PMC_TRY(chunk_reserve(ch, mb, device));
+    it = ch->live.find(mb);
+  }
+  Micro& m = it->second;
+  const pmc_chunk_cfg& c = ch->cfg;
+  hipStream_t st = ch->ctx->stream;
+  const int T = ch->tokens, h = c.hidden, f = c.ffn, L = c.layers;
+  for (int l = 0; l < L; ++l) {
+    const LayerOffsets& o = ch->off[l];
+    char* s = m.slab;
+    const void* xin = l == 0 ? x : (const void*)(s + o.x);
+    PMC_TRY(k::layernorm_forward(st, c.dtype, T, h, xin, P(ch, l, LN1_G), P(ch, l, LN1_B), c.ln_eps, s + o.a,
+                                 (float*)(s + o.mean1), (float*)(s + o.rstd1), l == 0 ? s + o.x : nullptr));
+    PMC_TRY(k::gemm(st, gemm_args(ch, false, false, T, 3 * h, h, s + o.a, h, P(ch, l, W_QKV), 3 * h, s + o.qkv, 3 * h,
+                                  PMC_EPI_BIAS, P(ch, l, B_QKV))));
+    PMC_TRY(k::attention_forward(st, c.dtype, c.microbatch, c.seq, c.heads, ch->head_dim, c.causal, s + o.qkv, s + o.o,
+                                 (float*)(s + o.lse)));
+    PMC_TRY(k::gemm(st, gemm_args(ch, false, false, T, h, h, s + o.o, h, P(ch, l, W_O), h, s + o.xmid, h,
+                                  PMC_EPI_BIAS_RESID, P(ch, l, B_O), s + o.x)));
+    PMC_TRY(k::layernorm_forward(st, c.dtype, T, h, s + o.xmid, P(ch, l, LN2_G), P(ch, l, LN2_B), c.ln_eps, s + o.c,
+                                 (float*)(s + o.mean2), (float*)(s + o.rstd2), nullptr));
+    PMC_TRY(k::gemm(st, gemm_args(ch, false, false, T, f, h, s + o.c, h, P(ch, l, W_1), f, s + o.u, f, PMC_EPI_BIAS_GELU,
+                                  P(ch, l, B_1), nullptr, s + o.g)));
+    void* out = l == L - 1 ? y : (void*)(s + ch->off[l + 1].x);
+    PMC_TRY(k::gemm(st, gemm_args(ch, false, false, T, h, f, s + o.g, f, P(ch, l, W_2), h, out, h, PMC_EPI_BIAS_RESID,
+                                  P(ch, l, B_2), s + o.xmid)));
+  }
+  m.state = kForwardDone;
+  return PMC_OK;
+}
+
+int chunk_backward_input(pmc_chunk* ch, int32_t mb, const void* dy, void* dx) {
+  PMC_TRY(ready(ch, "stage_backward_input"));
+  if (!dy || !dx) return fail(PMC_ERR_INVALID, "stage_backward_input: NULL tensor");
+  auto it = ch->live.find(mb);
+  if (it == ch->live.end() || it->second.state == kReserved)
+    return fail(PMC_ERR_STATE, "stage_backward_input: microbatch %d has no forward pass in this chunk", mb);
+  if (it->second.state != kForwardDone)
+    return fail(PMC_ERR_STATE, "stage_backward_input: microbatch %d already had its backward pass", mb);
+  Micro& m = it->second;
+  const pmc_chunk_cfg& c = ch->cfg;
+  hipStream_t st = ch->ctx->stream;
+  const int T = ch->tokens, h = c.hidden, f = c.ffn, L = c.layers;
+  char* s = m.slab;
+  char* ws = ch->ctx->ws;
+  void* t_h = ws + ch->wsl.t_h;
+  void* attn_ws = ws + ch->wsl.attn;
+  float* partial = (float*)(ws + ch->wsl.partial);
+  for (int l = L - 1; l >= 0; --l) {
+    const LayerOffsets& o = ch->off[l];
+    const void* dyl = l == L - 1 ? dy : (const void*)(s + ch->off[l + 1].x);
+    // dU = (dY . W2^T) * gelu'(U), written over U
+    PMC_TRY(k::gemm(st, gemm_args(ch, false, true, T, f, h, dyl, h, P(ch, l, W_2), h, s + o.u, f, PMC_EPI_DGELU, nullptr,
+                                  nullptr, s + o.u)));
+    // dC = dU . W1^T
+    PMC_TRY(k::gemm(st, gemm_args(ch, false, true, T, h, f, s + o.u, f, P(ch, l, W_1), f, t_h, h, PMC_EPI_NONE)));
+    // dX_mid = dY + LN2 input-gradient(dC), written over X_mid; LN2 gain/bias gradients
+    PMC_TRY(k::layernorm_backward(st, c.dtype, T, h, t_h, s + o.xmid, P(ch, l, LN2_G), (const float*)(s + o.mean2),
+                                  (const float*)(s + o.rstd2), dyl, s + o.xmid, G(ch, l, LN2_G), G(ch, l, LN2_B), partial));
+    // dO = dX_mid . Wo^T
+    PMC_TRY(k::gemm(st, gemm_args(ch, false, true, T, h, h, s + o.xmid, h, P(ch, l, W_O), h, t_h, h, PMC_EPI_NONE)));
+    // dQKV, written over QKV
+    PMC_TRY(k::attention_backward(st, c.dtype, c.microbatch, c.seq, c.heads, ch->head_dim, c.causal, s + o.qkv, s + o.o,
+                                  (const float*)(s + o.lse), t_h, s + o.qkv, attn_ws));
+    // dA = dQKV . Wqkv^T
+    PMC_TRY(k::gemm(st, gemm_args(ch, false, true, T, h, 3 * h, s + o.qkv, 3 * h, P(ch, l, W_QKV), 3 * h, t_h, h,
+                                  PMC_EPI_NONE)));
+    // dX = dX_mid + LN1 input-gradient(dA): over X for inner layers, to the caller for layer 0
+    void* out = l == 0 ? dx : (void*)(s + o.x);
+    PMC_TRY(k::layernorm_backward(st, c.dtype, T, h, t_h, s + o.x, P(ch, l, LN1_G), (const float*)(s + o.mean1),
+                                  (const float*)(s + o.rstd1), s + o.xmid, out, G(ch, l, LN1_G), G(ch, l, LN1_B), partial));
+  }
+  // keep the chunk's dY for W of the top layer in the slot of the (now dead) chunk input
+  PMC_TRY(k::copy_rows(st, c.dtype, T, h, dy, h, s + ch->off[0].x, h));
+  m.state = kBackwardDone;
+  ch->ctx->pool.shrink(m.device, (int64_t)ch->stats_bytes);
+  return PMC_OK;
+}
+
+int chunk_backward_weight_one(pmc_chunk* ch, int32_t mb, bool release) {
+  auto it = ch->live.find(mb);
+  if (it == ch->live.end() || it->second.state != kBackwardDone)
+    return fail(PMC_ERR_STATE, "stage_backward_weight: microbatch %d has not had its backward-input pass", mb);
+  Micro& m = it->second;
+  const pmc_chunk_cfg& c = ch->cfg;
+  hipStream_t st = ch->ctx->stream;
+  const int T = ch->tokens, h = c.hidden, f = c.ffn, L = c.layers;
+  char* s = m.slab;
+  float* partial = (float*)(ch->ctx->ws + ch->wsl.partial);
+  for (int l = L - 1; l >= 0; --l) {
+    const LayerOffsets& o = ch->off[l];
+    const void* dxout = s + (l == L - 1 ? ch->off[0].x : ch->off[l + 1].x);
+    PMC_TRY(k::gemm(st, gemm_args(ch, true, false, f, h, T, s + o.g, f, dxout, h, G(ch, l, W_2), h, PMC_EPI_ACCUM_F32)));
+    PMC_TRY(k::column_sum(st, c.dtype, T, h, dxout, h, G(ch, l, B_2), partial));
+    PMC_TRY(k::gemm(st, gemm_args(ch, true, false, h, f, T, s + o.c, h, s + o.u, f, G(ch, l, W_1), f, PMC_EPI_ACCUM_F32)));
+    PMC_TRY(k::column_sum(st, c.dtype, T, f, s + o.u, f, G(ch, l, B_1), partial));
+    PMC_TRY(k::gemm(st, gemm_args(ch, true, false, h, h, T, s + o.o, h, s + o.xmid, h, G(ch, l, W_O), h, PMC_EPI_ACCUM_F32)));
+    PMC_TRY(k::column_sum(st, c.dtype, T, h, s + o.xmid, h, G(ch, l, B_O), partial));
+    PMC_TRY(k::gemm(st, gemm_args(ch, true, false, h, 3 * h, T, s + o.a, h, s + o.qkv, 3 * h, G(ch, l, W_QKV), 3 * h,
+                                  PMC_EPI_ACCUM_F32)));
+    PMC_TRY(k::column_sum(st, c.dtype, T, 3 * h, s + o.qkv, 3 * h, G(ch, l, B_QKV), partial));
+  }
+  if (release) {
+    ch->ctx->pool.give(m.slab, m.device, (int64_t)(ch->unit_bytes - ch->stats_bytes));
+    ch->live.erase(it);
+  }
+  return PMC_OK;
+}
+
+// Returns a slab whose W has run with release = false.
+int chunk_release(pmc_chunk* ch, int32_t mb) {
+  auto it = ch->live.find(mb);
+  if (it == ch->live.end()) return fail(PMC_ERR_STATE, "release: microbatch %d is not live", mb);
+  Micro& m = it->second;
+  const int64_t rest = m.state == kBackwardDone ? (int64_t)(ch->unit_bytes - ch->stats_bytes) : (int64_t)ch->unit_bytes;
+  ch->ctx->pool.give(m.slab, m.device, rest);
+  ch->live.erase(it);
+  return PMC_OK;
+}
+
+size_t chunk_unit_bytes(const pmc_chunk* ch) { return ch->unit_bytes; }
+size_t chunk_stats_bytes(const pmc_chunk* ch) { return ch->stats_bytes; }
+size_t chunk_workspace_bytes(const pmc_chunk* ch) { return ch->wsl.total; }
+pmc_ctx* chunk_ctx(const pmc_chunk* ch) { return ch->ctx; }
+const pmc_chunk_cfg& chunk_cfg(const pmc_chunk* ch) { return ch->cfg; }
+hipStream_t ctx_stream(const pmc_ctx* ctx) { return ctx->stream; }
+char* ctx_workspace(const pmc_ctx* ctx, size_t* bytes) {
+  *bytes = ctx->ws_bytes;
+  return ctx->ws;
+}
+void ctx_device_peaks(pmc_ctx* ctx, int d, int64_t unit_bytes, pmc_device_peak* out) {
+  for (int i = 0; i < d; ++i) {
+    const Pool::Dev& dv = ctx->pool.dev[i];
+    out[i].peak_live_units = dv.peak_units;
+    out[i].peak_live_bytes = dv.peak_units * unit_bytes;
+    out[i].peak_tensor_bytes = dv.peak_tensor_bytes;
+  }
+}
+
+}  // namespace pmc
+
+using namespace pmc;
+
+extern "C" {
+
+int pmc_create(void* hip_stream, pmc_ctx** out) {
+  if (!out) return fail(PMC_ERR_INVALID, "out is NULL");
+  auto* ctx = new (std::nothrow) pmc_ctx;
+  if (!ctx) return fail(PMC_ERR_NOMEM, "host allocation failed");
+  ctx->stream = (hipStream_t)hip_stream;
+  *out = ctx;
+  return PMC_OK;
+}
+
+void pmc_destroy(pmc_ctx* ctx) { delete ctx; }
+
+int pmc_pool_attach(pmc_ctx* ctx, void* arena, size_t bytes, size_t slab_bytes) {
+  if (!ctx || !arena) return fail(PMC_ERR_INVALID, "pool_attach: NULL argument");
+  if ((uintptr_t)arena & 255) return fail(PMC_ERR_INVALID, "pool_attach: arena must be 256-byte aligned");
+  if (slab_bytes == 0) return fail(PMC_ERR_INVALID, "pool_attach: slab_bytes is 0");
+  if (ctx->pool.live) return fail(PMC_ERR_STATE, "pool_attach: %lld slabs still in use", (long long)ctx->pool.live);
+  const size_t sb = align256(slab_bytes);
+  const int64_t n = (int64_t)(bytes / sb);
+  if (n < 1) return fail(PMC_ERR_NOMEM, "pool_attach: arena of %zu bytes holds no slab of %zu bytes", bytes, sb);
+  ctx->pool = Pool();
+  ctx->pool.base = (char*)arena;
+  ctx->pool.slab_bytes = sb;
+  ctx->pool.slabs = n;
+  for (int64_t i = 0; i < n; ++i) ctx->pool.free_list.insert(i);
+  return PMC_OK;
+}
+
+int64_t pmc_pool_live_slabs(const pmc_ctx* ctx) { return ctx ? ctx->pool.live : 0; }
+int64_t pmc_pool_peak_slabs(const pmc_ctx* ctx) { return ctx ? ctx->pool.peak : 0; }
+void pmc_pool_reset_peak(pmc_ctx* ctx) {
+  if (ctx) ctx->pool.reset_peaks();
+}
+
+int pmc_workspace_attach(pmc_ctx* ctx, void* workspace, size_t bytes) {
+  if (!ctx || !workspace) return fail(PMC_ERR_INVALID, "workspace_attach: NULL argument");
+  if ((uintptr_t)workspace & 255) return fail(PMC_ERR_INVALID, "workspace_attach: must be 256-byte aligned");
+  ctx->ws = (char*)workspace;
+  ctx->ws_bytes = bytes;
+  return PMC_OK;
+}
+
+size_t pmc_activation_bytes(const pmc_chunk_cfg* cfg) { return check_cfg(cfg) == PMC_OK ? unit_bytes_of(*cfg) : 0; }
+size_t pmc_activation_stats_bytes(const pmc_chunk_cfg* cfg) { return check_cfg(cfg) == PMC_OK ? stats_bytes_of(*cfg) : 0; }
+size_t pmc_pass_workspace_bytes(const pmc_chunk_cfg* cfg) { return check_cfg(cfg) == PMC_OK ? workspace_of(*cfg).total : 0; }
+
+int pmc_chunk_create(pmc_ctx* ctx, const pmc_chunk_cfg* cfg, pmc_chunk** out) {
+  if (!ctx || !out) return fail(PMC_ERR_INVALID, "chunk_create: NULL argument");
+  PMC_TRY(check_cfg(cfg));
+  auto* ch = new (std::nothrow) pmc_chunk;
+  if (!ch) return fail(PMC_ERR_NOMEM, "host allocation failed");
+  ch->ctx = ctx;
+  ch->cfg = *cfg;
+  ch->tokens = cfg->seq * cfg->microbatch;
+  ch->head_dim = cfg->hidden / cfg->heads;
+  ch->esz = esize(*cfg);
+  ch->unit_bytes = unit_bytes_of(*cfg);
+  ch->stats_bytes = stats_bytes_of(*cfg);
+  ch->wsl = workspace_of(*cfg);
+  const size_t th = (size_t)ch->tokens * cfg->hidden * ch->esz, tf = (size_t)ch->tokens * cfg->ffn * ch->esz;
+  const size_t per_layer = 8 * th + 2 * tf;
+  const size_t st_layer = (size_t)(4 + cfg->heads) * ch->tokens * 4;
+  const size_t stats0 = per_layer * cfg->layers;
+  ch->off.resize(cfg->layers);
+  for (int l = 0; l < cfg->layers; ++l) {
+    LayerOffsets& o = ch->off[l];
+    size_t at = per_layer * l;
+    o.x = at; at += th;
+    o.a = at; at += th;
+    o.qkv = at; at += 3 * th;
+    o.o = at; at += th;
+    o.xmid = at; at += th;
+    o.c = at; at += th;
+    o.u = at; at += tf;
+    o.g = at; at += tf;
+    size_t sa = stats0 + st_layer * l;
+    const size_t tb = (size_t)ch->tokens * 4;
+    o.mean1 = sa; sa += tb;
+    o.rstd1 = sa; sa += tb;
+    o.mean2 = sa; sa += tb;
+    o.rstd2 = sa; sa += tb;
+    o.lse = sa;
+  }
+  ++ctx->chunks_alive;
+  *out = ch;
+  return PMC_OK;
+}
+
+void pmc_chunk_destroy(pmc_chunk* ch) {
+  if (!ch) return;
+  for (auto& kv : ch->live) {
+    const int64_t rest = kv.second.state == kBackwardDone ? (int64_t)(ch->unit_bytes - ch->stats_bytes) : (int64_t)ch->unit_bytes;
+    ch->ctx->pool.give(kv.second.slab, kv.second.device, rest);
+  }
+  --ch->ctx->chunks_alive;
+  delete ch;
+}
+
+int pmc_chunk_bind(pmc_chunk* ch, const void* const* params, void* const* grads_fp32) {
+  if (!ch || !params || !grads_fp32) return fail(PMC_ERR_INVALID, "chunk_bind: NULL argument");
+  const size_t n = (size_t)ch->cfg.layers * PMC_PARAMS_PER_LAYER;
+  for (size_t i = 0; i < n; ++i) {
+    if (!params[i] || !grads_fp32[i]) return fail(PMC_ERR_INVALID, "chunk_bind: pointer %zu is NULL", i);
+    if (((uintptr_t)params[i] & 15) || ((uintptr_t)grads_fp32[i] & 15))
+      return fail(PMC_ERR_INVALID, "chunk_bind: pointer %zu is not 16-byte aligned", i);
+  }
+  ch->params.assign(params, params + n);
+  ch->grads.resize(n);
+  for (size_t i = 0; i < n; ++i) ch->grads[i] = (float*)grads_fp32[i];
+  ch->bound = true;
+  return PMC_OK;
+}
+
+int stage_forward(pmc_chunk* ch, int32_t mb, const void* x, void* y) { return chunk_forward(ch, mb, x, y, 0); }
+int stage_forward_on(pmc_chunk* ch, int32_t mb, const void* x, void* y, int32_t device) {
+  if (device < 0) return fail(PMC_ERR_INVALID, "stage_forward_on: device %d", device);
+  return chunk_forward(ch, mb, x, y, device);
+}
+int stage_backward_input(pmc_chunk* ch, int32_t mb, const void* dy, void* dx) { return chunk_backward_input(ch, mb, dy, dx); }
+
+int stage_backward_weight(pmc_chunk* ch, const int32_t* mbs, int32_t count) {
+  PMC_TRY(ready(ch, "stage_backward_weight"));
+  if (!mbs || count < 1) return fail(PMC_ERR_INVALID, "stage_backward_weight: empty list");
+  for (int32_t i = 0; i < count; ++i) {
+    auto it = ch->live.find(mbs[i]);
+    if (it == ch->live.end() || it->second.state != kBackwardDone)
+      return fail(PMC_ERR_STATE, "stage_backward_weight: microbatch %d has not had its backward-input pass", mbs[i]);
+    for (int32_t j = 0; j < i; ++j)
+      if (mbs[j] == mbs[i]) return fail(PMC_ERR_INVALID, "stage_backward_weight: microbatch %d listed twice", mbs[i]);
+  }
+  for (int32_t i = 0; i < count; ++i) PMC_TRY(chunk_backward_weight_one(ch, mbs[i], true));
+  return PMC_OK;
+}
+
+/* ---- single operations ---- */
+
+int pmc_gemm(pmc_ctx* ctx, int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32_t N, int32_t K, const void* A,
+             int32_t lda, const void* B, int32_t ldb, void* C, int32_t ldc, int32_t epilogue, const void* bias,
+             const void* resid, void* aux) {
+  if (!ctx) return fail(PMC_ERR_INVALID, "ctx is NULL");
+  k::GemmArgs g;
+  g.dtype = dtype; g.trans_a = trans_a != 0; g.trans_b = trans_b != 0;
+  g.M = M; g.N = N; g.K = K; g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc;
+  g.epilogue = epilogue; g.bias = bias; g.resid = resid; g.aux = aux;
+  return k::gemm(ctx->stream, g);
+}
+
+int pmc_layernorm_forward(pmc_ctx* ctx, int32_t dtype, int32_t rows, int32_t h, const void* x, const void* gain,
+                          const void* bias, float eps, void* y, float* mean, float* rstd, void* x_copy) {
+  if (!ctx) return fail(PMC_ERR_INVALID, "ctx is NULL");
+  return k::layernorm_forward(ctx->stream, dtype, rows, h, x, gain, bias, eps, y, mean, rstd, x_copy);
+}
+
+int pmc_layernorm_backward(pmc_ctx* ctx, int32_t dtype, int32_t rows, int32_t h, const void* dy, const void* x,
+                           const void* gain, const float* mean, const float* rstd, const void* resid, void* dx,
+                           float* dgain, float* dbias) {
+  if (!ctx) return fail(PMC_ERR_INVALID, "ctx is NULL");
+  if (rows <= 0 || h <= 0) return fail(PMC_ERR_INVALID, "layernorm_backward: rows=%d h=%d", rows, h);
+  const size_t need = k::layernorm_backward_scratch_floats(rows, h) * sizeof(float);
+  if (!ctx->ws || ctx->ws_bytes < need) return fail(PMC_ERR_NOMEM, "layernorm_backward: workspace needs %zu bytes", need);
+  return k::layernorm_backward(ctx->stream, dtype, rows, h, dy, x, gain, mean, rstd, resid, dx, dgain, dbias, (float*)ctx->ws);
+}
+
+int pmc_attention_forward(pmc_ctx* ctx, int32_t dtype, int32_t batch, int32_t seq, int32_t heads, int32_t head_dim,
+                          int32_t causal, const void* qkv, void* o, float* lse) {
+  if (!ctx) return fail(PMC_ERR_INVALID, "ctx is NULL");
+  return k::attention_forward(ctx->stream, dtype, batch, seq, heads, head_dim, causal, qkv, o, lse);
+}
+
+int pmc_attention_backward(pmc_ctx* ctx, int32_t dtype, int32_t batch, int32_t seq, int32_t heads, int32_t head_dim,
+                           int32_t causal, const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv) {
+  if (!ctx) return fail(PMC_ERR_INVALID, "ctx is NULL");
+  if (batch <= 0 || seq <= 0 || heads <= 0 || head_dim <= 0) return fail(PMC_ERR_INVALID, "attention_backward: bad shape");
+  const size_t need = k::attention_backward_scratch_bytes(dtype, batch, seq, heads, head_dim);
+  if (!ctx->ws || ctx->ws_bytes < need) return fail(PMC_ERR_NOMEM, "attention_backward: workspace needs %zu bytes", need);
+  return k::attention_backward(ctx->stream, dtype, batch, seq, heads, head_dim, causal, qkv, o, lse, d_o, dqkv, ctx->ws);
+}
+
+int pmc_column_sum(pmc_ctx* ctx, int32_t dtype, int32_t rows, int32_t n, const void* a, int32_t lda, float* out) {
+  if (!ctx) return fail(PMC_ERR_INVALID, "ctx is NULL");
+  if (rows <= 0 || n <= 0) return fail(PMC_ERR_INVALID, "column_sum: rows=%d n=%d", rows, n);
+  const size_t need = k::column_sum_scratch_floats(rows, n) * sizeof(float);
+  if (!ctx->ws || ctx->ws_bytes < need) return fail(PMC_ERR_NOMEM, "column_sum: workspace needs %zu bytes", need);
+  return k::column_sum(ctx->stream, dtype, rows, n, a, lda, out, (float*)ctx->ws);
+}
+
+}  // extern "C"

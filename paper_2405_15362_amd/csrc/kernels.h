@@ -1,0 +1,53 @@
+// Host-callable launchers of the HIP kernels.  Every launcher validates what its kernel assumes
+// about shapes and alignment, enqueues on `stream` and returns a pmc_status.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "pmc_internal.h"
+
+namespace pmc {
+namespace k {
+
+struct GemmArgs {
+  int dtype = PMC_BF16;
+  bool trans_a = false, trans_b = false;
+  int M = 0, N = 0, K = 0;
+  const void* A = nullptr;
+  int lda = 0;
+  const void* B = nullptr;
+  int ldb = 0;
+  void* C = nullptr;
+  int ldc = 0;
+  int epilogue = PMC_EPI_NONE;
+  const void* bias = nullptr;   // [N], storage type
+  const void* resid = nullptr;  // [M, N], pitch ldc
+  void* aux = nullptr;          // [M, N], pitch ldc
+};
+
+int gemm(hipStream_t stream, const GemmArgs& a);
+int gemm_f32(hipStream_t stream, const GemmArgs& a);
+int gemm_bf16(hipStream_t stream, const GemmArgs& a);
+
+int layernorm_forward(hipStream_t stream, int dtype, int rows, int h, const void* x, const void* gain,
+                      const void* bias, float eps, void* y, float* mean, float* rstd, void* x_copy);
+// partial: fp32 scratch of layernorm_backward_scratch_floats(rows, h) floats.
+size_t layernorm_backward_scratch_floats(int rows, int h);
+int layernorm_backward(hipStream_t stream, int dtype, int rows, int h, const void* dy, const void* x,
+                       const void* gain, const float* mean, const float* rstd, const void* resid, void* dx,
+                       float* dgain, float* dbias, float* partial);
+
+int attention_forward(hipStream_t stream, int dtype, int batch, int seq, int heads, int head_dim, int causal,
+                      const void* qkv, void* o, float* lse);
+// scratch: dq staging [batch*seq, heads*head_dim] in the storage type, then delta fp32 [batch, heads, seq].
+size_t attention_backward_scratch_bytes(int dtype, int batch, int seq, int heads, int head_dim);
+int attention_backward(hipStream_t stream, int dtype, int batch, int seq, int heads, int head_dim, int causal,
+                       const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv,
+                       void* scratch);
+
+size_t column_sum_scratch_floats(int rows, int n);
+int column_sum(hipStream_t stream, int dtype, int rows, int n, const void* a, int lda, float* out, float* partial);
+
+int copy_rows(hipStream_t stream, int dtype, int rows, int cols, const void* src, int ld_src, void* dst, int ld_dst);
+
+}  // namespace k
+}  // namespace pmc

@@ -1,0 +1,30 @@
+// Internal declarations shared by the host-side translation units of the library.
+#pragma once
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <map>
+#include <string>
+#include <vector>
+
+#include "../../include/pmc.h"
+
+namespace pmc {
+
+// Records a message for pmc_last_error() and returns `code`.
+int fail(int code, const char* fmt, ...);
+
+struct Schedule {
+  int kind = -1;  // pmc_kind, or -1 for a custom V-shape block
+  int d = 0, n = 0;
+  bool grouped_bw = false;           // 1F1B: the stage is the unit of allocation
+  std::vector<int32_t> block;        // [6][d]: rows F0, F1, B1, B0, W1, W0
+  std::vector<pmc_pass> passes;      // all passes, global order
+  std::vector<std::vector<pmc_pass>> per_device;
+};
+
+}  // namespace pmc
+
+struct pmc_schedule {
+  pmc::Schedule s;
+};

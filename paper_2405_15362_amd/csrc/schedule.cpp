@@ -1,0 +1,309 @@
+// Host-only schedule generator: building blocks, repetition, pass orders, lifetime accounting
+// and the as-early-as-possible timing of a squeezed schedule.  No HIP in this file.
+//
+// Construction (paper Section 2): the passes of one microbatch are laid out on a device x time
+// grid; microbatch j's copy is shifted by j * T cells; a device's order is its passes sorted by
+// cell, which squeezing preserves.  T = 6: every device runs 2 F, 2 B and 2 W per microbatch
+// (Section 2.2: T equals the units of computation per stage of the block).
+#include <algorithm>
+#include <cstring>
+
+#include "pmc_internal.h"
+
+namespace pmc {
+namespace {
+
+constexpr int T = 6;
+enum Row { F0 = 0, F1 = 1, B1 = 2, B0 = 3, W1 = 4, W0 = 5 };
+const int kRowOp[6] = {PMC_F, PMC_F, PMC_B, PMC_B, PMC_W, PMC_W};
+const int kRowChunk[6] = {0, 1, 1, 0, 1, 0};
+
+// V-shape block (Section 3, 3.1): chunk 0 of device i is model chunk i, chunk 1 is 2d-1-i.
+// Forward runs down the devices with step delta0, turns on the last device, runs back up with
+// step delta1; the backward retraces it with the steps exchanged (Section 3.1's balance
+// constraint delta_F^0 = delta_B^1, delta_F^1 = delta_B^0).
+bool vshape_block(int d, int delta0, int delta1, int turn_f, int turn_fb, int turn_b,
+                  std::vector<int32_t>& blk) {
+  blk.assign(6 * d, 0);
+  auto at = [&](int row, int i) -> int32_t& { return blk[row * d + i]; };
+  for (int i = 0; i < d; ++i) at(F0, i) = i * delta0;
+  at(F1, d - 1) = at(F0, d - 1) + turn_f;
+  for (int i = d - 2; i >= 0; --i) at(F1, i) = at(F1, i + 1) + delta1;
+  at(B1, 0) = at(F1, 0) + turn_fb;
+  for (int i = 1; i < d; ++i) at(B1, i) = at(B1, i - 1) + delta0;
+  at(B0, d - 1) = at(B1, d - 1) + turn_b;
+  for (int i = d - 2; i >= 0; --i) at(B0, i) = at(B0, i + 1) + delta1;
+  for (int i = 0; i < d; ++i) {
+    bool used[T] = {false, false, false, false, false, false};
+    for (int row : {F0, F1, B1, B0}) {
+      int r = at(row, i) % T;
+      if (used[r]) return false;  // would collide when repeated every T cells (Section 2.3)
+      used[r] = true;
+    }
+    // W is placed greedily once F and B are settled (Section 3.1): in the order of the B passes,
+    // each W takes the first cell after its B that is free modulo T.
+    const int b_rows[2] = {B1, B0}, w_rows[2] = {W1, W0};
+    for (int k = 0; k < 2; ++k) {
+      int t = at(b_rows[k], i) + 1;
+      while (used[t % T]) ++t;
+      used[t % T] = true;
+      at(w_rows[k], i) = t;
+    }
+  }
+  return true;
+}
+
+// 1F1B at chunk granularity: a stage (two consecutive chunks) runs F of both chunks in two cells
+// and its fused backward in four (B, W of the upper chunk, then of the lower one).  Adjacent
+// stages' forwards are 2 cells apart, their backwards 4 (Table 1's delta0, delta1 for 1F1B).
+void one_f_one_b_block(int d, std::vector<int32_t>& blk) {
+  blk.assign(6 * d, 0);
+  for (int i = 0; i < d; ++i) {
+    int tf = 2 * i, tbw = 2 * d + 4 * (d - 1 - i);
+    blk[F0 * d + i] = tf;
+    blk[F1 * d + i] = tf + 1;
+    blk[B1 * d + i] = tbw;
+    blk[W1 * d + i] = tbw + 1;
+    blk[B0 * d + i] = tbw + 2;
+    blk[W0 * d + i] = tbw + 3;
+  }
+}
+
+int model_chunk(const Schedule& s, int device, int chunk) {
+  if (s.grouped_bw) return 2 * device + chunk;
+  return chunk == 0 ? device : 2 * s.d - 1 - device;
+}
+
+int finish(Schedule& s) {
+  const int d = s.d, n = s.n;
+  s.per_device.assign(d, {});
+  for (int i = 0; i < d; ++i) {
+    auto& v = s.per_device[i];
+    v.reserve(6 * n);
+    for (int row = 0; row < 6; ++row)
+      for (int j = 0; j < n; ++j) {
+        pmc_pass p;
+        p.time = s.block[row * d + i] + j * T;
+        p.device = i;
+        p.op = kRowOp[row];
+        p.chunk = kRowChunk[row];
+        p.mb = j;
+        p.model_chunk = model_chunk(s, i, p.chunk);
+        v.push_back(p);
+      }
+    std::sort(v.begin(), v.end(), [](const pmc_pass& a, const pmc_pass& b) { return a.time < b.time; });
+    for (size_t k = 1; k < v.size(); ++k)
+      if (v[k].time == v[k - 1].time)
+        return fail(PMC_ERR_ILLEGAL_BLOCK, "two passes share cell %d on device %d", v[k].time, i);
+  }
+  s.passes.clear();
+  for (auto& v : s.per_device) s.passes.insert(s.passes.end(), v.begin(), v.end());
+  std::sort(s.passes.begin(), s.passes.end(), [](const pmc_pass& a, const pmc_pass& b) {
+    return a.time != b.time ? a.time < b.time : a.device < b.device;
+  });
+  return PMC_OK;
+}
+
+}  // namespace
+
+int build_schedule(int kind, int d, int n, Schedule& s) {
+  if (d < 1 || n < 1) return fail(PMC_ERR_INVALID, "need d >= 1 and n >= 1 (got d=%d n=%d)", d, n);
+  if ((int64_t)d * n > (1 << 24)) return fail(PMC_ERR_INVALID, "d*n too large");
+  s.kind = kind;
+  s.d = d;
+  s.n = n;
+  s.grouped_bw = false;
+  bool ok = true;
+  switch (kind) {
+    case PMC_1F1B:
+      s.grouped_bw = true;
+      one_f_one_b_block(d, s.block);
+      break;
+    case PMC_VMIN:  // Table 1 (1,1); Appendix F: F->B turn is 3 when d is a multiple of 3
+      ok = vshape_block(d, 1, 1, 1, d % 3 == 0 ? 3 : 1, 1, s.block);
+      break;
+    case PMC_VHALF:  // Table 1 (2,1); Appendix F: F turn 2, F->B turn 4 for even d
+      ok = vshape_block(d, 2, 1, 2, d % 2 == 0 ? 4 : 1, 1, s.block);
+      break;
+    case PMC_VZB:  // Table 1 (4,2); same-device offsets not printed in the paper
+      ok = vshape_block(d, 4, 2, 1, 1, 1, s.block);
+      break;
+    default:
+      return fail(PMC_ERR_INVALID, "unknown schedule kind %d", kind);
+  }
+  if (!ok) return fail(PMC_ERR_ILLEGAL_BLOCK, "building block of kind %d collides for d=%d", kind, d);
+  return finish(s);
+}
+
+int build_vshape(int d, int n, int delta0, int delta1, int turn_f, int turn_fb, int turn_b, Schedule& s) {
+  if (d < 1 || n < 1) return fail(PMC_ERR_INVALID, "need d >= 1 and n >= 1");
+  if (delta0 < 1 || delta1 < 1 || turn_f < 1 || turn_fb < 1 || turn_b < 1)
+    return fail(PMC_ERR_INVALID, "offsets must be positive");
+  s.kind = -1;
+  s.d = d;
+  s.n = n;
+  s.grouped_bw = false;
+  if (!vshape_block(d, delta0, delta1, turn_f, turn_fb, turn_b, s.block))
+    return fail(PMC_ERR_ILLEGAL_BLOCK, "V-shape block (%d,%d | %d,%d,%d) collides for d=%d", delta0, delta1,
+                turn_f, turn_fb, turn_b, d);
+  return finish(s);
+}
+
+// Section 2.2: a unit is allocated when its F starts and retained until B and W have both used
+// it.  With 1F1B the stage is the unit: two chunk units from the start of the stage's F to the
+// end of its fused backward.
+void account(const Schedule& s, int64_t unit_bytes, int64_t stats_bytes, pmc_device_peak* out) {
+  for (int i = 0; i < s.d; ++i) {
+    int64_t units = 0, peak_units = 0, bytes = 0, peak_bytes = 0;
+    for (const pmc_pass& p : s.per_device[i]) {
+      if (p.op == PMC_F) {
+        if (!s.grouped_bw) {
+          units += 1;
+          bytes += unit_bytes;
+        } else if (p.chunk == 0) {
+          units += 2;
+          bytes += 2 * unit_bytes;
+        }
+        peak_units = std::max(peak_units, units);
+        peak_bytes = std::max(peak_bytes, bytes);
+      } else if (p.op == PMC_B) {
+        bytes -= stats_bytes;
+      } else {
+        if (!s.grouped_bw) {
+          units -= 1;
+          bytes -= unit_bytes - stats_bytes;
+        } else if (p.chunk == 0) {
+          units -= 2;
+          bytes -= 2 * (unit_bytes - stats_bytes);
+        }
+      }
+    }
+    out[i].peak_live_units = peak_units;
+    out[i].peak_live_bytes = peak_units * unit_bytes;
+    out[i].peak_tensor_bytes = peak_bytes;
+  }
+}
+
+// Every device starts each pass of its order as soon as the device is free and the passes it
+// depends on have ended.  F needs F of the previous model chunk, B needs B of the next one (the
+// last chunk's B needs its own F), W needs its own B.  In 1F1B the backward of a stage is one
+// pass, so the stage before it waits for the end of that whole pass.
+int makespan(const Schedule& s, double tf, double tb, double tw, double* out) {
+  const int d = s.d, n = s.n, last = 2 * d - 1;
+  const double dur[3] = {tf, tb, tw};
+  std::vector<double> end((size_t)3 * 2 * d * n, -1.0);
+  auto idx = [&](int op, int mc, int mb) { return ((size_t)op * 2 * d + mc) * n + mb; };
+  std::vector<size_t> next(d, 0);
+  std::vector<double> free_at(d, 0.0);
+  size_t remaining = s.passes.size();
+  while (remaining) {
+    bool progressed = false;
+    for (int i = 0; i < d; ++i) {
+      while (next[i] < s.per_device[i].size()) {
+        const pmc_pass& p = s.per_device[i][next[i]];
+        int dep_op = -1, dep_mc = 0;
+        if (p.op == PMC_F) {
+          if (p.model_chunk > 0) dep_op = PMC_F, dep_mc = p.model_chunk - 1;
+        } else if (p.op == PMC_B) {
+          if (p.model_chunk == last) dep_op = PMC_F, dep_mc = last;
+          else if (s.grouped_bw && p.chunk == 1) dep_op = PMC_W, dep_mc = p.model_chunk + 1;
+          else dep_op = PMC_B, dep_mc = p.model_chunk + 1;
+        } else {
+          dep_op = PMC_B, dep_mc = p.model_chunk;
+        }
+        double start = free_at[i];
+        if (dep_op >= 0) {
+          double e = end[idx(dep_op, dep_mc, p.mb)];
+          if (e < 0) break;
+          start = std::max(start, e);
+        }
+        free_at[i] = end[idx(p.op, p.model_chunk, p.mb)] = start + dur[p.op];
+        ++next[i];
+        --remaining;
+        progressed = true;
+      }
+    }
+    if (!progressed) return fail(PMC_ERR_ILLEGAL_BLOCK, "orders contradict the dependencies");
+  }
+  *out = *std::max_element(free_at.begin(), free_at.end());
+  return PMC_OK;
+}
+
+}  // namespace pmc
+
+using pmc::fail;
+
+extern "C" {
+
+int pmc_schedule_build(int32_t kind, int32_t d, int32_t n, pmc_schedule** out) {
+  if (!out) return fail(PMC_ERR_INVALID, "out is NULL");
+  auto* s = new (std::nothrow) pmc_schedule;
+  if (!s) return fail(PMC_ERR_NOMEM, "host allocation failed");
+  int rc = pmc::build_schedule(kind, d, n, s->s);
+  if (rc != PMC_OK) {
+    delete s;
+    return rc;
+  }
+  *out = s;
+  return PMC_OK;
+}
+
+int pmc_schedule_build_vshape(int32_t d, int32_t n, int32_t delta0, int32_t delta1, int32_t turn_f,
+                              int32_t turn_fb, int32_t turn_b, pmc_schedule** out) {
+  if (!out) return fail(PMC_ERR_INVALID, "out is NULL");
+  auto* s = new (std::nothrow) pmc_schedule;
+  if (!s) return fail(PMC_ERR_NOMEM, "host allocation failed");
+  int rc = pmc::build_vshape(d, n, delta0, delta1, turn_f, turn_fb, turn_b, s->s);
+  if (rc != PMC_OK) {
+    delete s;
+    return rc;
+  }
+  *out = s;
+  return PMC_OK;
+}
+
+void pmc_schedule_destroy(pmc_schedule* s) { delete s; }
+int32_t pmc_schedule_devices(const pmc_schedule* s) { return s ? s->s.d : 0; }
+int32_t pmc_schedule_microbatches(const pmc_schedule* s) { return s ? s->s.n : 0; }
+int32_t pmc_schedule_num_passes(const pmc_schedule* s) { return s ? (int32_t)s->s.passes.size() : 0; }
+
+int pmc_schedule_block(const pmc_schedule* s, int32_t* out, int32_t capacity) {
+  if (!s || !out) return fail(PMC_ERR_INVALID, "NULL argument");
+  if (capacity < (int32_t)s->s.block.size()) return fail(PMC_ERR_INVALID, "capacity %d < %zu", capacity, s->s.block.size());
+  std::memcpy(out, s->s.block.data(), s->s.block.size() * sizeof(int32_t));
+  return PMC_OK;
+}
+
+int pmc_schedule_device_order(const pmc_schedule* s, int32_t device, pmc_pass* out, int32_t capacity) {
+  if (!s || !out) return fail(PMC_ERR_INVALID, "NULL argument");
+  if (device < 0 || device >= s->s.d) return fail(PMC_ERR_INVALID, "device %d out of range", device);
+  const auto& v = s->s.per_device[device];
+  if (capacity < (int32_t)v.size()) return fail(PMC_ERR_INVALID, "capacity %d < %zu", capacity, v.size());
+  std::memcpy(out, v.data(), v.size() * sizeof(pmc_pass));
+  return PMC_OK;
+}
+
+int pmc_schedule_global_order(const pmc_schedule* s, pmc_pass* out, int32_t capacity) {
+  if (!s || !out) return fail(PMC_ERR_INVALID, "NULL argument");
+  const auto& v = s->s.passes;
+  if (capacity < (int32_t)v.size()) return fail(PMC_ERR_INVALID, "capacity %d < %zu", capacity, v.size());
+  std::memcpy(out, v.data(), v.size() * sizeof(pmc_pass));
+  return PMC_OK;
+}
+
+int pmc_schedule_account(const pmc_schedule* s, int64_t unit_bytes, int64_t stats_bytes, pmc_device_peak* out,
+                         int32_t capacity) {
+  if (!s || !out) return fail(PMC_ERR_INVALID, "NULL argument");
+  if (capacity < s->s.d) return fail(PMC_ERR_INVALID, "capacity %d < d=%d", capacity, s->s.d);
+  if (unit_bytes < 0 || stats_bytes < 0 || stats_bytes > unit_bytes) return fail(PMC_ERR_INVALID, "bad byte sizes");
+  pmc::account(s->s, unit_bytes, stats_bytes, out);
+  return PMC_OK;
+}
+
+int pmc_schedule_makespan(const pmc_schedule* s, double t_f, double t_b, double t_w, double* out) {
+  if (!s || !out) return fail(PMC_ERR_INVALID, "NULL argument");
+  if (t_f < 0 || t_b < 0 || t_w < 0) return fail(PMC_ERR_INVALID, "negative duration");
+  return pmc::makespan(s->s, t_f, t_b, t_w, out);
+}
+
+}  // extern "C"

@@ -1,0 +1,175 @@
+"""GPU parity of the single kernels against the CPU oracle, element by element, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2405_15362_amd as P
+import synth
+from oracle import layer as OL
+from gpu_util import dev, host, mat, rel_l2, tol
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = P.pmc_create(None)
+    ws = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+    P.pmc_workspace_attach(c, ws)
+    yield c
+    torch.cuda.synchronize()
+    P.pmc_destroy(c)
+
+
+def _gemm_case(ctx, dtype, ta, tb, M, N, K, epi):
+    key = (dtype, ta, tb, M, N, K, epi)
+    print("gemm case", key, flush=True)
+    a = mat(key + ("a",), (K, M) if ta else (M, K), dtype)
+    b = mat(key + ("b",), (N, K) if tb else (K, N), dtype, 0.05)
+    bias = mat(key + ("bias",), (N,), dtype)
+    resid = mat(key + ("r",), (M, N), dtype)
+    aux_in = mat(key + ("u",), (M, N), dtype)
+    A = a.T.astype(np.float64) if ta else a.astype(np.float64)
+    B = b.T.astype(np.float64) if tb else b.astype(np.float64)
+    ref = A @ B
+    out_dtype = "f32" if epi == P.EPI_ACCUM_F32 else dtype
+    c0 = mat(key + ("c0",), (M, N), "f32")
+    c = dev(c0, out_dtype)
+    aux = dev(aux_in, dtype) if epi in (P.EPI_BIAS_GELU, P.EPI_DGELU) else None
+    want_aux = None
+    if epi == P.EPI_BIAS:
+        ref = ref + bias
+    elif epi == P.EPI_BIAS_RESID:
+        ref = ref + bias + resid
+    elif epi == P.EPI_BIAS_GELU:
+        ref = ref + bias
+        want_aux = OL.gelu(ref)
+    elif epi == P.EPI_DGELU:
+        ref = ref * OL.gelu_grad(aux_in.astype(np.float64))
+    elif epi == P.EPI_ACCUM_F32:
+        ref = ref + c0
+    P.pmc_gemm(ctx, dev(a, dtype), dev(b, dtype), c, ta, tb, epi,
+               dev(bias, dtype) if epi in (P.EPI_BIAS, P.EPI_BIAS_RESID, P.EPI_BIAS_GELU) else None,
+               dev(resid, dtype) if epi == P.EPI_BIAS_RESID else None, aux)
+    torch.cuda.synchronize()
+    assert rel_l2(host(c), ref) <= tol(dtype), key
+    if want_aux is not None:
+        assert rel_l2(host(aux), want_aux) <= tol(dtype), key
+
+
+@pytest.mark.parametrize("ta", [False, True])
+@pytest.mark.parametrize("tb", [False, True])
+def test_gemm_f32_layouts_and_epilogues(ctx, ta, tb):
+    for epi in range(6):
+        _gemm_case(ctx, "f32", ta, tb, 77, 130, 45, epi)
+    _gemm_case(ctx, "f32", ta, tb, 128, 256, 1024, P.EPI_NONE)
+
+
+@pytest.mark.parametrize("ta", [False, True])
+@pytest.mark.parametrize("tb", [False, True])
+def test_gemm_bf16_small_tiles_ragged(ctx, ta, tb):
+    # several 128x128 tiles with ragged tails in M, N and K
+    for epi in range(6):
+        _gemm_case(ctx, "bf16", ta, tb, 200, 328, 136, epi)
+    _gemm_case(ctx, "bf16", ta, tb, 8, 8, 8, P.EPI_NONE)
+    _gemm_case(ctx, "bf16", ta, tb, 512, 768, 1024, P.EPI_NONE)
+
+
+@pytest.mark.parametrize("ta,tb", [(False, False), (False, True), (True, False)])
+def test_gemm_bf16_large_tiles(ctx, ta, tb):
+    # enough 256x256 tiles to take the large-tile path, ragged edge tiles included
+    for epi in ((P.EPI_BIAS_GELU, P.EPI_BIAS_RESID) if not ta and not tb else
+                (P.EPI_DGELU, P.EPI_NONE) if not ta else (P.EPI_ACCUM_F32,)):
+        _gemm_case(ctx, "bf16", ta, tb, 3848, 3592, 200, epi)
+
+
+def test_gemm_rejects_bad_arguments(ctx):
+    a = torch.zeros(16, 16, device="cuda", dtype=torch.bfloat16)
+    c = torch.zeros(16, 12, device="cuda", dtype=torch.bfloat16)
+    with pytest.raises(P.PmcError) as e:
+        P.pmc_gemm(ctx, a, a[:, :12].contiguous(), c)          # N = 12 is not a multiple of 8
+    assert e.value.code == P.PMC_ERR_INVALID
+    with pytest.raises(P.PmcError):
+        P.pmc_gemm(ctx, a, a, torch.zeros(16, 16, device="cuda", dtype=torch.bfloat16), epilogue=P.EPI_BIAS)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("rows,h", [(37, 16), (64, 256), (5, 320), (130, 2048), (33, 5120), (9, 8192)])
+def test_layernorm_forward_backward(ctx, dtype, rows, h):
+    if dtype == "bf16" and h % 8:
+        pytest.skip("bf16 rows are read in 8-element vectors")
+    key = ("ln", dtype, rows, h)
+    print("layernorm case", key, flush=True)
+    x = mat(key + ("x",), (rows, h), dtype, 2.0)
+    g = mat(key + ("g",), (h,), "f32", 0.1) + 1.0
+    if dtype == "bf16":
+        g = synth.round_to_bf16(g)
+    b = mat(key + ("b",), (h,), dtype, 0.1)
+    dy = mat(key + ("dy",), (rows, h), dtype)
+    resid = mat(key + ("res",), (rows, h), dtype)
+    eps = 1e-5
+    y_ref, xhat, rstd = OL.layer_norm(x.astype(np.float64), g.astype(np.float64), b.astype(np.float64), eps)
+    dx_ref, dg_ref, db_ref = OL.layer_norm_input_grad(dy.astype(np.float64), xhat, rstd, g.astype(np.float64))
+    dx_ref = dx_ref + resid
+    xd, y = dev(x, dtype), dev(np.zeros_like(x), dtype)
+    xc = dev(np.zeros_like(x), dtype)
+    mean = torch.zeros(rows, device="cuda")
+    rs = torch.zeros(rows, device="cuda")
+    P.pmc_layernorm_forward(ctx, xd, dev(g, dtype), dev(b, dtype), eps, y, mean, rs, xc)
+    torch.cuda.synchronize()
+    assert rel_l2(host(y), y_ref) <= tol(dtype)
+    assert np.abs(host(mean) - x.astype(np.float64).mean(-1)).max() <= 1e-5
+    assert rel_l2(host(rs), rstd[:, 0]) <= 1e-5
+    assert torch.equal(xc, xd)
+    dgain = torch.full((h,), 0.25, device="cuda")
+    dbias = torch.full((h,), -0.5, device="cuda")
+    dx = xd.clone()                      # in place over x, as the B pass does
+    P.pmc_layernorm_backward(ctx, dev(dy, dtype), dx, dev(g, dtype), mean, rs, dev(resid, dtype), dx, dgain, dbias)
+    torch.cuda.synchronize()
+    assert rel_l2(host(dx), dx_ref) <= tol(dtype)
+    assert rel_l2(host(dgain) - 0.25, dg_ref) <= (5e-3 if dtype == "bf16" else 1e-5)
+    assert rel_l2(host(dbias) + 0.5, db_ref) <= 1e-5
+
+
+@pytest.mark.parametrize("dtype,dh", [("f32", 4), ("f32", 16), ("f32", 64), ("f32", 128), ("bf16", 64), ("bf16", 128)])
+@pytest.mark.parametrize("causal", [True, False])
+def test_attention_forward_backward(ctx, dtype, dh, causal):
+    batch, seq, heads = 2, 88, 3
+    if dh == 4:
+        seq = 24                                     # vectors of 4 fp32: hidden must be a multiple of 4
+    h = heads * dh
+    key = ("attn", dtype, dh, causal)
+    print("attention case", key, flush=True)
+    qkv = mat(key + ("qkv",), (batch * seq, 3 * h), dtype)
+    d_o = mat(key + ("do",), (batch * seq, h), dtype)
+    q64 = qkv.astype(np.float64)
+    o_ref, probs, lse_ref = OL.attention(q64, heads, causal, batch)
+    dqkv_ref = OL.attention_input_grad(d_o.astype(np.float64), q64, probs, heads, batch)
+    qd = dev(qkv, dtype)
+    o = dev(np.zeros((batch * seq, h)), dtype)
+    lse = torch.zeros(batch * heads * seq, device="cuda")
+    P.pmc_attention_forward(ctx, qd, o, lse, batch, seq, heads, dh, causal)
+    torch.cuda.synchronize()
+    assert rel_l2(host(o), o_ref) <= tol(dtype)
+    assert np.abs(host(lse) - lse_ref.reshape(-1)).max() <= (2e-2 if dtype == "bf16" else 2e-5)
+    # separate output buffer
+    dq = dev(np.zeros_like(qkv), dtype)
+    P.pmc_attention_backward(ctx, qd, o, lse, dev(d_o, dtype), dq, batch, seq, heads, dh, causal)
+    torch.cuda.synchronize()
+    for name, cols in (("dq", slice(0, h)), ("dk", slice(h, 2 * h)), ("dv", slice(2 * h, 3 * h))):
+        assert rel_l2(host(dq)[:, cols], dqkv_ref[:, cols]) <= tol(dtype), name
+    # in place over qkv, as the B pass does
+    inplace = qd.clone()
+    P.pmc_attention_backward(ctx, inplace, o, lse, dev(d_o, dtype), inplace, batch, seq, heads, dh, causal)
+    torch.cuda.synchronize()
+    assert torch.equal(inplace, dq)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_column_sum(ctx, dtype):
+    for rows, n in ((1, 8), (50, 264), (1000, 2048), (300, 6144)):
+        a = mat(("cs", dtype, rows, n), (rows, n), dtype)
+        out = torch.full((n,), 2.0, device="cuda")
+        P.pmc_column_sum(ctx, dev(a, dtype), out)
+        torch.cuda.synchronize()
+        assert np.abs(host(out) - 2.0 - a.astype(np.float64).sum(0)).max() <= 1e-4 * max(1.0, np.sqrt(rows))

@@ -1,0 +1,212 @@
+"""GPU parity of the chunk passes F, B, W and of the schedule replay against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2405_15362_amd as P
+import synth
+from oracle import layer as OL
+from oracle import schedule as OS
+from paper_2405_15362_amd import runtime as R
+from gpu_util import dev, host, oracle_chunk, rel_l2, tol
+
+pytestmark = pytest.mark.gpu
+
+CASES = {
+    # the fp32 configuration of the build (1 layer, hidden 256, 4 heads, FFN 1024, seq 128)
+    "c1_f32": synth.CONFIGS["C1"],
+    "multi_f32": synth.ChunkCfg(layers=2, hidden=64, heads=4, ffn=200, seq=40, microbatch=2, dtype="f32"),
+    "noncausal_f32": synth.ChunkCfg(layers=1, hidden=96, heads=3, ffn=256, seq=52, dtype="f32", causal=False),
+    "dh128_bf16": synth.ChunkCfg(layers=2, hidden=256, heads=2, ffn=1024, seq=192, dtype="bf16"),
+    "dh64_ragged_bf16": synth.ChunkCfg(layers=3, hidden=192, heads=3, ffn=328, seq=104, microbatch=2, dtype="bf16"),
+}
+
+
+def _run_fbw(cfg, tag, n_mb=1, defer=False):
+    params = synth.chunk_params(cfg, tag)
+    ctx = R.Context(R.cfg_from_synth(cfg), slabs=n_mb)
+    ch = ctx.add_chunk(params, cfg.dtype)
+    out = []
+    xs = [synth.chunk_input(cfg, tag, j) for j in range(n_mb)]
+    dys = [synth.upstream_grad(cfg, tag, j) for j in range(n_mb)]
+    ys = [dev(np.zeros_like(x), cfg.dtype) for x in xs]
+    dxs = [dev(np.zeros_like(x), cfg.dtype) for x in xs]
+    for j in range(n_mb):
+        P.stage_forward(ch.handle, j, dev(xs[j], cfg.dtype), ys[j])
+        if not defer:
+            P.stage_backward_input(ch.handle, j, dev(dys[j], cfg.dtype), dxs[j])
+            P.stage_backward_weight(ch.handle, [j])
+    if defer:
+        for j in range(n_mb):
+            P.stage_backward_input(ch.handle, j, dev(dys[j], cfg.dtype), dxs[j])
+        assert P.pmc_pool_live_slabs(ctx.ctx) == n_mb
+        P.stage_backward_weight(ch.handle, list(range(n_mb)))
+    torch.cuda.synchronize()
+    assert P.pmc_pool_live_slabs(ctx.ctx) == 0 and P.pmc_pool_peak_slabs(ctx.ctx) == (n_mb if defer else 1)
+    grads = ch.grads_numpy()
+    res = ([host(y) for y in ys], [host(d) for d in dxs], grads)
+    ctx.close()
+    return params, xs, dys, res
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_f_b_w_match_oracle(name):
+    cfg = CASES[name]
+    print("pass parity case", name, cfg, flush=True)
+    params, xs, dys, (ys, dxs, grads) = _run_fbw(cfg, name)
+    y, dx, ln, wg = oracle_chunk(cfg, params, xs[0], dys[0])
+    t = tol(cfg.dtype)
+    assert rel_l2(ys[0], y) <= t
+    assert rel_l2(dxs[0], dx) <= t
+    for l in range(cfg.layers):
+        for k, v in {**ln[l], **wg[l]}.items():
+            assert rel_l2(grads[l][k], v) <= t, (l, k, rel_l2(grads[l][k], v))
+
+
+@pytest.mark.parametrize("name", ["multi_f32", "dh128_bf16"])
+def test_deferred_w_accumulates_over_microbatches(name):
+    cfg = CASES[name]
+    n_mb = 3
+    params, xs, dys, (ys, dxs, grads) = _run_fbw(cfg, name + "_defer", n_mb, defer=True)
+    total = OL.zero_grads(OL.cast_params(params))
+    for j in range(n_mb):
+        y, dx, ln, wg = oracle_chunk(cfg, params, xs[j], dys[j])
+        OL.accumulate(total, ln, wg)
+        assert rel_l2(ys[j], y) <= tol(cfg.dtype) and rel_l2(dxs[j], dx) <= tol(cfg.dtype)
+    for l in range(cfg.layers):
+        for k in OL.PARAM_NAMES:
+            assert rel_l2(grads[l][k], total[l][k]) <= tol(cfg.dtype), (l, k)
+    # immediate W per microbatch gives the same bits as the queued one (same order of additions)
+    _, _, _, (_, _, grads2) = _run_fbw(cfg, name + "_defer", n_mb, defer=False)
+    for l in range(cfg.layers):
+        for k in OL.PARAM_NAMES:
+            assert np.array_equal(grads[l][k], grads2[l][k]), (l, k)
+
+
+def test_pass_order_errors():
+    cfg = CASES["multi_f32"]
+    ctx = R.Context(R.cfg_from_synth(cfg), slabs=1)
+    ch = ctx.add_chunk(synth.chunk_params(cfg, "err"), cfg.dtype)
+    x = dev(synth.chunk_input(cfg, "err"), cfg.dtype)
+    y, dx = torch.empty_like(x), torch.empty_like(x)
+
+    def code(fn, *a):
+        with pytest.raises(P.PmcError) as e:
+            fn(*a)
+        return e.value.code
+
+    assert code(P.stage_backward_input, ch.handle, 0, x, dx) == P.PMC_ERR_STATE       # B before F
+    assert code(P.stage_backward_weight, ch.handle, [0]) == P.PMC_ERR_STATE           # W before F
+    P.stage_forward(ch.handle, 0, x, y)
+    assert code(P.stage_forward, ch.handle, 0, x, y) == P.PMC_ERR_STATE               # live id reused
+    assert code(P.stage_forward, ch.handle, 1, x, y) == P.PMC_ERR_NOMEM               # pool exhausted
+    assert code(P.stage_backward_weight, ch.handle, [0]) == P.PMC_ERR_STATE           # W before B
+    P.stage_backward_input(ch.handle, 0, x, dx)
+    assert code(P.stage_backward_input, ch.handle, 0, x, dx) == P.PMC_ERR_STATE       # B twice
+    assert code(P.stage_backward_weight, ch.handle, [0, 0]) == P.PMC_ERR_INVALID
+    P.stage_backward_weight(ch.handle, [0])
+    assert code(P.stage_backward_weight, ch.handle, [0]) == P.PMC_ERR_STATE           # W twice
+    torch.cuda.synchronize()
+    assert P.pmc_pool_live_slabs(ctx.ctx) == 0
+    ctx.close()
+
+
+def _oracle_model(cfg, chunk_params, xs, dys):
+    """The whole model (chunks in order), microbatch after microbatch, in fp64."""
+    p64 = [OL.cast_params(p) for p in chunk_params]
+    grads = [OL.zero_grads(p) for p in p64]
+    ys, dxs = [], []
+    for x, dy in zip(xs, dys):
+        a = x.astype(np.float64)
+        saved = []
+        for p in p64:
+            a, sv = OL.chunk_forward(a, p, cfg.heads, cfg.causal, cfg.ln_eps, cfg.microbatch)
+            saved.append(sv)
+        ys.append(a)
+        g = dy.astype(np.float64)
+        for c in reversed(range(len(p64))):
+            g, stash, ln = OL.chunk_backward_input(g, p64[c], saved[c], cfg.heads, cfg.microbatch)
+            OL.accumulate(grads[c], ln, OL.chunk_backward_weight(saved[c], stash))
+        dxs.append(g)
+    return ys, dxs, grads
+
+
+def _replay(cfg, tag, kind, d, n, chunk_params, xs, dys):
+    sched = P.pmc_schedule_build(kind, d, n)
+    pcfg = R.cfg_from_synth(cfg)
+    units = max(OS.peak_units(kind, d, n))
+    ctx = R.Context(pcfg, slabs=sum(OS.peak_units(kind, d, n)), workspace_bytes=P.pmc_replay_workspace_bytes(sched, pcfg))
+    chunks = [ctx.add_chunk(p, cfg.dtype) for p in chunk_params]
+    xd = [dev(x, cfg.dtype) for x in xs]
+    dyd = [dev(g, cfg.dtype) for g in dys]
+    yl = [torch.empty_like(t) for t in xd]
+    dxf = [torch.empty_like(t) for t in xd]
+    report, peaks = P.schedule_replay(ctx.ctx, sched, [c.handle for c in chunks], xd, dyd, yl, dxf, P.REPLAY_TIME_PASSES)
+    torch.cuda.synchronize()
+    assert P.pmc_pool_live_slabs(ctx.ctx) == 0
+    grads = [c.grads_numpy() for c in chunks]
+    out = ([host(t) for t in yl], [host(t) for t in dxf], grads, report, peaks)
+    ctx.close()
+    P.pmc_schedule_destroy(sched)
+    return out
+
+
+def test_replay_config1_all_schedules():
+    """2 simulated devices x 4 microbatches, 4 one-layer fp32 chunks (hidden 256, seq 128), replayed
+    as 1F1B, V-Half, V-Min and V-ZB: outputs and accumulated gradients against the oracle's whole
+    model, peaks against the oracle's accounting, gradients bit-identical across schedules."""
+    cfg, d, n = synth.CONFIGS["C1"], 2, 4
+    chunk_params = [synth.chunk_params(cfg, "C1", c) for c in range(2 * d)]
+    xs = [synth.chunk_input(cfg, "C1", j) for j in range(n)]
+    dys = [synth.upstream_grad(cfg, "C1", j) for j in range(n)]
+    ys_ref, dxs_ref, grads_ref = _oracle_model(cfg, chunk_params, xs, dys)
+    m = OL.chunk_activation_bytes(cfg.layers, cfg.hidden, cfg.heads, cfg.seq, 4, cfg.microbatch, cfg.ffn)
+    st = OL.chunk_stats_bytes(cfg.layers, cfg.heads, cfg.seq, cfg.microbatch)
+    first = None
+    for kind in ("1f1b", "vhalf", "vmin", "vzb"):
+        print("replay", kind, flush=True)
+        ys, dxs, grads, report, peaks = _replay(cfg, "C1", kind, d, n, chunk_params, xs, dys)
+        for j in range(n):
+            assert rel_l2(ys[j], ys_ref[j]) <= 1e-5 and rel_l2(dxs[j], dxs_ref[j]) <= 1e-5
+        for c in range(2 * d):
+            for k in OL.PARAM_NAMES:
+                assert rel_l2(grads[c][0][k], grads_ref[c][0][k]) <= 1e-5, (kind, c, k)
+        units = OS.peak_units(kind, d, n)
+        want = OS.peak_bytes(kind, d, n, m, st)
+        assert [p[0] for p in peaks] == units
+        assert [(p[1], p[2]) for p in peaks] == want
+        assert report["passes"] == 6 * d * n and report["ms_total"] > 0
+        if first is None:
+            first = grads
+        else:
+            for c in range(2 * d):
+                for k in OL.PARAM_NAMES:
+                    assert np.array_equal(grads[c][0][k], first[c][0][k]), (kind, c, k)
+
+
+def test_replay_bf16_d4_reduced_width():
+    """The d=4, n=16 replay of the large configuration at reduced width (2-layer bf16 chunks)."""
+    cfg = synth.ChunkCfg(layers=2, hidden=128, heads=2, ffn=512, seq=64, dtype="bf16")
+    d, n = 4, 16
+    chunk_params = [synth.chunk_params(cfg, "C5r", c) for c in range(2 * d)]
+    xs = [synth.chunk_input(cfg, "C5r", j) for j in range(n)]
+    dys = [synth.upstream_grad(cfg, "C5r", j) for j in range(n)]
+    ys_ref, dxs_ref, grads_ref = _oracle_model(cfg, chunk_params, xs, dys)
+    first = None
+    for kind in ("1f1b", "vzb", "vhalf", "vmin"):
+        print("replay", kind, flush=True)
+        ys, dxs, grads, report, peaks = _replay(cfg, "C5r", kind, d, n, chunk_params, xs, dys)
+        for j in range(n):
+            assert rel_l2(ys[j], ys_ref[j]) <= 2e-2 and rel_l2(dxs[j], dxs_ref[j]) <= 2e-2
+        for c in range(2 * d):
+            for l in range(cfg.layers):
+                for k in OL.PARAM_NAMES:
+                    assert rel_l2(grads[c][l][k], grads_ref[c][l][k]) <= 2e-2, (kind, c, l, k)
+        assert [p[0] for p in peaks] == OS.peak_units(kind, d, n)
+        if first is None:
+            first = grads
+        else:
+            for c in range(2 * d):
+                for l in range(cfg.layers):
+                    for k in OL.PARAM_NAMES:
+                        assert np.array_equal(grads[c][l][k], first[c][l][k]), (kind, c, l, k)

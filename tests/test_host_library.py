@@ -1,0 +1,117 @@
+"""CPU-only checks of the C-ABI library: it loads without a GPU, exports every symbol the header
+declares, and its host-only schedule generator agrees bit for bit with the oracle."""
+import os
+import re
+
+import pytest
+
+import paper_2405_15362_amd as P
+from oracle import layer as OL
+from oracle import schedule as S
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_header_symbols_are_exported_and_bound():
+    text = open(os.path.join(ROOT, "include", "pmc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b((?:pmc|stage|schedule)_[a-z0-9_]+)\s*\(", text))
+    assert len(declared) >= 30
+    for name in declared:
+        assert hasattr(P.lib, name), f"{name} is declared in pmc.h but not exported"
+    assert declared == set(P.EXPORTS), declared ^ set(P.EXPORTS)
+
+
+@pytest.mark.parametrize("kind", S.KINDS)
+@pytest.mark.parametrize("d,n", [(1, 3), (2, 4), (3, 7), (4, 16), (6, 13), (8, 32), (9, 20)])
+def test_orders_match_oracle(kind, d, n):
+    s = P.pmc_schedule_build(kind, d, n)
+    try:
+        assert P.pmc_schedule_devices(s) == d and P.pmc_schedule_microbatches(s) == n
+        assert P.pmc_schedule_num_passes(s) == 6 * d * n
+        assert P.pmc_schedule_block(s) == S.block(kind, d)
+        passes = S.build(kind, d, n)
+        want = [(p.time, p.device, p.op, p.chunk, p.mb, S.model_chunk(kind, d, p.device, p.chunk))
+                for p in S.global_order(passes)]
+        got = [(p.time, p.device, p.op, p.chunk, p.mb, p.model_chunk) for p in P.pmc_schedule_global_order(s)]
+        assert got == want
+        for i, order in enumerate(S.device_orders(passes, d)):
+            got_i = [(p.time, p.op, p.chunk, p.mb) for p in P.pmc_schedule_device_order(s, i)]
+            assert got_i == [(p.time, p.op, p.chunk, p.mb) for p in order]
+    finally:
+        P.pmc_schedule_destroy(s)
+
+
+@pytest.mark.parametrize("kind", S.KINDS)
+@pytest.mark.parametrize("d,n", [(2, 4), (4, 16), (5, 11), (8, 24), (64, 256)])
+def test_accounting_matches_oracle(kind, d, n):
+    m, st = 537460736, 589824
+    s = P.pmc_schedule_build(kind, d, n)
+    try:
+        got = P.pmc_schedule_account(s, m, st)
+        units = S.peak_units(kind, d, n)
+        bytes_ = S.peak_bytes(kind, d, n, m, st)
+        assert [g[0] for g in got] == units
+        assert [(g[1], g[2]) for g in got] == bytes_
+    finally:
+        P.pmc_schedule_destroy(s)
+
+
+@pytest.mark.parametrize("kind", S.KINDS)
+@pytest.mark.parametrize("times", [(1.0, 1.0, 1.0), (1.0, 1.1, 0.7), (2.0, 1.0, 0.5)])
+def test_makespan_matches_oracle(kind, times):
+    for d, n in ((2, 4), (4, 16), (8, 24)):
+        s = P.pmc_schedule_build(kind, d, n)
+        try:
+            assert P.pmc_schedule_makespan(s, *times) == pytest.approx(S.squeezed_makespan(kind, d, n, *times), rel=1e-12)
+        finally:
+            P.pmc_schedule_destroy(s)
+
+
+def test_custom_vshape_block_and_collision():
+    s = P.pmc_schedule_build_vshape(4, 8, 2, 1, 2, 4, 1)
+    ref = P.pmc_schedule_build("vhalf", 4, 8)
+    assert P.pmc_schedule_global_order(s) == P.pmc_schedule_global_order(ref)
+    P.pmc_schedule_destroy(s)
+    P.pmc_schedule_destroy(ref)
+    with pytest.raises(P.PmcError) as e:
+        P.pmc_schedule_build_vshape(4, 4, 2, 1, 1, 1, 1)
+    assert e.value.code == P.PMC_ERR_ILLEGAL_BLOCK
+    assert S.vshape_block(4, 2, 1, 1, 1, 1) is None
+    # every (a, b, c) below the repeat interval: both sides agree on which blocks are legal
+    for a in range(1, 6):
+        for b in range(1, 6):
+            for c in range(1, 6):
+                legal = S.vshape_block(5, 4, 2, a, b, c) is not None
+                try:
+                    P.pmc_schedule_destroy(P.pmc_schedule_build_vshape(5, 2, 4, 2, a, b, c))
+                    assert legal
+                except P.PmcError:
+                    assert not legal
+
+
+def test_bad_arguments():
+    for args in (("vhalf", 0, 4), ("vhalf", 4, 0), (17, 4, 4)):
+        with pytest.raises(P.PmcError) as e:
+            P.pmc_schedule_build(*args)
+        assert e.value.code == P.PMC_ERR_INVALID
+    assert "kind" in P.pmc_last_error()
+
+
+@pytest.mark.parametrize("name,cfg", [
+    ("C1", (1, 256, 4, 1024, 128, 1, "f32")), ("C2", (2, 2048, 16, 8192, 1024, 1, "bf16")),
+    ("C3", (4, 4096, 32, 16384, 2048, 1, "bf16")), ("C4", (2, 5120, 40, 20480, 4096, 1, "bf16")),
+    ("odd", (3, 192, 3, 320, 40, 2, "bf16"))])
+def test_activation_bytes_match_oracle(name, cfg):
+    L, h, nh, f, s, mb, dt = cfg
+    c = P.make_cfg(L, h, nh, f, s, mb, dt)
+    e = 4 if dt == "f32" else 2
+    assert P.pmc_activation_bytes(c) == OL.chunk_activation_bytes(L, h, nh, s, e, mb, f)
+    assert P.pmc_activation_stats_bytes(c) == OL.chunk_stats_bytes(L, nh, s, mb)
+    assert P.pmc_pass_workspace_bytes(c) > 0
+
+
+def test_bad_cfg_is_rejected():
+    assert P.pmc_activation_bytes(P.make_cfg(1, 100, 3, 400, 64)) == 0       # hidden % heads
+    assert P.pmc_activation_bytes(P.make_cfg(1, 2048, 4, 8192, 64)) == 0     # head size 512
+    assert P.pmc_activation_bytes(P.make_cfg(0, 256, 4, 1024, 64)) == 0

@@ -124,8 +124,9 @@ size_t pmc_activation_stats_bytes(const pmc_chunk_cfg* cfg);
 size_t pmc_pass_workspace_bytes(const pmc_chunk_cfg* cfg);
 
 /* Creates a chunk of cfg->layers identical layers.  Constraints: hidden % heads == 0, head size
- * 64 or 128 in bf16 mode (any multiple of 4 up to 128 in fp32 mode), hidden, ffn multiples of 64
- * in bf16 mode.  Host-only call. */
+ * <= 128 (64 and 128 take the matrix-core attention kernels in bf16 mode); hidden, ffn and tokens
+ * multiples of 8 with hidden <= 8192 in bf16 mode, multiples of 4 with hidden <= 4096 in fp32
+ * mode.  Host-only call. */
 int pmc_chunk_create(pmc_ctx* ctx, const pmc_chunk_cfg* cfg, pmc_chunk** out);
 void pmc_chunk_destroy(pmc_chunk* chunk);
 /* Binds parameters and gradient accumulators: arrays of layers * PMC_PARAMS_PER_LAYER device
@@ -217,12 +218,13 @@ int pmc_gemm(pmc_ctx* ctx, int32_t dtype, int32_t trans_a, int32_t trans_b, int3
              int32_t K, const void* A, int32_t lda, const void* B, int32_t ldb, void* C, int32_t ldc,
              int32_t epilogue, const void* bias, const void* resid, void* aux);
 
-/* y = LayerNorm(x) over rows of length h; mean and rstd are fp32 [rows]. x_copy may be NULL. */
+/* y = LayerNorm(x) over rows of length h (a multiple of 4 up to 4096 in fp32, of 8 up to 8192 in
+ * bf16); mean and rstd are fp32 [rows]; x_copy (may be NULL) receives a copy of x. */
 int pmc_layernorm_forward(pmc_ctx* ctx, int32_t dtype, int32_t rows, int32_t h, const void* x,
                           const void* gain, const void* bias, float eps, void* y, float* mean,
                           float* rstd, void* x_copy);
-/* dx = resid + LayerNorm input-gradient of dy; dgain/dbias (fp32 [h]) are accumulated into.
- * Needs 2 * h * 4 * ceil(rows / 32) bytes ... of workspace. dx may alias x. */
+/* dx = resid + LayerNorm input-gradient of dy (resid may be NULL); dgain/dbias (fp32 [h]) are
+ * accumulated into.  Uses the attached workspace.  dx may alias x. */
 int pmc_layernorm_backward(pmc_ctx* ctx, int32_t dtype, int32_t rows, int32_t h, const void* dy,
                            const void* x, const void* gain, const float* mean, const float* rstd,
                            const void* resid, void* dx, float* dgain, float* dbias);

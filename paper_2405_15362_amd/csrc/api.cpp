@@ -125,10 +125,12 @@ int check_cfg(const pmc_chunk_cfg* c) {
     if (c->hidden % 8 || c->ffn % 8 || tokens % 8)
       return fail(PMC_ERR_INVALID, "cfg: bf16 mode needs hidden, ffn and tokens to be multiples of 8");
     if (dh > 128) return fail(PMC_ERR_INVALID, "cfg: head size %d > 128", dh);
+    if (c->hidden > 8192) return fail(PMC_ERR_INVALID, "cfg: bf16 mode supports hidden <= 8192");
   } else {
     if (c->hidden % 4 || c->ffn % 4 || tokens % 4)
       return fail(PMC_ERR_INVALID, "cfg: fp32 mode needs hidden, ffn and tokens to be multiples of 4");
     if (dh > 128) return fail(PMC_ERR_INVALID, "cfg: head size %d > 128", dh);
+    if (c->hidden > 4096) return fail(PMC_ERR_INVALID, "cfg: fp32 mode supports hidden <= 4096");
   }
   if (!(c->ln_eps >= 0.f)) return fail(PMC_ERR_INVALID, "cfg: ln_eps must be >= 0");
   return PMC_OK;

@@ -10,7 +10,15 @@ int attention_backward_simple(hipStream_t st, int dtype, int batch, int seq, int
                               const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv,
                               void* dq_stage, float* delta);
 
+int attention_forward_mfma(hipStream_t st, int batch, int seq, int heads, int dh, int causal, const void* qkv, void* o,
+                           float* lse);
+int attention_backward_mfma(hipStream_t st, int batch, int seq, int heads, int dh, int causal, const void* qkv,
+                            const void* o, const float* lse, const void* d_o, void* dqkv, void* dq_stage, float* delta);
+
 namespace {
+// bf16 storage with head size 64 or 128 runs on the matrix cores; everything else (fp32 mode,
+// other head sizes) on the plain-arithmetic kernels.
+bool use_mfma(int dtype, int head_dim) { return dtype == PMC_BF16 && (head_dim == 64 || head_dim == 128); }
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 size_t elem(int dtype) { return dtype == PMC_F32 ? 4 : 2; }
 }  // namespace
@@ -19,6 +27,7 @@ int attention_forward(hipStream_t st, int dtype, int batch, int seq, int heads, 
                       const void* qkv, void* o, float* lse) {
   if (!qkv || !o || !lse) return fail(PMC_ERR_INVALID, "attention_forward: NULL pointer");
   if (dtype != PMC_F32 && dtype != PMC_BF16) return fail(PMC_ERR_INVALID, "attention_forward: bad dtype %d", dtype);
+  if (use_mfma(dtype, head_dim)) return attention_forward_mfma(st, batch, seq, heads, head_dim, causal, qkv, o, lse);
   return attention_forward_simple(st, dtype, batch, seq, heads, head_dim, causal, qkv, o, lse);
 }
 
@@ -40,9 +49,11 @@ int attention_backward(hipStream_t st, int dtype, int batch, int seq, int heads,
   // dq goes to the staging buffer because q is still needed by the dk/dv kernel, which reads k, v
   // from qkv and writes dk, dv to the same columns of dqkv (dqkv may be qkv itself: a key tile is
   // read only by the workgroup that later overwrites it).
-  if (int rc = attention_backward_simple(st, dtype, batch, seq, heads, head_dim, causal, qkv, o, lse, d_o, dqkv,
-                                         dq_stage, delta))
-    return rc;
+  const int rc = use_mfma(dtype, head_dim)
+                     ? attention_backward_mfma(st, batch, seq, heads, head_dim, causal, qkv, o, lse, d_o, dqkv, dq_stage, delta)
+                     : attention_backward_simple(st, dtype, batch, seq, heads, head_dim, causal, qkv, o, lse, d_o, dqkv,
+                                                 dq_stage, delta);
+  if (rc) return rc;
   return copy_rows(st, dtype, (int)tokens, h, dq_stage, h, dqkv, 3 * h);
 }
 

@@ -1,0 +1,494 @@
+// Fused flash-style attention for bf16 storage on the gfx950 matrix cores
+// (v_mfma_f32_32x32x16_bf16), head size 64 or 128, packed qkv [batch*seq, 3h].
+//
+// Forward: a workgroup owns 128 queries of one head (32 per wave) and streams 64-key blocks of K
+// and V through LDS (double buffered).  Scores are produced transposed, S^T[key][query], so every
+// lane owns ONE query column: the online-softmax max/sum over keys are in-lane reductions plus one
+// exchange between the two half-waves, and the probabilities already sit in the register layout of
+// the B operand of the second product O^T = V^T . P^T.  V^T is never formed in memory: the V tile
+// stays [key][dh] in LDS and is read with the transposing LDS load.  Saves O and the log-sum-exp.
+//
+// Backward is two kernels, each output element having one writer and a fixed summation order
+// (results are reproducible run to run):
+//   dQ   per 128-query block, streaming K/V blocks: recomputes P from the saved log-sum-exp,
+//        dS = P * (dO.V^T - delta), dQ^T += K^T . dS^T; also emits delta = rowsum(dO * O).
+//   dKdV per 128-key block, streaming Q/dO blocks: dV^T += dO^T . P, dK^T += Q^T . dS, written
+//        in place over K and V (a key block is read only by the workgroup that owns it).
+#include "dev_common.h"
+#include "kernels.h"
+
+namespace pmc {
+namespace k {
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+// Fragment with the contraction index contiguous in the LDS row: lane l gets row row0 + l%32,
+// contraction indices k0 + 8*(l/32) .. +7.
+__device__ __forceinline__ bf16x8 frag_rows(const bf16_t* tile, int pitch, int row0, int k0, int lane) {
+  return *reinterpret_cast<const bf16x8*>(tile + (row0 + (lane & 31)) * pitch + k0 + 8 * (lane >> 5));
+}
+
+// Fragment of the TRANSPOSE of an LDS tile: lane l gets tile column col0 + l%32 and, as its 8
+// contraction entries, tile rows  krow0 + 4*(l/32) + {0,1,2,3}  and  krow0 + 8 + 4*(l/32) + {0,1,2,3}.
+// That row order is exactly the one in which a lane holds a 32x32 accumulator tile's registers
+// 8t .. 8t+7 (rows 8*(r/4) + 4*(l/32) + r%4), so accumulators can be fed back as the other operand.
+__device__ __forceinline__ bf16x8 frag_cols(const bf16_t* tile, int pitch, int col0, int krow0, int lane) {
+  const int g = lane >> 4, j = lane & 15;
+  const bf16_t* p = tile + (krow0 + 4 * (g >> 1) + (j >> 2)) * pitch + col0 + 16 * (g & 1) + 4 * (j & 3);
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 8 * pitch));
+  const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// Registers 8t .. 8t+7 of an accumulator tile as a bf16 operand fragment.
+__device__ __forceinline__ bf16x8 acc_to_frag(const f32x16& a, int t) {
+  bf16x8 v;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = (__bf16)a[8 * t + e];
+  return v;
+}
+
+// Cooperative copy of a [ROWS][DH] block of rows row0.. (pitch ld in global memory) into registers
+// and from there into an LDS tile of pitch P; rows >= row_limit read as zero.
+template <int ROWS, int DH, int P, int NT>
+struct BlockStager {
+  static constexpr int CH = ROWS * DH / 8 / NT;
+  u32x4 r[CH];
+  __device__ __forceinline__ void load(const bf16_t* __restrict__ base, size_t ld, int row0, int row_limit, int tid) {
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int c = tid + i * NT, row = c / (DH / 8), cc = (c % (DH / 8)) * 8;
+      u32x4 z = {0u, 0u, 0u, 0u};
+      r[i] = (row0 + row < row_limit) ? *reinterpret_cast<const u32x4*>(base + (size_t)(row0 + row) * ld + cc) : z;
+    }
+  }
+  __device__ __forceinline__ void store(bf16_t* tile, int tid) const {
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int c = tid + i * NT, row = c / (DH / 8), cc = (c % (DH / 8)) * 8;
+      *reinterpret_cast<u32x4*>(tile + row * P + cc) = r[i];
+    }
+  }
+};
+
+__device__ __forceinline__ void zero(f32x16& a) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r) a[r] = 0.f;
+}
+
+// Writes an accumulator tile holding OUT^T[dh][row] (lane = row, registers = dh) times `mul` to
+// out[row][col0 + 32*dt + ...] as bf16, four consecutive columns per store.
+__device__ __forceinline__ void store_tile_t(bf16_t* row_ptr, const f32x16& a, float mul, int lane) {
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    u32x2 v = {pack_bf16x2(a[4 * q] * mul, a[4 * q + 1] * mul), pack_bf16x2(a[4 * q + 2] * mul, a[4 * q + 3] * mul)};
+    *reinterpret_cast<u32x2*>(row_ptr + 8 * q + 4 * (lane >> 5)) = v;
+  }
+}
+
+constexpr int BQ = 128;   // rows owned by a workgroup (32 per wave)
+constexpr int BS = 64;    // rows of a streamed block
+constexpr int PAD_ROWS = 8;    // tile read only with frag_rows: pitch DH + 8
+constexpr int PAD_COLS = 32;   // tile read only with frag_cols: pitch DH + 32
+constexpr int PAD_BOTH = 40;   // tile read both ways: pitch DH + 40
+
+template <int DH>
+__global__ __launch_bounds__(256, 2) void attn_fwd_mfma(int seq, int heads, int causal, const bf16_t* __restrict__ qkv,
+                                                         bf16_t* __restrict__ o, float* __restrict__ lse,
+                                                         float scale_log2) {
+  constexpr int KP = DH + PAD_ROWS, VP = DH + PAD_COLS;
+  constexpr int KT = BS * KP, VT = BS * VP;
+  extern __shared__ __attribute__((aligned(16))) bf16_t smem[];  // [2][K tile | V tile]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hl = lane >> 5;
+  const int h = heads * DH, head = blockIdx.y, b = blockIdx.z;
+  const int q0 = blockIdx.x * BQ, qw0 = q0 + 32 * wave, qrow = qw0 + (lane & 31);
+  const size_t ld = (size_t)3 * h;
+  const bf16_t* base = qkv + (size_t)b * seq * ld + (size_t)head * DH;
+
+  bf16x8 qf[DH / 16];
+  {
+    const bf16_t* qp = base + (size_t)min(qrow, seq - 1) * ld + 8 * hl;
+#pragma unroll
+    for (int ks = 0; ks < DH / 16; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+  }
+  f32x16 oacc[DH / 32];
+#pragma unroll
+  for (int dt = 0; dt < DH / 32; ++dt) zero(oacc[dt]);
+  float m2 = -INFINITY, lsum = 0.f;
+
+  const int kend = causal ? min(seq, q0 + BQ) : seq;
+  const int nblk = (kend + BS - 1) / BS;
+  BlockStager<BS, DH, KP, 256> sk;
+  BlockStager<BS, DH, VP, 256> sv;
+  sk.load(base + h, ld, 0, seq, tid);
+  sv.load(base + 2 * h, ld, 0, seq, tid);
+  sk.store(smem, tid);
+  sv.store(smem + KT, tid);
+  __syncthreads();
+  for (int blk = 0; blk < nblk; ++blk) {
+    const int k0 = blk * BS;
+    const bf16_t* kt_ = smem + (blk & 1) * (KT + VT);
+    const bf16_t* vt_ = kt_ + KT;
+    if (blk + 1 < nblk) {
+      sk.load(base + h, ld, k0 + BS, seq, tid);
+      sv.load(base + 2 * h, ld, k0 + BS, seq, tid);
+    }
+    if (!causal || k0 <= qw0 + 31) {
+      f32x16 s[2];
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+        zero(s[kt]);
+#pragma unroll
+        for (int ks = 0; ks < DH / 16; ++ks)
+          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(kt_, KP, 32 * kt, 16 * ks, lane), qf[ks], s[kt], 0, 0, 0);
+      }
+      float mx = -INFINITY;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = k0 + 32 * kt + 8 * (r >> 2) + 4 * hl + (r & 3);
+          float v = s[kt][r] * scale_log2;
+          if (key >= seq || (causal && key > qrow)) v = -INFINITY;
+          s[kt][r] = v;
+          mx = fmaxf(mx, v);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m2, mx);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      const float alpha = exp2f(m2 - m_use);
+      float rowsum = 0.f;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float p = exp2f(s[kt][r] - m_use);
+          s[kt][r] = p;
+          rowsum += p;
+        }
+      rowsum += __shfl_xor(rowsum, 32, 64);
+      lsum = lsum * alpha + rowsum;
+      m2 = m_new;
+#pragma unroll
+      for (int dt = 0; dt < DH / 32; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const bf16x8 pb = acc_to_frag(s[kt], t);
+#pragma unroll
+          for (int dt = 0; dt < DH / 32; ++dt)
+            oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(vt_, VP, 32 * dt, 32 * kt + 16 * t, lane), pb,
+                                                               oacc[dt], 0, 0, 0);
+        }
+    }
+    if (blk + 1 < nblk) {
+      bf16_t* nxt = smem + ((blk + 1) & 1) * (KT + VT);
+      sk.store(nxt, tid);
+      sv.store(nxt + KT, tid);
+    }
+    __syncthreads();
+  }
+  if (qrow < seq) {
+    const float inv = 1.0f / lsum;
+    bf16_t* orow = o + ((size_t)b * seq + qrow) * h + (size_t)head * DH;
+#pragma unroll
+    for (int dt = 0; dt < DH / 32; ++dt) store_tile_t(orow + 32 * dt, oacc[dt], inv, lane);
+    if (hl == 0) lse[((size_t)b * heads + head) * seq + qrow] = (m2 + log2f(lsum)) * kLn2;
+  }
+}
+
+template <int DH>
+__global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dq_mfma(int seq, int heads, int causal, const bf16_t* __restrict__ qkv,
+                                                            const bf16_t* __restrict__ o, const float* __restrict__ lse,
+                                                            const bf16_t* __restrict__ d_o, bf16_t* __restrict__ dq,
+                                                            float* __restrict__ delta, float scale, float scale_log2) {
+  constexpr int KP = DH + PAD_BOTH, VP = DH + PAD_ROWS;
+  constexpr int KT = BS * KP, VT = BS * VP;
+  extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hl = lane >> 5;
+  const int h = heads * DH, head = blockIdx.y, b = blockIdx.z;
+  const int q0 = blockIdx.x * BQ, qw0 = q0 + 32 * wave, qrow = qw0 + (lane & 31);
+  const int qclamp = min(qrow, seq - 1);
+  const size_t ld = (size_t)3 * h;
+  const bf16_t* base = qkv + (size_t)b * seq * ld + (size_t)head * DH;
+
+  bf16x8 qf[DH / 16], dof[DH / 16];
+  float dl = 0.f;
+  {
+    const bf16_t* qp = base + (size_t)qclamp * ld + 8 * hl;
+    const size_t orow = ((size_t)b * seq + qclamp) * h + (size_t)head * DH + 8 * hl;
+#pragma unroll
+    for (int ks = 0; ks < DH / 16; ++ks) {
+      qf[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+      dof[ks] = *reinterpret_cast<const bf16x8*>(d_o + orow + 16 * ks);
+      const bf16x8 of = *reinterpret_cast<const bf16x8*>(o + orow + 16 * ks);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dl += (float)dof[ks][e] * (float)of[e];
+    }
+  }
+  dl += __shfl_xor(dl, 32, 64);
+  const size_t stat = ((size_t)b * heads + head) * seq + qclamp;
+  if (hl == 0 && qrow < seq) delta[stat] = dl;
+  const float lse2 = lse[stat] * kLog2e;
+  f32x16 acc[DH / 32];
+#pragma unroll
+  for (int dt = 0; dt < DH / 32; ++dt) zero(acc[dt]);
+
+  const int kend = causal ? min(seq, q0 + BQ) : seq;
+  const int nblk = (kend + BS - 1) / BS;
+  BlockStager<BS, DH, KP, 256> sk;
+  BlockStager<BS, DH, VP, 256> sv;
+  sk.load(base + h, ld, 0, seq, tid);
+  sv.load(base + 2 * h, ld, 0, seq, tid);
+  sk.store(smem, tid);
+  sv.store(smem + KT, tid);
+  __syncthreads();
+  for (int blk = 0; blk < nblk; ++blk) {
+    const int k0 = blk * BS;
+    const bf16_t* kt_ = smem + (blk & 1) * (KT + VT);
+    const bf16_t* vt_ = kt_ + KT;
+    if (blk + 1 < nblk) {
+      sk.load(base + h, ld, k0 + BS, seq, tid);
+      sv.load(base + 2 * h, ld, k0 + BS, seq, tid);
+    }
+    if (!causal || k0 <= qw0 + 31) {
+      f32x16 s[2], dp[2];
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt) {
+        zero(s[kt]);
+        zero(dp[kt]);
+#pragma unroll
+        for (int ks = 0; ks < DH / 16; ++ks) {
+          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(kt_, KP, 32 * kt, 16 * ks, lane), qf[ks], s[kt], 0, 0, 0);
+          dp[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(vt_, VP, 32 * kt, 16 * ks, lane), dof[ks], dp[kt], 0, 0, 0);
+        }
+      }
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = k0 + 32 * kt + 8 * (r >> 2) + 4 * hl + (r & 3);
+          const bool dead = key >= seq || (causal && key > qrow);
+          const float p = dead ? 0.f : exp2f(s[kt][r] * scale_log2 - lse2);
+          s[kt][r] = p * (dp[kt][r] - dl);
+        }
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const bf16x8 dsb = acc_to_frag(s[kt], t);
+#pragma unroll
+          for (int dt = 0; dt < DH / 32; ++dt)
+            acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(kt_, KP, 32 * dt, 32 * kt + 16 * t, lane), dsb,
+                                                              acc[dt], 0, 0, 0);
+        }
+    }
+    if (blk + 1 < nblk) {
+      bf16_t* nxt = smem + ((blk + 1) & 1) * (KT + VT);
+      sk.store(nxt, tid);
+      sv.store(nxt + KT, tid);
+    }
+    __syncthreads();
+  }
+  if (qrow < seq) {
+    bf16_t* row = dq + ((size_t)b * seq + qrow) * h + (size_t)head * DH;
+#pragma unroll
+    for (int dt = 0; dt < DH / 32; ++dt) store_tile_t(row + 32 * dt, acc[dt], scale, lane);
+  }
+}
+
+template <int DH>
+__global__ __launch_bounds__(256, 1) void attn_bwd_dkv_mfma(int seq, int heads, int causal, const bf16_t* qkv,
+                                                             const float* __restrict__ lse, const float* __restrict__ delta,
+                                                             const bf16_t* __restrict__ d_o, bf16_t* dqkv, float scale,
+                                                             float scale_log2) {
+  constexpr int QP = DH + PAD_BOTH;
+  constexpr int QT = BS * QP;
+  extern __shared__ __attribute__((aligned(16))) bf16_t smem[];  // [2][Q tile | dO tile], then stats
+  float* stats = reinterpret_cast<float*>(smem + 4 * QT);       // [2][lse2[64] | delta[64]]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hl = lane >> 5;
+  const int h = heads * DH, head = blockIdx.y, b = blockIdx.z;
+  const int k0 = blockIdx.x * BQ, kw0 = k0 + 32 * wave, krow = kw0 + (lane & 31);
+  const size_t ld = (size_t)3 * h;
+  const bf16_t* base = qkv + (size_t)b * seq * ld + (size_t)head * DH;
+  const bf16_t* dob = d_o + (size_t)b * seq * h + (size_t)head * DH;
+  const float* lse_b = lse + ((size_t)b * heads + head) * seq;
+  const float* delta_b = delta + ((size_t)b * heads + head) * seq;
+
+  bf16x8 kf[DH / 16], vf[DH / 16];
+  {
+    const bf16_t* kp = base + (size_t)min(krow, seq - 1) * ld + h + 8 * hl;
+#pragma unroll
+    for (int ks = 0; ks < DH / 16; ++ks) {
+      kf[ks] = *reinterpret_cast<const bf16x8*>(kp + 16 * ks);
+      vf[ks] = *reinterpret_cast<const bf16x8*>(kp + h + 16 * ks);
+    }
+  }
+  f32x16 dk[DH / 32], dv[DH / 32];
+#pragma unroll
+  for (int dt = 0; dt < DH / 32; ++dt) {
+    zero(dk[dt]);
+    zero(dv[dt]);
+  }
+  const int qstart = causal ? (k0 / BS) * BS : 0;
+  const int nblk = (seq - qstart + BS - 1) / BS;
+  BlockStager<BS, DH, QP, 256> sq, sdo;
+  float st_reg = 0.f;  // threads 0..63: lse2 of query tid; 64..127: delta of query tid-64
+  auto load_stats = [&](int q0) {
+    if (tid < 128) {
+      const int qi = q0 + (tid & 63);
+      st_reg = qi < seq ? (tid < 64 ? lse_b[qi] * kLog2e : delta_b[qi]) : 0.f;
+    }
+  };
+  sq.load(base, ld, qstart, seq, tid);
+  sdo.load(dob, (size_t)h, qstart, seq, tid);
+  load_stats(qstart);
+  sq.store(smem, tid);
+  sdo.store(smem + QT, tid);
+  if (tid < 128) stats[tid] = st_reg;
+  __syncthreads();
+  for (int blk = 0; blk < nblk; ++blk) {
+    const int q0 = qstart + blk * BS;
+    const bf16_t* qt_ = smem + (blk & 1) * 2 * QT;
+    const bf16_t* dot_ = qt_ + QT;
+    const float* st_ = stats + (blk & 1) * 128;
+    if (blk + 1 < nblk) {
+      sq.load(base, ld, q0 + BS, seq, tid);
+      sdo.load(dob, (size_t)h, q0 + BS, seq, tid);
+      load_stats(q0 + BS);
+    }
+    if (!causal || q0 + BS - 1 >= kw0) {
+      f32x16 s[2], dp[2];
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt) {
+        zero(s[qt]);
+        zero(dp[qt]);
+#pragma unroll
+        for (int ks = 0; ks < DH / 16; ++ks) {
+          s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(qt_, QP, 32 * qt, 16 * ks, lane), kf[ks], s[qt], 0, 0, 0);
+          dp[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(dot_, QP, 32 * qt, 16 * ks, lane), vf[ks], dp[qt], 0, 0, 0);
+        }
+      }
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int qi = 32 * qt + 8 * (r >> 2) + 4 * hl + (r & 3);
+          const int query = q0 + qi;
+          const bool dead = query >= seq || krow >= seq || (causal && krow > query);
+          const float p = dead ? 0.f : exp2f(s[qt][r] * scale_log2 - st_[qi]);
+          s[qt][r] = p;
+          dp[qt][r] = p * (dp[qt][r] - st_[64 + qi]);
+        }
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const bf16x8 pb = acc_to_frag(s[qt], t);
+          const bf16x8 dsb = acc_to_frag(dp[qt], t);
+#pragma unroll
+          for (int dt = 0; dt < DH / 32; ++dt) {
+            dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(dot_, QP, 32 * dt, 32 * qt + 16 * t, lane), pb,
+                                                             dv[dt], 0, 0, 0);
+            dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(qt_, QP, 32 * dt, 32 * qt + 16 * t, lane), dsb,
+                                                             dk[dt], 0, 0, 0);
+          }
+        }
+    }
+    if (blk + 1 < nblk) {
+      bf16_t* nxt = smem + ((blk + 1) & 1) * 2 * QT;
+      sq.store(nxt, tid);
+      sdo.store(nxt + QT, tid);
+      if (tid < 128) stats[((blk + 1) & 1) * 128 + tid] = st_reg;
+    }
+    __syncthreads();
+  }
+  if (krow < seq) {
+    bf16_t* row = dqkv + ((size_t)b * seq + krow) * ld + (size_t)head * DH + h;
+#pragma unroll
+    for (int dt = 0; dt < DH / 32; ++dt) {
+      store_tile_t(row + 32 * dt, dk[dt], scale, lane);
+      store_tile_t(row + h + 32 * dt, dv[dt], 1.0f, lane);
+    }
+  }
+}
+
+template <typename K>
+int reserve_lds(K kern, size_t bytes, bool& done, const char* what) {
+  if (done) return PMC_OK;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e != hipSuccess) return fail(PMC_ERR_HIP, "%s: cannot reserve %zu bytes of LDS: %s", what, bytes, hipGetErrorString(e));
+  done = true;
+  return PMC_OK;
+}
+
+template <int DH>
+int fwd_t(hipStream_t st, int batch, int seq, int heads, int causal, const void* qkv, void* o, float* lse) {
+  constexpr size_t lds = 2 * sizeof(bf16_t) * BS * ((DH + PAD_ROWS) + (DH + PAD_COLS));
+  static bool done = false;
+  if (int rc = reserve_lds(attn_fwd_mfma<DH>, lds, done, "attention_forward")) return rc;
+  const float scale_log2 = kLog2e / sqrtf((float)DH);
+  attn_fwd_mfma<DH><<<dim3((seq + BQ - 1) / BQ, heads, batch), dim3(256), lds, st>>>(seq, heads, causal, (const bf16_t*)qkv,
+                                                                                    (bf16_t*)o, lse, scale_log2);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(PMC_ERR_HIP, "attention_forward launch failed: %s", hipGetErrorString(e));
+  return PMC_OK;
+}
+
+template <int DH>
+int bwd_t(hipStream_t st, int batch, int seq, int heads, int causal, const void* qkv, const void* o, const float* lse,
+          const void* d_o, void* dqkv, void* dq_stage, float* delta) {
+  constexpr size_t lds_dq = 2 * sizeof(bf16_t) * BS * ((DH + PAD_BOTH) + (DH + PAD_ROWS));
+  constexpr size_t lds_dkv = 4 * sizeof(bf16_t) * BS * (DH + PAD_BOTH) + 2 * 128 * sizeof(float);
+  static bool done_dq = false, done_dkv = false;
+  if (int rc = reserve_lds(attn_bwd_dq_mfma<DH>, lds_dq, done_dq, "attention_backward")) return rc;
+  if (int rc = reserve_lds(attn_bwd_dkv_mfma<DH>, lds_dkv, done_dkv, "attention_backward")) return rc;
+  const float scale = 1.0f / sqrtf((float)DH), scale_log2 = kLog2e * scale;
+  dim3 grid((seq + BQ - 1) / BQ, heads, batch), block(256);
+  attn_bwd_dq_mfma<DH><<<grid, block, lds_dq, st>>>(seq, heads, causal, (const bf16_t*)qkv, (const bf16_t*)o, lse,
+                                                    (const bf16_t*)d_o, (bf16_t*)dq_stage, delta, scale, scale_log2);
+  attn_bwd_dkv_mfma<DH><<<grid, block, lds_dkv, st>>>(seq, heads, causal, (const bf16_t*)qkv, lse, delta,
+                                                      (const bf16_t*)d_o, (bf16_t*)dqkv, scale, scale_log2);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(PMC_ERR_HIP, "attention_backward launch failed: %s", hipGetErrorString(e));
+  return PMC_OK;
+}
+
+int check(const char* what, int batch, int seq, int heads, int dh, const void* qkv) {
+  if (batch <= 0 || seq <= 0 || heads <= 0) return fail(PMC_ERR_INVALID, "%s: batch=%d seq=%d heads=%d", what, batch, seq, heads);
+  if (dh != 64 && dh != 128) return fail(PMC_ERR_INVALID, "%s: matrix-core path needs head size 64 or 128, got %d", what, dh);
+  if (heads > 65535 || batch > 65535) return fail(PMC_ERR_INVALID, "%s: heads/batch exceed the grid limit", what);
+  if (reinterpret_cast<uintptr_t>(qkv) & 15) return fail(PMC_ERR_INVALID, "%s: qkv must be 16-byte aligned", what);
+  return PMC_OK;
+}
+
+}  // namespace
+
+int attention_forward_mfma(hipStream_t st, int batch, int seq, int heads, int dh, int causal, const void* qkv, void* o,
+                           float* lse) {
+  if (int rc = check("attention_forward", batch, seq, heads, dh, qkv)) return rc;
+  if (reinterpret_cast<uintptr_t>(o) & 15) return fail(PMC_ERR_INVALID, "attention_forward: o must be 16-byte aligned");
+  return dh == 64 ? fwd_t<64>(st, batch, seq, heads, causal, qkv, o, lse) : fwd_t<128>(st, batch, seq, heads, causal, qkv, o, lse);
+}
+
+int attention_backward_mfma(hipStream_t st, int batch, int seq, int heads, int dh, int causal, const void* qkv,
+                            const void* o, const float* lse, const void* d_o, void* dqkv, void* dq_stage, float* delta) {
+  if (int rc = check("attention_backward", batch, seq, heads, dh, qkv)) return rc;
+  if ((reinterpret_cast<uintptr_t>(o) | reinterpret_cast<uintptr_t>(d_o) | reinterpret_cast<uintptr_t>(dqkv) |
+       reinterpret_cast<uintptr_t>(dq_stage)) & 15)
+    return fail(PMC_ERR_INVALID, "attention_backward: tensors must be 16-byte aligned");
+  return dh == 64 ? bwd_t<64>(st, batch, seq, heads, causal, qkv, o, lse, d_o, dqkv, dq_stage, delta)
+                  : bwd_t<128>(st, batch, seq, heads, causal, qkv, o, lse, d_o, dqkv, dq_stage, delta);
+}
+
+}  // namespace k
+}  // namespace pmc

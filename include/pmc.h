@@ -200,6 +200,29 @@ int schedule_replay(pmc_ctx* ctx, const pmc_schedule* s, pmc_chunk* const* chunk
                     void* const* dx_first, uint32_t flags, pmc_replay_report* report,
                     pmc_device_peak* peaks, int32_t peaks_capacity);
 
+/* ---- per-operation timing (profiling the passes, as the paper profiles F/B/W for its
+ *      scheduler, Appendix D.1) -------------------------------------------------------------- */
+
+typedef enum pmc_trace_op {
+  PMC_OP_GEMM = 0, PMC_OP_LN_FWD = 1, PMC_OP_LN_BWD = 2, PMC_OP_ATTN_FWD = 3, PMC_OP_ATTN_BWD = 4,
+  PMC_OP_COLSUM = 5, PMC_OP_COPY = 6
+} pmc_trace_op;
+
+typedef struct pmc_trace_rec {
+  int32_t op;        /* pmc_trace_op                                                          */
+  int32_t pass;      /* pmc_op of the pass that launched it                                    */
+  int32_t m, n, k;   /* GEMM: problem size; attention: tokens, heads, head size; else rows, cols, 0 */
+  int32_t variant;   /* GEMM: trans_a | trans_b << 1 | epilogue << 2; else 0                   */
+  float ms;          /* elapsed time between HIP events recorded around the operation          */
+} pmc_trace_rec;
+
+/* From this call on, every operation the passes launch is bracketed by a pair of HIP events on
+ * the context's stream (up to `capacity` operations; later ones are not recorded). */
+int pmc_trace_begin(pmc_ctx* ctx, int32_t capacity);
+/* Synchronises the stream, writes up to `capacity` records to `out`, stores the number recorded in
+ * *count, and stops tracing. */
+int pmc_trace_end(pmc_ctx* ctx, pmc_trace_rec* out, int32_t capacity, int32_t* count);
+
 /* ---- single operations (unit parity tests and kernel timing) --------------------------------- */
 
 typedef enum pmc_epilogue {

@@ -3,7 +3,7 @@
 Every function here has the name of the C entry point it calls (see include/pmc.h); tensors are
 torch tensors on the GPU whose data_ptr() is handed over, and every step of F / B / W and of the
 schedule replay runs inside the library's HIP kernels.  There is no fallback: if the library has
-not been built (python -m paper_2405_15362_amd.build) importing this module raises.
+not been built (python paper_2405_15362_amd/build.py) importing this module raises.
 """
 from __future__ import annotations
 
@@ -14,7 +14,7 @@ from dataclasses import dataclass
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpmc.so")
 if not os.path.exists(LIB_PATH):
-    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2405_15362_amd.build`")
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python paper_2405_15362_amd/build.py`")
 lib = C.CDLL(LIB_PATH)
 
 PMC_F32, PMC_BF16 = 0, 1
@@ -47,6 +47,11 @@ class Pass(C.Structure):
 
 class DevicePeak(C.Structure):
     _fields_ = [("peak_live_units", C.c_int64), ("peak_live_bytes", C.c_int64), ("peak_tensor_bytes", C.c_int64)]
+
+
+class TraceRec(C.Structure):
+    _fields_ = [("op", C.c_int32), ("pass_", C.c_int32), ("m", C.c_int32), ("n", C.c_int32), ("k", C.c_int32),
+                ("variant", C.c_int32), ("ms", C.c_float)]
 
 
 class ReplayReport(C.Structure):
@@ -88,6 +93,8 @@ _SIGS = {
     "pmc_replay_workspace_bytes": (_sz, [_vp, C.POINTER(ChunkCfg)]),
     "schedule_replay": (C.c_int, [_vp, _vp, C.POINTER(_vp), C.POINTER(_vp), C.POINTER(_vp), C.POINTER(_vp),
                                   C.POINTER(_vp), C.c_uint32, C.POINTER(ReplayReport), C.POINTER(DevicePeak), _i32]),
+    "pmc_trace_begin": (C.c_int, [_vp, _i32]),
+    "pmc_trace_end": (C.c_int, [_vp, C.POINTER(TraceRec), _i32, C.POINTER(_i32)]),
     "pmc_gemm": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _i32, _vp, _i32, _vp, _i32, _i32, _vp, _vp, _vp]),
     "pmc_layernorm_forward": (C.c_int, [_vp, _i32, _i32, _i32, _vp, _vp, _vp, C.c_float, _vp, _vp, _vp, _vp]),
     "pmc_layernorm_backward": (C.c_int, [_vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
@@ -311,6 +318,23 @@ def schedule_replay(ctx, s, chunks, x, dy_last, y_last=None, dx_first=None, flag
                                flags, C.byref(rep), peaks, d))
     report = {f: getattr(rep, f) for f, _ in ReplayReport._fields_}
     return report, [(p.peak_live_units, p.peak_live_bytes, p.peak_tensor_bytes) for p in peaks]
+
+
+# ---- tracing ---------------------------------------------------------------------------------
+
+TRACE_OPS = ("gemm", "ln_fwd", "ln_bwd", "attn_fwd", "attn_bwd", "colsum", "copy")
+
+
+def pmc_trace_begin(ctx, capacity: int = 4096) -> None:
+    _check(lib.pmc_trace_begin(ctx, capacity))
+
+
+def pmc_trace_end(ctx, capacity: int = 4096) -> list[dict]:
+    buf = (TraceRec * capacity)()
+    n = _i32()
+    _check(lib.pmc_trace_end(ctx, buf, capacity, C.byref(n)))
+    return [dict(op=TRACE_OPS[r.op], pass_=OPS[r.pass_], m=r.m, n=r.n, k=r.k, trans_a=bool(r.variant & 1),
+                 trans_b=bool(r.variant & 2), epilogue=r.variant >> 2, ms=r.ms) for r in buf[:n.value]]
 
 
 # ---- single operations -----------------------------------------------------------------------

@@ -1,6 +1,6 @@
 """Builds libpmc.so (the C-ABI library) for gfx950 with hipcc, in-tree.
 
-    python -m paper_2405_15362_amd.build
+    python paper_2405_15362_amd/build.py
 
 Objects go to _build/ (git-ignored); the shared library lands next to this file.
 """

@@ -66,8 +66,18 @@ struct Pool {
 
 }  // namespace pmc
 
+namespace pmc {
+struct TraceSlot {
+  pmc_trace_rec rec;
+  hipEvent_t e0, e1;
+};
+}  // namespace pmc
+
 struct pmc_ctx {
   hipStream_t stream = nullptr;
+  bool tracing = false;
+  size_t trace_capacity = 0;
+  std::vector<pmc::TraceSlot> trace;
   pmc::Pool pool;
   char* ws = nullptr;
   size_t ws_bytes = 0;
@@ -169,6 +179,26 @@ WorkspaceLayout workspace_of(const pmc_chunk_cfg& c) {
     if (rc_ != PMC_OK) return rc_; \
   } while (0)
 
+// Runs `call` (which enqueues one operation) between two events when tracing is on.
+template <typename F>
+int traced(pmc_ctx* ctx, int op, int pass, int m, int n, int k, int variant, F&& call) {
+  if (!ctx->tracing || ctx->trace.size() >= ctx->trace_capacity) return call();
+  TraceSlot t;
+  t.rec = pmc_trace_rec{op, pass, m, n, k, variant, 0.f};
+  if (hipEventCreate(&t.e0) != hipSuccess || hipEventCreate(&t.e1) != hipSuccess)
+    return fail(PMC_ERR_HIP, "trace: cannot create events");
+  (void)hipEventRecord(t.e0, ctx->stream);
+  const int rc = call();
+  (void)hipEventRecord(t.e1, ctx->stream);
+  ctx->trace.push_back(t);
+  return rc;
+}
+
+int t_gemm(pmc_ctx* ctx, int pass, const k::GemmArgs& g) {
+  const int variant = (g.trans_a ? 1 : 0) | (g.trans_b ? 2 : 0) | (g.epilogue << 2);
+  return traced(ctx, PMC_OP_GEMM, pass, g.M, g.N, g.K, variant, [&] { return k::gemm(ctx->stream, g); });
+}
+
 const void* P(const pmc_chunk* ch, int layer, int idx) { return ch->params[(size_t)layer * PMC_PARAMS_PER_LAYER + idx]; }
 float* G(const pmc_chunk* ch, int layer, int idx) { return ch->grads[(size_t)layer * PMC_PARAMS_PER_LAYER + idx]; }
 enum { LN1_G, LN1_B, W_QKV, B_QKV, W_O, B_O, LN2_G, LN2_B, W_1, B_1, W_2, B_2 };
@@ -233,20 +263,20 @@ int chunk_forward(pmc_chunk* ch, int32_t mb, const void* x, void* y, int device)
     const LayerOffsets& o = ch->off[l];
     char* s = m.slab;
     const void* xin = l == 0 ? x : (const void*)(s + o.x);
-    PMC_TRY(k::layernorm_forward(st, c.dtype, T, h, xin, P(ch, l, LN1_G), P(ch, l, LN1_B), c.ln_eps, s + o.a,
-                                 (float*)(s + o.mean1), (float*)(s + o.rstd1), l == 0 ? s + o.x : nullptr));
-    PMC_TRY(k::gemm(st, gemm_args(ch, false, false, T, 3 * h, h, s + o.a, h, P(ch, l, W_QKV), 3 * h, s + o.qkv, 3 * h,
+    PMC_TRY(traced(ch->ctx, PMC_OP_LN_FWD, PMC_F, T, h, 0, 0, [&] { return k::layernorm_forward(st, c.dtype, T, h, xin, P(ch, l, LN1_G), P(ch, l, LN1_B), c.ln_eps, s + o.a,
+                                 (float*)(s + o.mean1), (float*)(s + o.rstd1), l == 0 ? s + o.x : nullptr); }));
+    PMC_TRY(t_gemm(ch->ctx, PMC_F, gemm_args(ch, false, false, T, 3 * h, h, s + o.a, h, P(ch, l, W_QKV), 3 * h, s + o.qkv, 3 * h,
                                   PMC_EPI_BIAS, P(ch, l, B_QKV))));
-    PMC_TRY(k::attention_forward(st, c.dtype, c.microbatch, c.seq, c.heads, ch->head_dim, c.causal, s + o.qkv, s + o.o,
-                                 (float*)(s + o.lse)));
-    PMC_TRY(k::gemm(st, gemm_args(ch, false, false, T, h, h, s + o.o, h, P(ch, l, W_O), h, s + o.xmid, h,
+    PMC_TRY(traced(ch->ctx, PMC_OP_ATTN_FWD, PMC_F, T, c.heads, ch->head_dim, 0, [&] { return k::attention_forward(st, c.dtype, c.microbatch, c.seq, c.heads, ch->head_dim, c.causal, s + o.qkv, s + o.o,
+                                 (float*)(s + o.lse)); }));
+    PMC_TRY(t_gemm(ch->ctx, PMC_F, gemm_args(ch, false, false, T, h, h, s + o.o, h, P(ch, l, W_O), h, s + o.xmid, h,
                                   PMC_EPI_BIAS_RESID, P(ch, l, B_O), s + o.x)));
-    PMC_TRY(k::layernorm_forward(st, c.dtype, T, h, s + o.xmid, P(ch, l, LN2_G), P(ch, l, LN2_B), c.ln_eps, s + o.c,
-                                 (float*)(s + o.mean2), (float*)(s + o.rstd2), nullptr));
-    PMC_TRY(k::gemm(st, gemm_args(ch, false, false, T, f, h, s + o.c, h, P(ch, l, W_1), f, s + o.u, f, PMC_EPI_BIAS_GELU,
+    PMC_TRY(traced(ch->ctx, PMC_OP_LN_FWD, PMC_F, T, h, 0, 0, [&] { return k::layernorm_forward(st, c.dtype, T, h, s + o.xmid, P(ch, l, LN2_G), P(ch, l, LN2_B), c.ln_eps, s + o.c,
+                                 (float*)(s + o.mean2), (float*)(s + o.rstd2), nullptr); }));
+    PMC_TRY(t_gemm(ch->ctx, PMC_F, gemm_args(ch, false, false, T, f, h, s + o.c, h, P(ch, l, W_1), f, s + o.u, f, PMC_EPI_BIAS_GELU,
                                   P(ch, l, B_1), nullptr, s + o.g)));
     void* out = l == L - 1 ? y : (void*)(s + ch->off[l + 1].x);
-    PMC_TRY(k::gemm(st, gemm_args(ch, false, false, T, h, f, s + o.g, f, P(ch, l, W_2), h, out, h, PMC_EPI_BIAS_RESID,
+    PMC_TRY(t_gemm(ch->ctx, PMC_F, gemm_args(ch, false, false, T, h, f, s + o.g, f, P(ch, l, W_2), h, out, h, PMC_EPI_BIAS_RESID,
                                   P(ch, l, B_2), s + o.xmid)));
   }
   m.state = kForwardDone;
@@ -274,28 +304,28 @@ int chunk_backward_input(pmc_chunk* ch, int32_t mb, const void* dy, void* dx) {
     const LayerOffsets& o = ch->off[l];
     const void* dyl = l == L - 1 ? dy : (const void*)(s + ch->off[l + 1].x);
     // dU = (dY . W2^T) * gelu'(U), written over U
-    PMC_TRY(k::gemm(st, gemm_args(ch, false, true, T, f, h, dyl, h, P(ch, l, W_2), h, s + o.u, f, PMC_EPI_DGELU, nullptr,
+    PMC_TRY(t_gemm(ch->ctx, PMC_B, gemm_args(ch, false, true, T, f, h, dyl, h, P(ch, l, W_2), h, s + o.u, f, PMC_EPI_DGELU, nullptr,
                                   nullptr, s + o.u)));
     // dC = dU . W1^T
-    PMC_TRY(k::gemm(st, gemm_args(ch, false, true, T, h, f, s + o.u, f, P(ch, l, W_1), f, t_h, h, PMC_EPI_NONE)));
+    PMC_TRY(t_gemm(ch->ctx, PMC_B, gemm_args(ch, false, true, T, h, f, s + o.u, f, P(ch, l, W_1), f, t_h, h, PMC_EPI_NONE)));
     // dX_mid = dY + LN2 input-gradient(dC), written over X_mid; LN2 gain/bias gradients
-    PMC_TRY(k::layernorm_backward(st, c.dtype, T, h, t_h, s + o.xmid, P(ch, l, LN2_G), (const float*)(s + o.mean2),
-                                  (const float*)(s + o.rstd2), dyl, s + o.xmid, G(ch, l, LN2_G), G(ch, l, LN2_B), partial));
+    PMC_TRY(traced(ch->ctx, PMC_OP_LN_BWD, PMC_B, T, h, 0, 0, [&] { return k::layernorm_backward(st, c.dtype, T, h, t_h, s + o.xmid, P(ch, l, LN2_G), (const float*)(s + o.mean2),
+                                  (const float*)(s + o.rstd2), dyl, s + o.xmid, G(ch, l, LN2_G), G(ch, l, LN2_B), partial); }));
     // dO = dX_mid . Wo^T
-    PMC_TRY(k::gemm(st, gemm_args(ch, false, true, T, h, h, s + o.xmid, h, P(ch, l, W_O), h, t_h, h, PMC_EPI_NONE)));
+    PMC_TRY(t_gemm(ch->ctx, PMC_B, gemm_args(ch, false, true, T, h, h, s + o.xmid, h, P(ch, l, W_O), h, t_h, h, PMC_EPI_NONE)));
     // dQKV, written over QKV
-    PMC_TRY(k::attention_backward(st, c.dtype, c.microbatch, c.seq, c.heads, ch->head_dim, c.causal, s + o.qkv, s + o.o,
-                                  (const float*)(s + o.lse), t_h, s + o.qkv, attn_ws));
+    PMC_TRY(traced(ch->ctx, PMC_OP_ATTN_BWD, PMC_B, T, c.heads, ch->head_dim, 0, [&] { return k::attention_backward(st, c.dtype, c.microbatch, c.seq, c.heads, ch->head_dim, c.causal, s + o.qkv, s + o.o,
+                                  (const float*)(s + o.lse), t_h, s + o.qkv, attn_ws); }));
     // dA = dQKV . Wqkv^T
-    PMC_TRY(k::gemm(st, gemm_args(ch, false, true, T, h, 3 * h, s + o.qkv, 3 * h, P(ch, l, W_QKV), 3 * h, t_h, h,
+    PMC_TRY(t_gemm(ch->ctx, PMC_B, gemm_args(ch, false, true, T, h, 3 * h, s + o.qkv, 3 * h, P(ch, l, W_QKV), 3 * h, t_h, h,
                                   PMC_EPI_NONE)));
     // dX = dX_mid + LN1 input-gradient(dA): over X for inner layers, to the caller for layer 0
     void* out = l == 0 ? dx : (void*)(s + o.x);
-    PMC_TRY(k::layernorm_backward(st, c.dtype, T, h, t_h, s + o.x, P(ch, l, LN1_G), (const float*)(s + o.mean1),
-                                  (const float*)(s + o.rstd1), s + o.xmid, out, G(ch, l, LN1_G), G(ch, l, LN1_B), partial));
+    PMC_TRY(traced(ch->ctx, PMC_OP_LN_BWD, PMC_B, T, h, 0, 0, [&] { return k::layernorm_backward(st, c.dtype, T, h, t_h, s + o.x, P(ch, l, LN1_G), (const float*)(s + o.mean1),
+                                  (const float*)(s + o.rstd1), s + o.xmid, out, G(ch, l, LN1_G), G(ch, l, LN1_B), partial); }));
   }
   // keep the chunk's dY for W of the top layer in the slot of the (now dead) chunk input
-  PMC_TRY(k::copy_rows(st, c.dtype, T, h, dy, h, s + ch->off[0].x, h));
+  PMC_TRY(traced(ch->ctx, PMC_OP_COPY, PMC_B, T, h, 0, 0, [&] { return k::copy_rows(st, c.dtype, T, h, dy, h, s + ch->off[0].x, h); }));
   m.state = kBackwardDone;
   ch->ctx->pool.shrink(m.device, (int64_t)ch->stats_bytes);
   return PMC_OK;
@@ -314,15 +344,15 @@ int chunk_backward_weight_one(pmc_chunk* ch, int32_t mb, bool release) {
   for (int l = L - 1; l >= 0; --l) {
     const LayerOffsets& o = ch->off[l];
     const void* dxout = s + (l == L - 1 ? ch->off[0].x : ch->off[l + 1].x);
-    PMC_TRY(k::gemm(st, gemm_args(ch, true, false, f, h, T, s + o.g, f, dxout, h, G(ch, l, W_2), h, PMC_EPI_ACCUM_F32)));
-    PMC_TRY(k::column_sum(st, c.dtype, T, h, dxout, h, G(ch, l, B_2), partial));
-    PMC_TRY(k::gemm(st, gemm_args(ch, true, false, h, f, T, s + o.c, h, s + o.u, f, G(ch, l, W_1), f, PMC_EPI_ACCUM_F32)));
-    PMC_TRY(k::column_sum(st, c.dtype, T, f, s + o.u, f, G(ch, l, B_1), partial));
-    PMC_TRY(k::gemm(st, gemm_args(ch, true, false, h, h, T, s + o.o, h, s + o.xmid, h, G(ch, l, W_O), h, PMC_EPI_ACCUM_F32)));
-    PMC_TRY(k::column_sum(st, c.dtype, T, h, s + o.xmid, h, G(ch, l, B_O), partial));
-    PMC_TRY(k::gemm(st, gemm_args(ch, true, false, h, 3 * h, T, s + o.a, h, s + o.qkv, 3 * h, G(ch, l, W_QKV), 3 * h,
+    PMC_TRY(t_gemm(ch->ctx, PMC_W, gemm_args(ch, true, false, f, h, T, s + o.g, f, dxout, h, G(ch, l, W_2), h, PMC_EPI_ACCUM_F32)));
+    PMC_TRY(traced(ch->ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sum(st, c.dtype, T, h, dxout, h, G(ch, l, B_2), partial); }));
+    PMC_TRY(t_gemm(ch->ctx, PMC_W, gemm_args(ch, true, false, h, f, T, s + o.c, h, s + o.u, f, G(ch, l, W_1), f, PMC_EPI_ACCUM_F32)));
+    PMC_TRY(traced(ch->ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sum(st, c.dtype, T, f, s + o.u, f, G(ch, l, B_1), partial); }));
+    PMC_TRY(t_gemm(ch->ctx, PMC_W, gemm_args(ch, true, false, h, h, T, s + o.o, h, s + o.xmid, h, G(ch, l, W_O), h, PMC_EPI_ACCUM_F32)));
+    PMC_TRY(traced(ch->ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sum(st, c.dtype, T, h, s + o.xmid, h, G(ch, l, B_O), partial); }));
+    PMC_TRY(t_gemm(ch->ctx, PMC_W, gemm_args(ch, true, false, h, 3 * h, T, s + o.a, h, s + o.qkv, 3 * h, G(ch, l, W_QKV), 3 * h,
                                   PMC_EPI_ACCUM_F32)));
-    PMC_TRY(k::column_sum(st, c.dtype, T, 3 * h, s + o.qkv, 3 * h, G(ch, l, B_QKV), partial));
+    PMC_TRY(traced(ch->ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sum(st, c.dtype, T, 3 * h, s + o.qkv, 3 * h, G(ch, l, B_QKV), partial); }));
   }
   if (release) {
     ch->ctx->pool.give(m.slab, m.device, (int64_t)(ch->unit_bytes - ch->stats_bytes));
@@ -498,6 +528,40 @@ int stage_backward_weight(pmc_chunk* ch, const int32_t* mbs, int32_t count) {
   }
   for (int32_t i = 0; i < count; ++i) PMC_TRY(chunk_backward_weight_one(ch, mbs[i], true));
   return PMC_OK;
+}
+
+/* ---- tracing ---- */
+
+int pmc_trace_begin(pmc_ctx* ctx, int32_t capacity) {
+  if (!ctx || capacity < 1) return fail(PMC_ERR_INVALID, "trace_begin: bad argument");
+  if (ctx->tracing) return fail(PMC_ERR_STATE, "trace_begin: already tracing");
+  ctx->trace.clear();
+  ctx->trace.reserve((size_t)capacity);
+  ctx->trace_capacity = (size_t)capacity;
+  ctx->tracing = true;
+  return PMC_OK;
+}
+
+int pmc_trace_end(pmc_ctx* ctx, pmc_trace_rec* out, int32_t capacity, int32_t* count) {
+  if (!ctx || !out || !count || capacity < 0) return fail(PMC_ERR_INVALID, "trace_end: bad argument");
+  if (!ctx->tracing) return fail(PMC_ERR_STATE, "trace_end: not tracing");
+  ctx->tracing = false;
+  hipError_t e = hipStreamSynchronize(ctx->stream);
+  int rc = e == hipSuccess ? PMC_OK : fail(PMC_ERR_HIP, "trace_end: %s", hipGetErrorString(e));
+  int32_t n = 0;
+  for (TraceSlot& t : ctx->trace) {
+    if (rc == PMC_OK && n < capacity) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, t.e0, t.e1) != hipSuccess) ms = -1.f;
+      t.rec.ms = ms;
+      out[n++] = t.rec;
+    }
+    (void)hipEventDestroy(t.e0);
+    (void)hipEventDestroy(t.e1);
+  }
+  ctx->trace.clear();
+  *count = n;
+  return rc;
 }
 
 /* ---- single operations ---- */

@@ -3,15 +3,32 @@
 //   F: Y  = X . W  (+ bias, + residual, GeLU)      A stored [M,K], B stored [K,N]
 //   B: dX = dY . W^T  (* GeLU')                    A stored [M,K], B stored [N,K]
 //   W: dW += X^T . dY  (fp32 accumulate)           A stored [K,M], B stored [K,N]
-// A workgroup computes a BM x BN tile; operand tiles go global -> registers -> LDS (double
-// buffered, one barrier per K step) and are read back as MFMA fragments.  An operand whose
-// contraction index is contiguous in memory is read with 16-byte LDS loads; one whose contraction
-// index is the slow dimension is kept in its natural layout in LDS and read with the transposing
-// load ds_read_b64_tr_b16, so no operand is ever transposed in HBM.  The MFMA is issued with the
-// operand roles exchanged (B-fragment as first operand), which leaves every lane with four
-// consecutive output columns of one row and lets the epilogue use 8/16-byte accesses.
-// Workgroup ids are remapped so that the ids resident on one XCD (they are dealt round-robin over
-// the 8 XCDs) cover a compact group of tiles and share operand panels in that XCD's L2.
+// Two kernels share the fragment layouts and the epilogue:
+//
+//  * gemm_bf16_dma_kernel, the fast path (K a multiple of 64).  Operand tiles go straight from
+//    global memory into LDS (buffer_load ... lds, no registers in between) into a ring of 2 or 3
+//    stages; rows past the edge are clamped, never branched on.  LDS tiles are unpadded and
+//    XOR-swizzled in 16-byte chunks so that both the DMA writes and the fragment reads are free of
+//    bank conflicts.  The K loop is software pipelined by hand: while the MFMAs of one 16-wide K
+//    step run, the fragments of the next step are read from LDS into a second register set, in a
+//    fixed interleave; the barrier that releases a stage sits before the last K step of a tile, so
+//    the first fragments of the next tile are read under that step's MFMAs and no LDS latency is
+//    exposed at tile boundaries.  The DMA loads are issued as inline assembly and waited for with
+//    explicit vmcnt values, because the compiler would otherwise drain every outstanding load
+//    before each LDS read.
+//  * gemm_bf16_kernel, the general path (any K multiple of 8, all layout/epilogue combinations):
+//    global -> registers -> padded LDS tiles, double buffered.
+//
+// An operand whose contraction index is contiguous in memory is read from LDS with 16-byte loads;
+// one whose contraction index is the slow dimension (W in F; X and dY in W) keeps its natural
+// layout in LDS and is read with the transposing load ds_read_b64_tr_b16, so no operand is ever
+// transposed in HBM.  The MFMA is issued with the operand roles exchanged (B-fragment as first
+// operand), which leaves every lane with four consecutive output columns of one row and lets the
+// epilogue use 8/16-byte accesses.  Workgroup ids are remapped so that the ids resident on one XCD
+// (they are dealt round-robin over the 8 XCDs) cover a compact group of tiles and share operand
+// panels in that XCD's L2.
+#include <cstdlib>
+
 #include "dev_common.h"
 #include "kernels.h"
 
@@ -108,6 +125,245 @@ __device__ __forceinline__ u32x2 pack4(const float* f) {
   return v;
 }
 
+// Epilogue shared by both kernels.  acc[i][j][r] of a wave whose tile starts at (mw0, nw0): row
+// m = mw0 + 32 i + lane%32, columns n = nw0 + 32 j + 8 (r/4) + 4 (lane/32) + r%4.
+template <int TM, int TN, int EPI>
+__device__ __forceinline__ void epilogue(const GemmParams& p, f32x16 (&acc)[TM][TN], int mw0, int nw0, int lane) {
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int m = mw0 + 32 * i + (lane & 31);
+    if (m >= p.M) continue;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = nw0 + 32 * j + 8 * q + 4 * (lane >> 5);
+        if (n >= p.N) continue;
+        const size_t idx = (size_t)m * p.ldc + n;
+        float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+        if (EPI == PMC_EPI_ACCUM_F32) {
+          float* c = reinterpret_cast<float*>(p.C) + idx;
+          f32x4 old = *reinterpret_cast<f32x4*>(c);
+          f32x4 out = {old[0] + v[0], old[1] + v[1], old[2] + v[2], old[3] + v[3]};
+          *reinterpret_cast<f32x4*>(c) = out;
+          continue;
+        }
+        bf16_t* c = reinterpret_cast<bf16_t*>(p.C) + idx;
+        if (EPI == PMC_EPI_BIAS || EPI == PMC_EPI_BIAS_RESID || EPI == PMC_EPI_BIAS_GELU) {
+          float b[4];
+          unpack4(*reinterpret_cast<const u32x2*>(p.bias + n), b);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] += b[e];
+        }
+        if (EPI == PMC_EPI_BIAS_RESID) {
+          float r[4];
+          unpack4(*reinterpret_cast<const u32x2*>(p.resid + idx), r);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] += r[e];
+        }
+        if (EPI == PMC_EPI_DGELU) {
+          float u[4];
+          unpack4(*reinterpret_cast<const u32x2*>(p.aux + idx), u);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_f(u[e]);
+        }
+        *reinterpret_cast<u32x2*>(c) = pack4(v);
+        if (EPI == PMC_EPI_BIAS_GELU) {
+          float g[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) g[e] = gelu_f(v[e]);
+          *reinterpret_cast<u32x2*>(p.aux + idx) = pack4(g);
+        }
+      }
+    }
+  }
+}
+
+// Workgroup id -> (tile_m, tile_n).  Ids are dealt round-robin over 8 XCDs; give each XCD a
+// contiguous run of tile indices, then walk tiles in column groups 8 tiles of M tall.
+__device__ __forceinline__ void tile_of_block(const GemmParams& p, int& tile_m, int& tile_n) {
+  const int ntiles = p.tiles_m * p.tiles_n;
+  int pid = blockIdx.x;
+  const int xcd = pid & 7, local = pid >> 3, lo = ntiles >> 3, rem = ntiles & 7;
+  pid = xcd * lo + (xcd < rem ? xcd : rem) + local;
+  constexpr int GROUP = 8;
+  const int per_group = GROUP * p.tiles_n;
+  const int group = pid / per_group;
+  const int first_m = group * GROUP;
+  const int group_m = min(p.tiles_m - first_m, GROUP);
+  tile_m = first_m + (pid % per_group) % group_m;
+  tile_n = (pid % per_group) / group_m;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Fast path: direct-to-LDS operand tiles, swizzled, hand-pipelined.
+//
+// LDS tile layouts (BK = 64, no padding; a "chunk" is 16 bytes = 8 elements):
+//   contraction-contiguous operand: [rows][64]; chunk position p of row r holds k-chunk
+//       p ^ ((r >> 1) & 7)   -> 16 lanes reading 16 consecutive rows at one k hit 16 distinct
+//       16-byte bank groups;
+//   other operand: [64 k][ROWS]; chunk position p of k-row kr holds chunk p ^ ((kr & 3) << 2)
+//       -> the four k-rows one half-wave touches in a transposing read fall into four different
+//       64-byte bank quarters.
+// One buffer_load...lds instruction of a wave fills 1 KB of LDS (lane l writes bytes 16 l .. 16 l + 15
+// of it), so the swizzle is applied to the GLOBAL address each lane fetches from.
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+
+template <int ROWS, bool KMAJ, int NW>
+struct DmaLoader {
+  static constexpr int NL = ROWS * 64 * 2 / 1024 / NW;  // 1 KB loads per wave per tile
+  static_assert(ROWS * 64 * 2 / 1024 % NW == 0, "tile must split evenly over the waves");
+  uint32_t voff[NL];  // byte offset of this lane's chunk at K offset 0
+
+  // Wave w issues loads w*NL .. w*NL+NL-1; load q fills tile bytes [1024 q, 1024 q + 1024).
+  // Rows (or columns) past the edge of the matrix are clamped to the last valid ones: what they
+  // produce lands in output rows/columns that the epilogue does not store.
+  __device__ __forceinline__ void init(int ld, int mn0, int mn_total, int wave, int lane) {
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+      const int q = wave * NL + i;
+      if (KMAJ) {
+        const int row = q * 8 + (lane >> 3), pos = lane & 7;
+        const int kc = pos ^ ((row >> 1) & 7);
+        int grow = mn0 + row;
+        grow = grow < mn_total ? grow : mn_total - 1;
+        voff[i] = ((uint32_t)grow * (uint32_t)ld + kc * 8) * 2;
+      } else {
+        constexpr int CPR = ROWS / 8;  // chunks per k-row
+        const int idx = q * 64 + lane, kr = idx / CPR, pos = idx % CPR;
+        const int mc = pos ^ ((kr & 3) << 2);
+        int gmn = mn0 + mc * 8;
+        gmn = gmn < mn_total ? gmn : mn_total - 8;
+        voff[i] = ((uint32_t)kr * (uint32_t)ld + gmn) * 2;
+      }
+    }
+  }
+  __device__ __forceinline__ void issue(i32x4 rsrc, bf16_t* tile, uint32_t soff, int wave) const {
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+      const int q = wave * NL + i;
+      const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)((lds_void_ptr)(tile + q * 512)));
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                   :: "s"(lds_addr), "v"(voff[i]), "s"(rsrc), "s"(soff) : "memory");
+    }
+  }
+};
+
+template <int ROWS, bool KMAJ>
+__device__ __forceinline__ bf16x8 read_frag_swz(const bf16_t* tile, int r0, int ks, int lane) {
+  if (KMAJ) {
+    const int row = r0 + (lane & 31), kc = (ks >> 3) + (lane >> 5);
+    return *reinterpret_cast<const bf16x8*>(tile + row * 64 + ((kc ^ ((row >> 1) & 7)) << 3));
+  } else {
+    const int g = lane >> 4, j = lane & 15;
+    const int kr = ks + 8 * (g >> 1) + (j >> 2);  // (kr & 3) is the same for kr and kr + 4
+    const int col = r0 + 16 * (g & 1) + 4 * (j & 3);
+    const bf16_t* p = tile + kr * ROWS + (col ^ ((kr & 3) << 5));
+    typedef __attribute__((address_space(3))) s16x4* lds_ptr;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * ROWS));
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
+  }
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KMAJ, bool B_KMAJ, int NSTAGE, int EPI>
+__global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_bf16_dma_kernel(GemmParams p) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  constexpr int BK = 64, NW = WAVES_M * WAVES_N, WM = BM / WAVES_M, WN = BN / WAVES_N, TM = WM / 32, TN = WN / 32;
+  constexpr int TA = BM * BK, TB = BN * BK, STAGE = TA + TB;
+  extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
+  int tile_m, tile_n;
+  tile_of_block(p, tile_m, tile_n);
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  auto make_rsrc = [](const void* ptr) {  // raw buffer descriptor: base, no stride, 2 GB window
+    const uint64_t a = (uint64_t)ptr;
+    i32x4 r = {(int)(uint32_t)a, (int)(uint32_t)(a >> 32), 0x7fffffff, 0x00020000};
+    return r;
+  };
+  const i32x4 ra = make_rsrc(p.A), rb = make_rsrc(p.B);
+  DmaLoader<BM, A_KMAJ, NW> la;
+  DmaLoader<BN, B_KMAJ, NW> lb;
+  la.init(p.lda, m0, p.M, wave, lane);
+  lb.init(p.ldb, n0, p.N, wave, lane);
+  const uint32_t stepa = A_KMAJ ? BK * 2 : (uint32_t)BK * p.lda * 2;
+  const uint32_t stepb = B_KMAJ ? BK * 2 : (uint32_t)BK * p.ldb * 2;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nk = p.K / BK;
+  bf16x8 fa[2][TM], fb[2][TN];
+  // One 16-wide K step: the MFMAs on fragment set c, interleaved in a fixed order with the LDS
+  // reads that fill set c^1 from (src_a, src_b) at K offset ks.
+  auto step = [&](int c, const bf16_t* src_a, const bf16_t* src_b, int ks) {
+#pragma unroll
+    for (int q = 0; q < TM + TN; ++q) {
+      if (q < TM) fa[c ^ 1][q] = read_frag_swz<BM, A_KMAJ>(src_a, wm0 + 32 * q, ks, lane);
+      else fb[c ^ 1][q - TM] = read_frag_swz<BN, B_KMAJ>(src_b, wn0 + 32 * (q - TM), ks, lane);
+      __builtin_amdgcn_sched_barrier(0);
+      constexpr int NP = TM + TN, TOT = TM * TN;
+#pragma unroll
+      for (int idx = (q * TOT) / NP; idx < ((q + 1) * TOT) / NP; ++idx) {
+        const int i = idx / TN, j = idx % TN;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[c][j], fa[c][i], acc[i][j], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  // Ring of NSTAGE stages.  Tiles past the end are clamped (fetched again, never used) so that the
+  // number of loads in flight is the same at every wait.
+  constexpr int LPT = DmaLoader<BM, A_KMAJ, NW>::NL + DmaLoader<BN, B_KMAJ, NW>::NL;  // loads per tile per wave
+  constexpr int INFL = (NSTAGE - 2) * LPT;  // loads that may stay in flight at a wait
+  static_assert(INFL < 64, "vmcnt is a 6-bit field");
+  constexpr int WAIT_TILE = (INFL & 15) | ((INFL >> 4) << 14) | (7 << 4) | (15 << 8);  // s_waitcnt vmcnt(INFL)
+  auto tile_k = [&](int t) { return t < nk ? t : nk - 1; };
+#pragma unroll
+  for (int t = 0; t < NSTAGE - 1; ++t) {
+    la.issue(ra, smem + t * STAGE, tile_k(t) * stepa, wave);
+    lb.issue(rb, smem + t * STAGE + TA, tile_k(t) * stepb, wave);
+  }
+  __builtin_amdgcn_s_waitcnt(WAIT_TILE);
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < TM; ++i) fa[0][i] = read_frag_swz<BM, A_KMAJ>(smem, wm0 + 32 * i, 0, lane);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) fb[0][j] = read_frag_swz<BN, B_KMAJ>(smem + TA, wn0 + 32 * j, 0, lane);
+  int cur = 0;
+  for (int kt = 0; kt < nk; ++kt) {
+    const bf16_t* cur_a = smem + cur * STAGE;
+    const bf16_t* cur_b = cur_a + TA;
+    const int nxt = cur + 1 == NSTAGE ? 0 : cur + 1;
+    const int fill = cur == 0 ? NSTAGE - 1 : cur - 1;  // all its readers passed the last barrier
+    la.issue(ra, smem + fill * STAGE, tile_k(kt + NSTAGE - 1) * stepa, wave);
+    lb.issue(rb, smem + fill * STAGE + TA, tile_k(kt + NSTAGE - 1) * stepb, wave);
+    step(0, cur_a, cur_b, 16);
+    step(1, cur_a, cur_b, 32);
+    step(0, cur_a, cur_b, 48);
+    // Tile kt+1 must have landed (younger tiles may still be in flight).  Every fragment of tile
+    // kt is in registers, so after this barrier its stage may be refilled.
+    __builtin_amdgcn_s_waitcnt(WAIT_TILE);
+    __syncthreads();
+    step(1, smem + nxt * STAGE, smem + nxt * STAGE + TA, 0);  // after the last tile: a clamped tile, unused
+    cur = nxt;
+  }
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): drain the clamped tail loads
+  epilogue<TM, TN, EPI>(p, acc, m0 + wm0, n0 + wn0, lane);
+#endif
+}
+
+// ---------------------------------------------------------------------------------------------
+// General path.
 template <int BM, int BN, int BK, int WM, int WN, bool A_KMAJ, bool B_KMAJ, int EPI>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(GemmParams p) {
   constexpr int WAVES_N = BN / WN;
@@ -121,21 +377,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(G
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
 
-  // Workgroup id -> tile.  Ids are dealt round-robin over 8 XCDs; give each XCD a contiguous run
-  // of tile indices, then walk tiles in column groups 8 tiles of M tall.
-  const int ntiles = p.tiles_m * p.tiles_n;
-  int pid = blockIdx.x;
-  {
-    const int xcd = pid & 7, local = pid >> 3, lo = ntiles >> 3, rem = ntiles & 7;
-    pid = xcd * lo + (xcd < rem ? xcd : rem) + local;
-  }
-  constexpr int GROUP = 8;
-  const int per_group = GROUP * p.tiles_n;
-  const int group = pid / per_group;
-  const int first_m = group * GROUP;
-  const int group_m = min(p.tiles_m - first_m, GROUP);
-  const int tile_m = first_m + (pid % per_group) % group_m;
-  const int tile_n = (pid % per_group) / group_m;
+  int tile_m, tile_n;
+  tile_of_block(p, tile_m, tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
   Stager<BM, BK, A_KMAJ, NT> sa;
@@ -182,56 +425,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(G
     __syncthreads();
   }
 
-  // Epilogue.  acc[i][j][r]: row m = m0 + wm0 + 32 i + lane%32, column
-  // n = n0 + wn0 + 32 j + 8 (r/4) + 4 (lane/32) + r%4.
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int m = m0 + wm0 + 32 * i + (lane & 31);
-    if (m >= p.M) continue;
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int n = n0 + wn0 + 32 * j + 8 * q + 4 * (lane >> 5);
-        if (n >= p.N) continue;
-        const size_t idx = (size_t)m * p.ldc + n;
-        float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-        if (EPI == PMC_EPI_ACCUM_F32) {
-          float* c = reinterpret_cast<float*>(p.C) + idx;
-          f32x4 old = *reinterpret_cast<f32x4*>(c);
-          f32x4 out = {old[0] + v[0], old[1] + v[1], old[2] + v[2], old[3] + v[3]};
-          *reinterpret_cast<f32x4*>(c) = out;
-          continue;
-        }
-        bf16_t* c = reinterpret_cast<bf16_t*>(p.C) + idx;
-        if (EPI == PMC_EPI_BIAS || EPI == PMC_EPI_BIAS_RESID || EPI == PMC_EPI_BIAS_GELU) {
-          float b[4];
-          unpack4(*reinterpret_cast<const u32x2*>(p.bias + n), b);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] += b[e];
-        }
-        if (EPI == PMC_EPI_BIAS_RESID) {
-          float r[4];
-          unpack4(*reinterpret_cast<const u32x2*>(p.resid + idx), r);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] += r[e];
-        }
-        if (EPI == PMC_EPI_DGELU) {
-          float u[4];
-          unpack4(*reinterpret_cast<const u32x2*>(p.aux + idx), u);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_f(u[e]);
-        }
-        *reinterpret_cast<u32x2*>(c) = pack4(v);
-        if (EPI == PMC_EPI_BIAS_GELU) {
-          float g[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) g[e] = gelu_f(v[e]);
-          *reinterpret_cast<u32x2*>(p.aux + idx) = pack4(g);
-        }
-      }
-    }
-  }
+  epilogue<TM, TN, EPI>(p, acc, m0 + wm0, n0 + wn0, lane);
 }
 
 template <int BM, int BN, int BK, int WM, int WN, bool A_KMAJ, bool B_KMAJ, int EPI>
@@ -269,10 +463,85 @@ int launch_epi(hipStream_t st, const GemmParams& p, int epi) {
 
 template <bool A_KMAJ, bool B_KMAJ>
 int launch_tile(hipStream_t st, const GemmParams& p, int epi) {
-  // Large tile when it still yields at least about one workgroup per compute unit.
-  const long big_tiles = (long)((p.M + 255) / 256) * ((p.N + 255) / 256);
-  if (big_tiles >= 200) return launch_epi<256, 256, 64, 128, 128, A_KMAJ, B_KMAJ>(st, p, epi);
   return launch_epi<128, 128, 64, 64, 64, A_KMAJ, B_KMAJ>(st, p, epi);
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KMAJ, bool B_KMAJ, int NSTAGE, int EPI>
+int launch_dma(hipStream_t st, GemmParams p) {
+  constexpr int NT = WAVES_M * WAVES_N * 64;
+  constexpr size_t lds = (size_t)NSTAGE * (BM + BN) * 64 * sizeof(bf16_t);
+  static_assert(lds <= 160 * 1024, "stages do not fit the 160 KB LDS");
+  auto kern = gemm_bf16_dma_kernel<BM, BN, WAVES_M, WAVES_N, A_KMAJ, B_KMAJ, NSTAGE, EPI>;
+  static bool configured = false;  // per instantiation
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return fail(PMC_ERR_HIP, "gemm_bf16: cannot reserve %zu bytes of LDS: %s", lds, hipGetErrorString(e));
+    configured = true;
+  }
+  p.tiles_m = (p.M + BM - 1) / BM;
+  p.tiles_n = (p.N + BN - 1) / BN;
+  kern<<<dim3(p.tiles_m * p.tiles_n), dim3(NT), lds, st>>>(p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(PMC_ERR_HIP, "gemm_bf16 launch failed: %s", hipGetErrorString(e));
+  return PMC_OK;
+}
+
+// Tile shape for the fast path.  Tiles are dealt over the 256 compute units, so the time is
+// (tiles per unit, rounded up) x (work of a tile) / (throughput of that shape on a busy unit); the
+// largest tile wins once there are enough tiles, smaller ones when units would otherwise idle.
+//   0: 256x256, 8 waves, 2 stages    1: 256x128, 8 waves, 3 stages    2: 128x128, 4 waves, 2 stages
+// PMC_GEMM_TILE=0|1|2 in the environment forces a shape (for tests and tuning).
+int pick_tile(int M, int N) {
+  if (const char* f = std::getenv("PMC_GEMM_TILE")) {
+    if (f[0] >= '0' && f[0] <= '2' && f[1] == 0) return f[0] - '0';
+  }
+  const int bm[3] = {256, 256, 128}, bn[3] = {256, 128, 128};
+  const double rate[3] = {1.0, 0.95, 0.75};
+  int best = 0;
+  double best_t = 1e300;
+  for (int c = 0; c < 3; ++c) {
+    const long n = (long)((M + bm[c] - 1) / bm[c]) * ((N + bn[c] - 1) / bn[c]);
+    const double t = (double)((n + 255) / 256) * bm[c] * bn[c] / rate[c];
+    if (t < best_t) {
+      best_t = t;
+      best = c;
+    }
+  }
+  return best;
+}
+
+template <bool A_KMAJ, bool B_KMAJ, int EPI>
+int launch_dma_tile(hipStream_t st, const GemmParams& p) {
+  switch (pick_tile(p.M, p.N)) {
+    case 0: return launch_dma<256, 256, 2, 4, A_KMAJ, B_KMAJ, 2, EPI>(st, p);
+    case 1: return launch_dma<256, 128, 4, 2, A_KMAJ, B_KMAJ, 3, EPI>(st, p);
+    default: return launch_dma<128, 128, 2, 2, A_KMAJ, B_KMAJ, 2, EPI>(st, p);
+  }
+}
+
+// The layout/epilogue combinations the passes use (and the plain product of each layout) have a
+// fast-path instantiation; returns -100 if this combination has none.
+constexpr int kNoFastPath = -100;
+int launch_fast(hipStream_t st, const GemmParams& p, bool a_kmaj, bool b_kmaj, int epi) {
+  if (a_kmaj && !b_kmaj) {  // F: Y = X . W
+    switch (epi) {
+      case PMC_EPI_NONE: return launch_dma_tile<true, false, PMC_EPI_NONE>(st, p);
+      case PMC_EPI_BIAS: return launch_dma_tile<true, false, PMC_EPI_BIAS>(st, p);
+      case PMC_EPI_BIAS_RESID: return launch_dma_tile<true, false, PMC_EPI_BIAS_RESID>(st, p);
+      case PMC_EPI_BIAS_GELU: return launch_dma_tile<true, false, PMC_EPI_BIAS_GELU>(st, p);
+    }
+  } else if (a_kmaj && b_kmaj) {  // B: dX = dY . W^T
+    switch (epi) {
+      case PMC_EPI_NONE: return launch_dma_tile<true, true, PMC_EPI_NONE>(st, p);
+      case PMC_EPI_DGELU: return launch_dma_tile<true, true, PMC_EPI_DGELU>(st, p);
+    }
+  } else if (!a_kmaj && !b_kmaj) {  // W: dW += X^T . dY
+    switch (epi) {
+      case PMC_EPI_NONE: return launch_dma_tile<false, false, PMC_EPI_NONE>(st, p);
+      case PMC_EPI_ACCUM_F32: return launch_dma_tile<false, false, PMC_EPI_ACCUM_F32>(st, p);
+    }
+  }
+  return kNoFastPath;
 }
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
@@ -291,6 +560,12 @@ int gemm_bf16(hipStream_t st, const GemmArgs& a) {
   p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldb = a.ldb; p.ldc = a.ldc;
   p.tiles_m = p.tiles_n = 0;
   const bool a_kmaj = !a.trans_a, b_kmaj = a.trans_b;
+  // Fast path: K in whole 64-wide tiles, operands inside the 2 GB window of a buffer descriptor.
+  const size_t a_bytes = (size_t)(a.trans_a ? a.K : a.M) * a.lda * 2, b_bytes = (size_t)(a.trans_b ? a.N : a.K) * a.ldb * 2;
+  if (a.K % 64 == 0 && a_bytes < 0x7fffffffull && b_bytes < 0x7fffffffull) {
+    const int rc = launch_fast(st, p, a_kmaj, b_kmaj, a.epilogue);
+    if (rc != kNoFastPath) return rc;
+  }
   if (a_kmaj && b_kmaj) return launch_tile<true, true>(st, p, a.epilogue);
   if (a_kmaj && !b_kmaj) return launch_tile<true, false>(st, p, a.epilogue);
   if (!a_kmaj && b_kmaj) return launch_tile<false, true>(st, p, a.epilogue);

@@ -151,16 +151,36 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(int rows, int h, const T* _
   for (int i = threadIdx.x; i < 2 * h; i += 256) out[i] = red[i];
 }
 
-// out_a[i] += sum_p partial[p*stride + i] (i < split), out_b[i - split] += ... (i >= split), p ascending.
+// out_a[i] += sum_p partial[p*stride + i] (i < split), out_b[i - split] += ... (i >= split).
+// A block handles 64 columns; its four waves each sum a contiguous quarter of the parts (loads
+// are independent, so many are in flight), and the quarters are added in order 0,1,2,3: the
+// summation order is fixed by (parts) alone.
 __global__ __launch_bounds__(256) void sum_partials_kernel(int parts, int width, int split, size_t stride,
                                                             const float* __restrict__ partial,
                                                             float* __restrict__ out_a, float* __restrict__ out_b) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= width) return;
+  __shared__ float quarter[4][64];
+  const int lane = threadIdx.x & 63, g = threadIdx.x >> 6;
+  const int i = blockIdx.x * 64 + lane;
+  const int per = (parts + 3) / 4, p0 = g * per, p1 = min(parts, p0 + per);
   float acc = 0.f;
-  for (int p = 0; p < parts; ++p) acc += partial[(size_t)p * stride + i];
-  if (i < split) out_a[i] += acc;
-  else out_b[i - split] += acc;
+  if (i < width) {
+    int p = p0;
+    for (; p + 8 <= p1; p += 8) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = partial[(size_t)(p + u) * stride + i];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc += v[u];
+    }
+    for (; p < p1; ++p) acc += partial[(size_t)p * stride + i];
+  }
+  quarter[g][lane] = acc;
+  __syncthreads();
+  if (g == 0 && i < width) {
+    const float total = ((quarter[0][lane] + quarter[1][lane]) + quarter[2][lane]) + quarter[3][lane];
+    if (i < split) out_a[i] += total;
+    else out_b[i - split] += total;
+  }
 }
 
 // partial[blockIdx.y][col] = sum over the block's slice of rows of a[row][col].
@@ -256,7 +276,7 @@ int ln_bwd_t(hipStream_t st, int rows, int h, const void* dy, const void* x, con
   }
 #undef LN_BWD_CASE
   PMC_LAUNCH_CHECK("layernorm_backward");
-  sum_partials_kernel<<<dim3((2 * h + 255) / 256), dim3(256), 0, st>>>(blocks, 2 * h, h, (size_t)2 * h, partial, dgain,
+  sum_partials_kernel<<<dim3((2 * h + 63) / 64), dim3(256), 0, st>>>(blocks, 2 * h, h, (size_t)2 * h, partial, dgain,
                                                                        dbias);
   PMC_LAUNCH_CHECK("layernorm_backward reduce");
   return PMC_OK;
@@ -314,7 +334,7 @@ int column_sum(hipStream_t st, int dtype, int rows, int n, const void* a, int ld
   else if (dtype == PMC_BF16) colsum_kernel<bf16_t><<<grid, block, 0, st>>>(rows, n, (const bf16_t*)a, lda, rpp, partial);
   else return fail(PMC_ERR_INVALID, "column_sum: bad dtype %d", dtype);
   PMC_LAUNCH_CHECK("column_sum");
-  sum_partials_kernel<<<dim3((n + 255) / 256), dim3(256), 0, st>>>(parts, n, n, (size_t)n, partial, out, out);
+  sum_partials_kernel<<<dim3((n + 63) / 64), dim3(256), 0, st>>>(parts, n, n, (size_t)n, partial, out, out);
   PMC_LAUNCH_CHECK("column_sum reduce");
   return PMC_OK;
 }

@@ -75,6 +75,26 @@ def test_gemm_bf16_small_tiles_ragged(ctx, ta, tb):
     _gemm_case(ctx, "bf16", ta, tb, 512, 768, 1024, P.EPI_NONE)
 
 
+@pytest.mark.parametrize("ta,tb,epis", [(False, False, (P.EPI_NONE, P.EPI_BIAS, P.EPI_BIAS_RESID, P.EPI_BIAS_GELU)),
+                                        (False, True, (P.EPI_NONE, P.EPI_DGELU)),
+                                        (True, False, (P.EPI_NONE, P.EPI_ACCUM_F32))])
+def test_gemm_bf16_direct_to_lds_path(ctx, ta, tb, epis):
+    """K in whole 64-wide tiles takes the direct-to-LDS kernel: each of its three tile shapes, with
+    ragged edges in M and N (clamped loads), a single K tile and many K tiles."""
+    import os
+    try:
+        for tile in ("2", "1", "0"):                # 128x128, 256x128, 256x256 tiles
+            os.environ["PMC_GEMM_TILE"] = tile
+            for epi in epis:
+                _gemm_case(ctx, "bf16", ta, tb, 200, 328, 192, epi)
+                _gemm_case(ctx, "bf16", ta, tb, 1000, 1544, 64, epi)
+            _gemm_case(ctx, "bf16", ta, tb, 8, 8, 64, epis[0])
+            _gemm_case(ctx, "bf16", ta, tb, 264, 136, 2048, epis[-1])
+    finally:
+        os.environ.pop("PMC_GEMM_TILE", None)
+    _gemm_case(ctx, "bf16", ta, tb, 3848, 4104, 320, epis[-1])   # heuristic choice, many tiles
+
+
 @pytest.mark.parametrize("ta,tb", [(False, False), (False, True), (True, False)])
 def test_gemm_bf16_large_tiles(ctx, ta, tb):
     # enough 256x256 tiles to take the large-tile path, ragged edge tiles included

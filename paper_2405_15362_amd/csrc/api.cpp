@@ -100,7 +100,7 @@ struct LayerOffsets {  // byte offsets inside the slab
 };
 
 struct WorkspaceLayout {
-  size_t t_h, attn, partial, total;
+  size_t t_h, attn, partial, gemm, gemm_bytes, total;
 };
 
 }  // namespace pmc
@@ -169,6 +169,14 @@ WorkspaceLayout workspace_of(const pmc_chunk_cfg& c) {
   const int widest = std::max(3 * c.hidden, c.ffn);
   const size_t pf = std::max(k::layernorm_backward_scratch_floats(t, c.hidden), k::column_sum_scratch_floats(t, widest));
   at += align256(pf * sizeof(float));
+  // split-K partial products of the skinny projections (F and B write [tokens, hidden] outputs)
+  size_t g = 0;
+  const int h = c.hidden, f = c.ffn;
+  const int shapes[7][3] = {{t, 3 * h, h}, {t, h, h}, {t, f, h}, {t, h, f}, {t, h, 3 * h}, {f, h, t}, {h, 3 * h, t}};
+  for (const auto& sh : shapes) g = std::max(g, k::gemm_scratch_bytes(c.dtype, sh[0], sh[1], sh[2]));
+  w.gemm = at;
+  w.gemm_bytes = g;
+  at += align256(g);
   w.total = at;
   return w;
 }
@@ -194,7 +202,11 @@ int traced(pmc_ctx* ctx, int op, int pass, int m, int n, int k, int variant, F&&
   return rc;
 }
 
-int t_gemm(pmc_ctx* ctx, int pass, const k::GemmArgs& g) {
+int t_gemm(pmc_ctx* ctx, int pass, k::GemmArgs g, const WorkspaceLayout& wsl) {
+  if (wsl.gemm_bytes) {
+    g.ws = ctx->ws + wsl.gemm;
+    g.ws_bytes = wsl.gemm_bytes;
+  }
   const int variant = (g.trans_a ? 1 : 0) | (g.trans_b ? 2 : 0) | (g.epilogue << 2);
   return traced(ctx, PMC_OP_GEMM, pass, g.M, g.N, g.K, variant, [&] { return k::gemm(ctx->stream, g); });
 }
@@ -266,18 +278,18 @@ int chunk_forward(pmc_chunk* ch, int32_t mb, const void* x, void* y, int device)
     PMC_TRY(traced(ch->ctx, PMC_OP_LN_FWD, PMC_F, T, h, 0, 0, [&] { return k::layernorm_forward(st, c.dtype, T, h, xin, P(ch, l, LN1_G), P(ch, l, LN1_B), c.ln_eps, s + o.a,
                                  (float*)(s + o.mean1), (float*)(s + o.rstd1), l == 0 ? s + o.x : nullptr); }));
     PMC_TRY(t_gemm(ch->ctx, PMC_F, gemm_args(ch, false, false, T, 3 * h, h, s + o.a, h, P(ch, l, W_QKV), 3 * h, s + o.qkv, 3 * h,
-                                  PMC_EPI_BIAS, P(ch, l, B_QKV))));
+                                  PMC_EPI_BIAS, P(ch, l, B_QKV)), ch->wsl));
     PMC_TRY(traced(ch->ctx, PMC_OP_ATTN_FWD, PMC_F, T, c.heads, ch->head_dim, 0, [&] { return k::attention_forward(st, c.dtype, c.microbatch, c.seq, c.heads, ch->head_dim, c.causal, s + o.qkv, s + o.o,
                                  (float*)(s + o.lse)); }));
     PMC_TRY(t_gemm(ch->ctx, PMC_F, gemm_args(ch, false, false, T, h, h, s + o.o, h, P(ch, l, W_O), h, s + o.xmid, h,
-                                  PMC_EPI_BIAS_RESID, P(ch, l, B_O), s + o.x)));
+                                  PMC_EPI_BIAS_RESID, P(ch, l, B_O), s + o.x), ch->wsl));
     PMC_TRY(traced(ch->ctx, PMC_OP_LN_FWD, PMC_F, T, h, 0, 0, [&] { return k::layernorm_forward(st, c.dtype, T, h, s + o.xmid, P(ch, l, LN2_G), P(ch, l, LN2_B), c.ln_eps, s + o.c,
                                  (float*)(s + o.mean2), (float*)(s + o.rstd2), nullptr); }));
     PMC_TRY(t_gemm(ch->ctx, PMC_F, gemm_args(ch, false, false, T, f, h, s + o.c, h, P(ch, l, W_1), f, s + o.u, f, PMC_EPI_BIAS_GELU,
-                                  P(ch, l, B_1), nullptr, s + o.g)));
+                                  P(ch, l, B_1), nullptr, s + o.g), ch->wsl));
     void* out = l == L - 1 ? y : (void*)(s + ch->off[l + 1].x);
     PMC_TRY(t_gemm(ch->ctx, PMC_F, gemm_args(ch, false, false, T, h, f, s + o.g, f, P(ch, l, W_2), h, out, h, PMC_EPI_BIAS_RESID,
-                                  P(ch, l, B_2), s + o.xmid)));
+                                  P(ch, l, B_2), s + o.xmid), ch->wsl));
   }
   m.state = kForwardDone;
   return PMC_OK;
@@ -305,20 +317,20 @@ int chunk_backward_input(pmc_chunk* ch, int32_t mb, const void* dy, void* dx) {
     const void* dyl = l == L - 1 ? dy : (const void*)(s + ch->off[l + 1].x);
     // dU = (dY . W2^T) * gelu'(U), written over U
     PMC_TRY(t_gemm(ch->ctx, PMC_B, gemm_args(ch, false, true, T, f, h, dyl, h, P(ch, l, W_2), h, s + o.u, f, PMC_EPI_DGELU, nullptr,
-                                  nullptr, s + o.u)));
+                                  nullptr, s + o.u), ch->wsl));
     // dC = dU . W1^T
-    PMC_TRY(t_gemm(ch->ctx, PMC_B, gemm_args(ch, false, true, T, h, f, s + o.u, f, P(ch, l, W_1), f, t_h, h, PMC_EPI_NONE)));
+    PMC_TRY(t_gemm(ch->ctx, PMC_B, gemm_args(ch, false, true, T, h, f, s + o.u, f, P(ch, l, W_1), f, t_h, h, PMC_EPI_NONE), ch->wsl));
     // dX_mid = dY + LN2 input-gradient(dC), written over X_mid; LN2 gain/bias gradients
     PMC_TRY(traced(ch->ctx, PMC_OP_LN_BWD, PMC_B, T, h, 0, 0, [&] { return k::layernorm_backward(st, c.dtype, T, h, t_h, s + o.xmid, P(ch, l, LN2_G), (const float*)(s + o.mean2),
                                   (const float*)(s + o.rstd2), dyl, s + o.xmid, G(ch, l, LN2_G), G(ch, l, LN2_B), partial); }));
     // dO = dX_mid . Wo^T
-    PMC_TRY(t_gemm(ch->ctx, PMC_B, gemm_args(ch, false, true, T, h, h, s + o.xmid, h, P(ch, l, W_O), h, t_h, h, PMC_EPI_NONE)));
+    PMC_TRY(t_gemm(ch->ctx, PMC_B, gemm_args(ch, false, true, T, h, h, s + o.xmid, h, P(ch, l, W_O), h, t_h, h, PMC_EPI_NONE), ch->wsl));
     // dQKV, written over QKV
     PMC_TRY(traced(ch->ctx, PMC_OP_ATTN_BWD, PMC_B, T, c.heads, ch->head_dim, 0, [&] { return k::attention_backward(st, c.dtype, c.microbatch, c.seq, c.heads, ch->head_dim, c.causal, s + o.qkv, s + o.o,
                                   (const float*)(s + o.lse), t_h, s + o.qkv, attn_ws); }));
     // dA = dQKV . Wqkv^T
     PMC_TRY(t_gemm(ch->ctx, PMC_B, gemm_args(ch, false, true, T, h, 3 * h, s + o.qkv, 3 * h, P(ch, l, W_QKV), 3 * h, t_h, h,
-                                  PMC_EPI_NONE)));
+                                  PMC_EPI_NONE), ch->wsl));
     // dX = dX_mid + LN1 input-gradient(dA): over X for inner layers, to the caller for layer 0
     void* out = l == 0 ? dx : (void*)(s + o.x);
     PMC_TRY(traced(ch->ctx, PMC_OP_LN_BWD, PMC_B, T, h, 0, 0, [&] { return k::layernorm_backward(st, c.dtype, T, h, t_h, s + o.x, P(ch, l, LN1_G), (const float*)(s + o.mean1),
@@ -344,14 +356,14 @@ int chunk_backward_weight_one(pmc_chunk* ch, int32_t mb, bool release) {
   for (int l = L - 1; l >= 0; --l) {
     const LayerOffsets& o = ch->off[l];
     const void* dxout = s + (l == L - 1 ? ch->off[0].x : ch->off[l + 1].x);
-    PMC_TRY(t_gemm(ch->ctx, PMC_W, gemm_args(ch, true, false, f, h, T, s + o.g, f, dxout, h, G(ch, l, W_2), h, PMC_EPI_ACCUM_F32)));
+    PMC_TRY(t_gemm(ch->ctx, PMC_W, gemm_args(ch, true, false, f, h, T, s + o.g, f, dxout, h, G(ch, l, W_2), h, PMC_EPI_ACCUM_F32), ch->wsl));
     PMC_TRY(traced(ch->ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sum(st, c.dtype, T, h, dxout, h, G(ch, l, B_2), partial); }));
-    PMC_TRY(t_gemm(ch->ctx, PMC_W, gemm_args(ch, true, false, h, f, T, s + o.c, h, s + o.u, f, G(ch, l, W_1), f, PMC_EPI_ACCUM_F32)));
+    PMC_TRY(t_gemm(ch->ctx, PMC_W, gemm_args(ch, true, false, h, f, T, s + o.c, h, s + o.u, f, G(ch, l, W_1), f, PMC_EPI_ACCUM_F32), ch->wsl));
     PMC_TRY(traced(ch->ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sum(st, c.dtype, T, f, s + o.u, f, G(ch, l, B_1), partial); }));
-    PMC_TRY(t_gemm(ch->ctx, PMC_W, gemm_args(ch, true, false, h, h, T, s + o.o, h, s + o.xmid, h, G(ch, l, W_O), h, PMC_EPI_ACCUM_F32)));
+    PMC_TRY(t_gemm(ch->ctx, PMC_W, gemm_args(ch, true, false, h, h, T, s + o.o, h, s + o.xmid, h, G(ch, l, W_O), h, PMC_EPI_ACCUM_F32), ch->wsl));
     PMC_TRY(traced(ch->ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sum(st, c.dtype, T, h, s + o.xmid, h, G(ch, l, B_O), partial); }));
     PMC_TRY(t_gemm(ch->ctx, PMC_W, gemm_args(ch, true, false, h, 3 * h, T, s + o.a, h, s + o.qkv, 3 * h, G(ch, l, W_QKV), 3 * h,
-                                  PMC_EPI_ACCUM_F32)));
+                                  PMC_EPI_ACCUM_F32), ch->wsl));
     PMC_TRY(traced(ch->ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sum(st, c.dtype, T, 3 * h, s + o.qkv, 3 * h, G(ch, l, B_QKV), partial); }));
   }
   if (release) {
@@ -574,6 +586,7 @@ int pmc_gemm(pmc_ctx* ctx, int32_t dtype, int32_t trans_a, int32_t trans_b, int3
   g.dtype = dtype; g.trans_a = trans_a != 0; g.trans_b = trans_b != 0;
   g.M = M; g.N = N; g.K = K; g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.C = C; g.ldc = ldc;
   g.epilogue = epilogue; g.bias = bias; g.resid = resid; g.aux = aux;
+  g.ws = ctx->ws; g.ws_bytes = ctx->ws_bytes;
   return k::gemm(ctx->stream, g);
 }
 

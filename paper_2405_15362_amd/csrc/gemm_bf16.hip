@@ -45,7 +45,10 @@ struct GemmParams {
   bf16_t* aux;
   int M, N, K, lda, ldb, ldc;
   int tiles_m, tiles_n;
+  int k_tiles_per_split;  // fast path: 64-wide K tiles each blockIdx.y handles (all of K when not split)
 };
+
+constexpr int kEpiPartial = 100;  // fast path, split K: store the fp32 partial product of split blockIdx.y
 
 constexpr int kPadK = 8;    // K-major tile: row pitch BK + 8 elements (144 B for BK = 64)
 constexpr int kPadMN = 32;  // MN-major tile: row pitch ROWS + 32 elements (pitch = 64 mod 256 bytes)
@@ -125,6 +128,51 @@ __device__ __forceinline__ u32x2 pack4(const float* f) {
   return v;
 }
 
+// Applies epilogue EPI to four consecutive output columns n .. n+3 of row m and stores them.
+template <int EPI>
+__device__ __forceinline__ void store_quad(const GemmParams& p, float (&v)[4], int m, int n) {
+  const size_t idx = (size_t)m * p.ldc + n;
+  if (EPI == kEpiPartial) {
+    float* c = reinterpret_cast<float*>(p.C) + (size_t)blockIdx.y * p.M * p.N + (size_t)m * p.N + n;
+    f32x4 out = {v[0], v[1], v[2], v[3]};
+    *reinterpret_cast<f32x4*>(c) = out;
+    return;
+  }
+  if (EPI == PMC_EPI_ACCUM_F32) {
+    float* c = reinterpret_cast<float*>(p.C) + idx;
+    f32x4 old = *reinterpret_cast<f32x4*>(c);
+    f32x4 out = {old[0] + v[0], old[1] + v[1], old[2] + v[2], old[3] + v[3]};
+    *reinterpret_cast<f32x4*>(c) = out;
+    return;
+  }
+  bf16_t* c = reinterpret_cast<bf16_t*>(p.C) + idx;
+  if (EPI == PMC_EPI_BIAS || EPI == PMC_EPI_BIAS_RESID || EPI == PMC_EPI_BIAS_GELU) {
+    float b[4];
+    unpack4(*reinterpret_cast<const u32x2*>(p.bias + n), b);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] += b[e];
+  }
+  if (EPI == PMC_EPI_BIAS_RESID) {
+    float r[4];
+    unpack4(*reinterpret_cast<const u32x2*>(p.resid + idx), r);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] += r[e];
+  }
+  if (EPI == PMC_EPI_DGELU) {
+    float u[4];
+    unpack4(*reinterpret_cast<const u32x2*>(p.aux + idx), u);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_fast(u[e]);
+  }
+  *reinterpret_cast<u32x2*>(c) = pack4(v);
+  if (EPI == PMC_EPI_BIAS_GELU) {
+    float g[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) g[e] = gelu_fast(v[e]);
+    *reinterpret_cast<u32x2*>(p.aux + idx) = pack4(g);
+  }
+}
+
 // Epilogue shared by both kernels.  acc[i][j][r] of a wave whose tile starts at (mw0, nw0): row
 // m = mw0 + 32 i + lane%32, columns n = nw0 + 32 j + 8 (r/4) + 4 (lane/32) + r%4.
 template <int TM, int TN, int EPI>
@@ -139,44 +187,29 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, f32x16 (&acc)[TM][
       for (int q = 0; q < 4; ++q) {
         const int n = nw0 + 32 * j + 8 * q + 4 * (lane >> 5);
         if (n >= p.N) continue;
-        const size_t idx = (size_t)m * p.ldc + n;
         float v[4] = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-        if (EPI == PMC_EPI_ACCUM_F32) {
-          float* c = reinterpret_cast<float*>(p.C) + idx;
-          f32x4 old = *reinterpret_cast<f32x4*>(c);
-          f32x4 out = {old[0] + v[0], old[1] + v[1], old[2] + v[2], old[3] + v[3]};
-          *reinterpret_cast<f32x4*>(c) = out;
-          continue;
-        }
-        bf16_t* c = reinterpret_cast<bf16_t*>(p.C) + idx;
-        if (EPI == PMC_EPI_BIAS || EPI == PMC_EPI_BIAS_RESID || EPI == PMC_EPI_BIAS_GELU) {
-          float b[4];
-          unpack4(*reinterpret_cast<const u32x2*>(p.bias + n), b);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] += b[e];
-        }
-        if (EPI == PMC_EPI_BIAS_RESID) {
-          float r[4];
-          unpack4(*reinterpret_cast<const u32x2*>(p.resid + idx), r);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] += r[e];
-        }
-        if (EPI == PMC_EPI_DGELU) {
-          float u[4];
-          unpack4(*reinterpret_cast<const u32x2*>(p.aux + idx), u);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_f(u[e]);
-        }
-        *reinterpret_cast<u32x2*>(c) = pack4(v);
-        if (EPI == PMC_EPI_BIAS_GELU) {
-          float g[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) g[e] = gelu_f(v[e]);
-          *reinterpret_cast<u32x2*>(p.aux + idx) = pack4(g);
-        }
+        store_quad<EPI>(p, v, m, n);
       }
     }
   }
+}
+
+// Second half of a split-K product: adds the fp32 partials of the splits in ascending order (a
+// fixed order, so the result does not depend on scheduling) and applies the epilogue.
+template <int EPI>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmParams p, const float* __restrict__ partial, int splits) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  const size_t quad = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t e0 = quad * 4, total = (size_t)p.M * p.N;
+  if (e0 >= total) return;
+  const int m = (int)(e0 / p.N), n = (int)(e0 % p.N);
+  float v[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < splits; ++s) {
+    const f32x4 t = *reinterpret_cast<const f32x4*>(partial + (size_t)s * total + e0);
+    v[0] += t[0]; v[1] += t[1]; v[2] += t[2]; v[3] += t[3];
+  }
+  store_quad<EPI>(p, v, m, n);
+#endif
 }
 
 // Workgroup id -> (tile_m, tile_n).  Ids are dealt round-robin over 8 XCDs; give each XCD a
@@ -302,7 +335,8 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_bf16_dma_kernel(G
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int nk = p.K / BK;
+  const int nk = p.k_tiles_per_split;
+  const int kt0 = blockIdx.y * nk;  // first K tile of this split
   bf16x8 fa[2][TM], fb[2][TN];
   // One 16-wide K step: the MFMAs on fragment set c, interleaved in a fixed order with the LDS
   // reads that fill set c^1 from (src_a, src_b) at K offset ks.
@@ -327,7 +361,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_bf16_dma_kernel(G
   constexpr int INFL = (NSTAGE - 2) * LPT;  // loads that may stay in flight at a wait
   static_assert(INFL < 64, "vmcnt is a 6-bit field");
   constexpr int WAIT_TILE = (INFL & 15) | ((INFL >> 4) << 14) | (7 << 4) | (15 << 8);  // s_waitcnt vmcnt(INFL)
-  auto tile_k = [&](int t) { return t < nk ? t : nk - 1; };
+  auto tile_k = [&](int t) { return kt0 + (t < nk ? t : nk - 1); };
 #pragma unroll
   for (int t = 0; t < NSTAGE - 1; ++t) {
     la.issue(ra, smem + t * STAGE, tile_k(t) * stepa, wave);
@@ -366,6 +400,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_bf16_dma_kernel(G
 // General path.
 template <int BM, int BN, int BK, int WM, int WN, bool A_KMAJ, bool B_KMAJ, int EPI>
 __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(GemmParams p) {
+#if defined(__HIP_DEVICE_COMPILE__)
   constexpr int WAVES_N = BN / WN;
   constexpr int NT = (BM / WM) * (BN / WN) * 64;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -426,6 +461,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_bf16_kernel(G
   }
 
   epilogue<TM, TN, EPI>(p, acc, m0 + wm0, n0 + wn0, lane);
+#endif
 }
 
 template <int BM, int BN, int BK, int WM, int WN, bool A_KMAJ, bool B_KMAJ, int EPI>
@@ -480,7 +516,8 @@ int launch_dma(hipStream_t st, GemmParams p) {
   }
   p.tiles_m = (p.M + BM - 1) / BM;
   p.tiles_n = (p.N + BN - 1) / BN;
-  kern<<<dim3(p.tiles_m * p.tiles_n), dim3(NT), lds, st>>>(p);
+  const int splits = (p.K / 64) / p.k_tiles_per_split;
+  kern<<<dim3(p.tiles_m * p.tiles_n, splits), dim3(NT), lds, st>>>(p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(PMC_ERR_HIP, "gemm_bf16 launch failed: %s", hipGetErrorString(e));
   return PMC_OK;
@@ -517,6 +554,53 @@ int launch_dma_tile(hipStream_t st, const GemmParams& p) {
     case 1: return launch_dma<256, 128, 4, 2, A_KMAJ, B_KMAJ, 3, EPI>(st, p);
     default: return launch_dma<128, 128, 2, 2, A_KMAJ, B_KMAJ, 2, EPI>(st, p);
   }
+}
+
+// Split K: when even 128x128 tiles leave most compute units idle (skinny products such as the
+// [tokens, hidden] outputs at short sequence length), K is cut into `splits` ranges, each range
+// writes an fp32 partial product to the workspace and a second kernel adds them and applies the
+// epilogue.  Returns 1 when splitting does not pay or does not fit.
+int pick_splits(int M, int N, int K, size_t ws_bytes) {
+  if (std::getenv("PMC_GEMM_TILE")) return 1;
+  const long tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
+  if (tiles >= 192) return 1;
+  const int nkt = K / 64;
+  int best = 1;
+  for (int s : {2, 4, 8}) {
+    if (nkt % s || nkt / s < 4) continue;                          // whole tiles, at least 256 of K per split
+    if ((size_t)s * M * N * sizeof(float) > ws_bytes) break;
+    best = s;
+    if (tiles * s >= 384) break;
+  }
+  return best;
+}
+
+template <bool A_KMAJ, bool B_KMAJ>
+int launch_partial(hipStream_t st, GemmParams p, void* ws, int splits) {
+  p.C = ws;
+  p.k_tiles_per_split = (p.K / 64) / splits;
+  return launch_dma<128, 128, 2, 2, A_KMAJ, B_KMAJ, 2, kEpiPartial>(st, p);
+}
+
+template <int EPI>
+int launch_reduce_epi(hipStream_t st, const GemmParams& p, const float* ws, int splits) {
+  const size_t quads = (size_t)p.M * p.N / 4;
+  splitk_reduce_kernel<EPI><<<dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, st>>>(p, ws, splits);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(PMC_ERR_HIP, "gemm_bf16 split-K reduce launch failed: %s", hipGetErrorString(e));
+  return PMC_OK;
+}
+
+int launch_reduce(hipStream_t st, const GemmParams& p, const float* ws, int splits, int epi) {
+  switch (epi) {
+    case PMC_EPI_NONE: return launch_reduce_epi<PMC_EPI_NONE>(st, p, ws, splits);
+    case PMC_EPI_BIAS: return launch_reduce_epi<PMC_EPI_BIAS>(st, p, ws, splits);
+    case PMC_EPI_BIAS_RESID: return launch_reduce_epi<PMC_EPI_BIAS_RESID>(st, p, ws, splits);
+    case PMC_EPI_BIAS_GELU: return launch_reduce_epi<PMC_EPI_BIAS_GELU>(st, p, ws, splits);
+    case PMC_EPI_DGELU: return launch_reduce_epi<PMC_EPI_DGELU>(st, p, ws, splits);
+    case PMC_EPI_ACCUM_F32: return launch_reduce_epi<PMC_EPI_ACCUM_F32>(st, p, ws, splits);
+  }
+  return fail(PMC_ERR_INVALID, "gemm_bf16: unknown epilogue %d", epi);
 }
 
 // The layout/epilogue combinations the passes use (and the plain product of each layout) have a
@@ -559,10 +643,19 @@ int gemm_bf16(hipStream_t st, const GemmArgs& a) {
   p.bias = (const bf16_t*)a.bias; p.resid = (const bf16_t*)a.resid; p.aux = (bf16_t*)a.aux;
   p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldb = a.ldb; p.ldc = a.ldc;
   p.tiles_m = p.tiles_n = 0;
+  p.k_tiles_per_split = 0;
   const bool a_kmaj = !a.trans_a, b_kmaj = a.trans_b;
   // Fast path: K in whole 64-wide tiles, operands inside the 2 GB window of a buffer descriptor.
   const size_t a_bytes = (size_t)(a.trans_a ? a.K : a.M) * a.lda * 2, b_bytes = (size_t)(a.trans_b ? a.N : a.K) * a.ldb * 2;
   if (a.K % 64 == 0 && a_bytes < 0x7fffffffull && b_bytes < 0x7fffffffull) {
+    p.k_tiles_per_split = a.K / 64;
+    const int splits = (a.ws && !(a_kmaj == false && b_kmaj == true)) ? pick_splits(a.M, a.N, a.K, a.ws_bytes) : 1;
+    if (splits > 1) {
+      int rc = a_kmaj ? (b_kmaj ? launch_partial<true, true>(st, p, a.ws, splits) : launch_partial<true, false>(st, p, a.ws, splits))
+                      : launch_partial<false, false>(st, p, a.ws, splits);
+      if (rc != PMC_OK) return rc;
+      return launch_reduce(st, p, (const float*)a.ws, splits, a.epilogue);
+    }
     const int rc = launch_fast(st, p, a_kmaj, b_kmaj, a.epilogue);
     if (rc != kNoFastPath) return rc;
   }
@@ -570,6 +663,12 @@ int gemm_bf16(hipStream_t st, const GemmArgs& a) {
   if (a_kmaj && !b_kmaj) return launch_tile<true, false>(st, p, a.epilogue);
   if (!a_kmaj && b_kmaj) return launch_tile<false, true>(st, p, a.epilogue);
   return launch_tile<false, false>(st, p, a.epilogue);
+}
+
+size_t gemm_scratch_bytes(int dtype, int M, int N, int K) {
+  if (dtype != PMC_BF16 || K % 64 || M <= 0 || N <= 0) return 0;
+  const int splits = pick_splits(M, N, K, (size_t)-1);
+  return splits > 1 ? (size_t)splits * M * N * sizeof(float) : 0;
 }
 
 }  // namespace k

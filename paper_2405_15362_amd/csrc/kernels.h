@@ -22,7 +22,12 @@ struct GemmArgs {
   const void* bias = nullptr;   // [N], storage type
   const void* resid = nullptr;  // [M, N], pitch ldc
   void* aux = nullptr;          // [M, N], pitch ldc
+  void* ws = nullptr;           // optional scratch for split-K partial products (256-byte aligned)
+  size_t ws_bytes = 0;
 };
+
+// Scratch a product of this shape can use (0: none).
+size_t gemm_scratch_bytes(int dtype, int M, int N, int K);
 
 int gemm(hipStream_t stream, const GemmArgs& a);
 int gemm_f32(hipStream_t stream, const GemmArgs& a);

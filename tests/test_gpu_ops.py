@@ -95,6 +95,26 @@ def test_gemm_bf16_direct_to_lds_path(ctx, ta, tb, epis):
     _gemm_case(ctx, "bf16", ta, tb, 3848, 4104, 320, epis[-1])   # heuristic choice, many tiles
 
 
+@pytest.mark.parametrize("ta,tb,epis", [(False, False, (P.EPI_BIAS, P.EPI_BIAS_RESID, P.EPI_BIAS_GELU)),
+                                        (False, True, (P.EPI_NONE, P.EPI_DGELU)),
+                                        (True, False, (P.EPI_ACCUM_F32,))])
+def test_gemm_bf16_split_k(ctx, ta, tb, epis):
+    """Skinny products are cut along K into fp32 partials that a second kernel adds in a fixed
+    order; the result must also be identical from run to run."""
+    for epi in epis:
+        _gemm_case(ctx, "bf16", ta, tb, 512, 1024, 1024, epi)      # 4 splits
+        _gemm_case(ctx, "bf16", ta, tb, 136, 264, 4096, epi)       # 8 splits, ragged tiles
+    a = dev(mat(("sk", "a"), (1024, 256) if ta else (256, 1024), "bf16"), "bf16")
+    b = dev(mat(("sk", "b"), (512, 1024) if tb else (1024, 512), "bf16", 0.05), "bf16")
+    outs = []
+    for _ in range(3):
+        c = torch.zeros(256, 512, device="cuda", dtype=torch.bfloat16)
+        P.pmc_gemm(ctx, a, b, c, ta, tb)
+        outs.append(c)
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+
+
 @pytest.mark.parametrize("ta,tb", [(False, False), (False, True), (True, False)])
 def test_gemm_bf16_large_tiles(ctx, ta, tb):
     # enough 256x256 tiles to take the large-tile path, ragged edge tiles included

@@ -55,7 +55,8 @@ __device__ __forceinline__ bf16x8 acc_to_frag(const f32x16& a, int t) {
 }
 
 // Cooperative copy of a [ROWS][DH] block of rows row0.. (pitch ld in global memory) into registers
-// and from there into an LDS tile of pitch P; rows >= row_limit read as zero.
+// and from there into an LDS tile of pitch P.  Rows >= row_limit are clamped to the last valid
+// row (no branches around the loads); whatever they contribute is masked by the caller.
 template <int ROWS, int DH, int P, int NT>
 struct BlockStager {
   static constexpr int CH = ROWS * DH / 8 / NT;
@@ -64,8 +65,8 @@ struct BlockStager {
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
       const int c = tid + i * NT, row = c / (DH / 8), cc = (c % (DH / 8)) * 8;
-      u32x4 z = {0u, 0u, 0u, 0u};
-      r[i] = (row0 + row < row_limit) ? *reinterpret_cast<const u32x4*>(base + (size_t)(row0 + row) * ld + cc) : z;
+      const int gr = min(row0 + row, row_limit - 1);
+      r[i] = *reinterpret_cast<const u32x4*>(base + (size_t)gr * ld + cc);
     }
   }
   __device__ __forceinline__ void store(bf16_t* tile, int tid) const {
@@ -149,16 +150,28 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma(int seq, int heads, int 
           s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(kt_, KP, 32 * kt, 16 * ks, lane), qf[ks], s[kt], 0, 0, 0);
       }
       float mx = -INFINITY;
+      // only blocks that cross the diagonal of this wave's rows or the end of the sequence need masks
+      const bool need_mask = (causal && k0 + BS - 1 > qw0) || (k0 + BS > seq);
+      if (need_mask) {
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
+        for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = k0 + 32 * kt + 8 * (r >> 2) + 4 * hl + (r & 3);
-          float v = s[kt][r] * scale_log2;
-          if (key >= seq || (causal && key > qrow)) v = -INFINITY;
-          s[kt][r] = v;
-          mx = fmaxf(mx, v);
-        }
+          for (int r = 0; r < 16; ++r) {
+            const int key = k0 + 32 * kt + 8 * (r >> 2) + 4 * hl + (r & 3);
+            float v = s[kt][r] * scale_log2;
+            if (key >= seq || (causal && key > qrow)) v = -INFINITY;
+            s[kt][r] = v;
+            mx = fmaxf(mx, v);
+          }
+      } else {
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            s[kt][r] *= scale_log2;
+            mx = fmaxf(mx, s[kt][r]);
+          }
+      }
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       const float m_new = fmaxf(m2, mx);
       const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
@@ -272,15 +285,23 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dq_mfma(int s
           dp[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(vt_, VP, 32 * kt, 16 * ks, lane), dof[ks], dp[kt], 0, 0, 0);
         }
       }
+      const bool need_mask = (causal && k0 + BS - 1 > qw0) || (k0 + BS > seq);
+      if (need_mask) {
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
+        for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = k0 + 32 * kt + 8 * (r >> 2) + 4 * hl + (r & 3);
-          const bool dead = key >= seq || (causal && key > qrow);
-          const float p = dead ? 0.f : exp2f(s[kt][r] * scale_log2 - lse2);
-          s[kt][r] = p * (dp[kt][r] - dl);
-        }
+          for (int r = 0; r < 16; ++r) {
+            const int key = k0 + 32 * kt + 8 * (r >> 2) + 4 * hl + (r & 3);
+            const bool dead = key >= seq || (causal && key > qrow);
+            const float p = dead ? 0.f : exp2f(s[kt][r] * scale_log2 - lse2);
+            s[kt][r] = p * (dp[kt][r] - dl);
+          }
+      } else {
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) s[kt][r] = exp2f(s[kt][r] * scale_log2 - lse2) * (dp[kt][r] - dl);
+      }
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
@@ -378,17 +399,30 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_mfma(int seq, int heads, 
           dp[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(dot_, QP, 32 * qt, 16 * ks, lane), vf[ks], dp[qt], 0, 0, 0);
         }
       }
+      const bool need_mask = (causal && q0 < kw0 + 31) || (q0 + BS > seq) || (kw0 + 32 > seq);
+      if (need_mask) {
 #pragma unroll
-      for (int qt = 0; qt < 2; ++qt)
+        for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int qi = 32 * qt + 8 * (r >> 2) + 4 * hl + (r & 3);
-          const int query = q0 + qi;
-          const bool dead = query >= seq || krow >= seq || (causal && krow > query);
-          const float p = dead ? 0.f : exp2f(s[qt][r] * scale_log2 - st_[qi]);
-          s[qt][r] = p;
-          dp[qt][r] = p * (dp[qt][r] - st_[64 + qi]);
-        }
+          for (int r = 0; r < 16; ++r) {
+            const int qi = 32 * qt + 8 * (r >> 2) + 4 * hl + (r & 3);
+            const int query = q0 + qi;
+            const bool dead = query >= seq || krow >= seq || (causal && krow > query);
+            const float p = dead ? 0.f : exp2f(s[qt][r] * scale_log2 - st_[qi]);
+            s[qt][r] = p;
+            dp[qt][r] = p * (dp[qt][r] - st_[64 + qi]);
+          }
+      } else {
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int qi = 32 * qt + 8 * (r >> 2) + 4 * hl + (r & 3);
+            const float p = exp2f(s[qt][r] * scale_log2 - st_[qi]);
+            s[qt][r] = p;
+            dp[qt][r] = p * (dp[qt][r] - st_[64 + qi]);
+          }
+      }
 #pragma unroll
       for (int qt = 0; qt < 2; ++qt)
 #pragma unroll

@@ -1,7 +1,8 @@
 // Row-wise kernels bounded by HBM bandwidth: LayerNorm forward, LayerNorm input-gradient (with the
 // gain/bias gradient partial sums), column sums for the bias gradients, and a pitched row copy.
-// One 64-lane wave owns a row; all reductions along a row are wave shuffles.  Reductions across
-// rows go through fixed-order partial sums, so results do not depend on scheduling.
+// Forward: one 64-lane wave owns a row and the row reductions are wave shuffles.  Backward: one to
+// eight waves share a row.  Reductions across rows go through fixed-order partial sums, so results
+// do not depend on scheduling.
 #include "dev_common.h"
 #include "kernels.h"
 
@@ -10,6 +11,7 @@ namespace k {
 namespace {
 
 constexpr int kWaves = 4;
+constexpr int kBwdWaves = 8;  // LayerNorm backward: waves (= rows in flight) per workgroup
 
 template <typename T, int NC>
 __global__ __launch_bounds__(256) void ln_fwd_kernel(int rows, int h, const T* __restrict__ x,
@@ -66,81 +68,116 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(int rows, int h, const T* _
 }
 
 // dx = resid + rstd * (g - mean(g) - xhat * mean(g * xhat)),  g = dy * gain,  xhat = (x - mean) * rstd.
-// Each wave walks rows blockIdx*4+wave, +4*gridDim, ... and keeps, per lane, the running column
-// sums of dy * xhat and dy for its own columns; the block then folds its four waves in wave
-// order and writes one row of partials: partial[block][0..h) = d gain, [h..2h) = d bias.
-template <typename T, int NC>
-__global__ __launch_bounds__(256) void ln_bwd_kernel(int rows, int h, const T* __restrict__ dy,
+// A workgroup is 8 waves; WR of them share a row (wave w takes the column slice w % WR, NC chunks
+// of 64 lanes x V elements), so a lane holds at most 3*V elements per tensor and 8/WR rows are in
+// flight per workgroup.  The two row means are summed from the WR slices' wave sums in slice
+// order through LDS.  Each lane keeps running column sums of dy * xhat and dy for its own
+// columns; at the end the 8/WR waves that share a slice are folded in wave order and the
+// workgroup writes one row of partials: partial[block][0..h) = d gain, [h..2h) = d bias.
+template <typename T, int NC, int WR>
+__global__ __launch_bounds__(kBwdWaves * 64) void ln_bwd_kernel(int rows, int h, const T* __restrict__ dy,
                                                       const T* x, const T* __restrict__ gain,
                                                       const float* __restrict__ mean, const float* __restrict__ rstd,
                                                       const T* resid, T* dx, float* __restrict__ partial) {
   constexpr int V = Vec<T>::N;
-  extern __shared__ float red[];  // [2][h]
+  constexpr int RG = kBwdWaves / WR;  // rows in flight
+  extern __shared__ float red[];      // [2][WR * NC * V * 64], then the row sums [2][RG][WR][2]
+  float (*stat)[RG][WR][2] = reinterpret_cast<float (*)[RG][WR][2]>(red + 2 * WR * NC * V * 64);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int rg = wave / WR, slice = wave % WR;
+  const int col0 = (slice * NC * 64 + lane) * V;  // chunk c starts at col0 + c * 64 * V
   float pg[NC][V], pb[NC][V], gn[NC][V];
 #pragma unroll
   for (int c = 0; c < NC; ++c) {
-    const int col = (c * 64 + lane) * V;
+    const int col = col0 + c * 64 * V;
 #pragma unroll
     for (int i = 0; i < V; ++i) pg[c][i] = pb[c][i] = gn[c][i] = 0.f;
     if (col < h) Vec<T>::load(gain + col, gn[c]);
   }
-  for (int row = blockIdx.x * kWaves + wave; row < rows; row += gridDim.x * kWaves) {
-    const float mu = mean[row], rs = rstd[row];
-    float xh[NC][V], g[NC][V];
-    float s1 = 0.f, s2 = 0.f;
+  int it = 0;
+  for (int base = blockIdx.x * RG; base < rows; base += gridDim.x * RG, ++it) {
+    const int row = base + rg;
+    const bool live = row < rows;
+    float xh[NC][V], g[NC][V], r[NC][V];
+    float mu = 0.f, rs = 0.f, s1 = 0.f, s2 = 0.f;
+    if (live) {
+      mu = mean[row];
+      rs = rstd[row];
+      float xv[NC][V], d[NC][V];
 #pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      const int col = (c * 64 + lane) * V;
-      if (col < h) {
-        float xv[V], d[V];
-        Vec<T>::load(x + (size_t)row * h + col, xv);
-        Vec<T>::load(dy + (size_t)row * h + col, d);
+      for (int c = 0; c < NC; ++c) {
+        const int col = col0 + c * 64 * V;
 #pragma unroll
-        for (int i = 0; i < V; ++i) {
-          xh[c][i] = (xv[i] - mu) * rs;
-          g[c][i] = d[i] * gn[c][i];
-          s1 += g[c][i];
-          s2 += g[c][i] * xh[c][i];
-          pg[c][i] += d[i] * xh[c][i];
-          pb[c][i] += d[i];
+        for (int i = 0; i < V; ++i) xv[c][i] = d[c][i] = r[c][i] = 0.f;
+        if (col < h) {
+          Vec<T>::load(x + (size_t)row * h + col, xv[c]);
+          Vec<T>::load(dy + (size_t)row * h + col, d[c]);
+          if (resid) Vec<T>::load(resid + (size_t)row * h + col, r[c]);
         }
       }
-    }
-    s1 = wave_sum(s1) / (float)h;
-    s2 = wave_sum(s2) / (float)h;
 #pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      const int col = (c * 64 + lane) * V;
-      if (col < h) {
-        float r[V], out[V];
-        if (resid) {
-          Vec<T>::load(resid + (size_t)row * h + col, r);
-        } else {
+      for (int c = 0; c < NC; ++c) {
+        const bool in = col0 + c * 64 * V < h;  // lanes past the row end hold zeros, but mu != 0
 #pragma unroll
-          for (int i = 0; i < V; ++i) r[i] = 0.f;
+        for (int i = 0; i < V; ++i) {
+          xh[c][i] = in ? (xv[c][i] - mu) * rs : 0.f;
+          g[c][i] = d[c][i] * gn[c][i];
+          s1 += g[c][i];
+          s2 += g[c][i] * xh[c][i];
+          pg[c][i] += d[c][i] * xh[c][i];
+          pb[c][i] += d[c][i];
         }
+      }
+      s1 = wave_sum(s1);
+      s2 = wave_sum(s2);
+    }
+    if constexpr (WR > 1) {
+      // Slots alternate with the iteration: a wave can only overwrite a slot two barriers after
+      // every wave has read it.
+      if (lane == 0) {
+        stat[it & 1][rg][slice][0] = s1;
+        stat[it & 1][rg][slice][1] = s2;
+      }
+      __syncthreads();
+      s1 = s2 = 0.f;
 #pragma unroll
-        for (int i = 0; i < V; ++i) out[i] = r[i] + rs * (g[c][i] - s1 - xh[c][i] * s2);
-        Vec<T>::store(dx + (size_t)row * h + col, out);
+      for (int w = 0; w < WR; ++w) {
+        s1 += stat[it & 1][rg][w][0];
+        s2 += stat[it & 1][rg][w][1];
+      }
+    }
+    s1 /= (float)h;
+    s2 /= (float)h;
+    if (live) {
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        const int col = col0 + c * 64 * V;
+        if (col < h) {
+          float out[V];
+#pragma unroll
+          for (int i = 0; i < V; ++i) out[i] = r[c][i] + rs * (g[c][i] - s1 - xh[c][i] * s2);
+          Vec<T>::store(dx + (size_t)row * h + col, out);
+        }
       }
     }
   }
-  for (int w = 0; w < kWaves; ++w) {
-    if (wave == w) {
+  // Fold: element (c, i) of lane l of slice s lives at red[((s*NC + c)*V + i) * 64 + (l + i*64/V) % 64]
+  // (the d-bias half kHalf further on): a wave's 64 lanes hit 64 different words of one 64-word
+  // line, and so does the write-out below, which walks i fastest.
+  constexpr int kHalf = WR * NC * V * 64;
+  for (int w = 0; w < RG; ++w) {
+    if (rg == w) {
 #pragma unroll
       for (int c = 0; c < NC; ++c) {
-        const int col = (c * 64 + lane) * V;
-        if (col < h) {
 #pragma unroll
-          for (int i = 0; i < V; ++i) {
-            if (w == 0) {
-              red[col + i] = pg[c][i];
-              red[h + col + i] = pb[c][i];
-            } else {
-              red[col + i] += pg[c][i];
-              red[h + col + i] += pb[c][i];
-            }
+        for (int i = 0; i < V; ++i) {
+          const int a = ((slice * NC + c) * V + i) * 64 + ((lane + i * (64 / V)) & 63);
+          if (w == 0) {
+            red[a] = pg[c][i];
+            red[kHalf + a] = pb[c][i];
+          } else {
+            red[a] += pg[c][i];
+            red[kHalf + a] += pb[c][i];
           }
         }
       }
@@ -148,7 +185,12 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(int rows, int h, const T* _
     __syncthreads();
   }
   float* out = partial + (size_t)blockIdx.x * 2 * h;
-  for (int i = threadIdx.x; i < 2 * h; i += 256) out[i] = red[i];
+  for (int j = threadIdx.x; j < h; j += kBwdWaves * 64) {
+    const int i = j % V, l = (j / V) & 63, c = j / (V * 64);  // c counts chunks across slices
+    const int a = (c * V + i) * 64 + ((l + i * (64 / V)) & 63);
+    out[j] = red[a];
+    out[h + j] = red[kHalf + a];
+  }
 }
 
 // out_a[i] += sum_p partial[p*stride + i] (i < split), out_b[i - split] += ... (i >= split).
@@ -195,7 +237,17 @@ __global__ __launch_bounds__(256) void colsum_kernel(int rows, int n, const T* _
   float acc[V];
 #pragma unroll
   for (int i = 0; i < V; ++i) acc[i] = 0.f;
-  for (int r = r0; r < r1; ++r) {
+  int r = r0;
+  for (; r + 4 <= r1; r += 4) {  // four independent loads in flight, added in row order
+    float v[4][V];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) Vec<T>::load(a + (size_t)(r + u) * lda + col, v[u]);
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int i = 0; i < V; ++i) acc[i] += v[u][i];
+  }
+  for (; r < r1; ++r) {
     float v[V];
     Vec<T>::load(a + (size_t)r * lda + col, v);
 #pragma unroll
@@ -223,9 +275,24 @@ int pick_nc(int h, int vec) {
   return 0;
 }
 
-int ln_bwd_blocks(int rows) {
-  int b = (rows + 2 * kWaves - 1) / (2 * kWaves);
-  return b < 1 ? 1 : (b > 256 ? 256 : b);
+// LayerNorm backward launch shape: WR waves per row so that a lane holds at most 3 chunks.
+struct LnBwdShape {
+  int nc, wr;
+};
+LnBwdShape ln_bwd_shape(int h, int vec) {
+  const int need = (h + 64 * vec - 1) / (64 * vec);
+  for (int wr : {1, 2, 4, 8}) {
+    const int nc = (need + wr - 1) / wr;
+    if (nc <= 3) return {nc, wr};
+  }
+  return {0, 0};
+}
+
+constexpr int kLnBwdMaxBlocks = 512;
+
+int ln_bwd_blocks(int rows, int rows_in_flight) {
+  const int b = (rows + rows_in_flight - 1) / rows_in_flight;
+  return b < 1 ? 1 : (b > kLnBwdMaxBlocks ? kLnBwdMaxBlocks : b);
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -260,19 +327,24 @@ int ln_fwd_t(hipStream_t st, int rows, int h, const void* x, const void* gain, c
 template <typename T>
 int ln_bwd_t(hipStream_t st, int rows, int h, const void* dy, const void* x, const void* gain, const float* mean,
              const float* rstd, const void* resid, void* dx, float* dgain, float* dbias, float* partial) {
-  const int nc = pick_nc(h, Vec<T>::N);
-  const int blocks = ln_bwd_blocks(rows);
-  const size_t lds = (size_t)2 * h * sizeof(float);
-#define LN_BWD_CASE(NC)                                                                                       \
-  case NC:                                                                                                    \
-    ln_bwd_kernel<T, NC><<<dim3(blocks), dim3(256), lds, st>>>(rows, h, (const T*)dy, (const T*)x, (const T*)gain, \
-                                                               mean, rstd, (const T*)resid, (T*)dx, partial); \
+  const LnBwdShape sh = ln_bwd_shape(h, Vec<T>::N);
+  if (!sh.nc) return fail(PMC_ERR_INVALID, "LayerNorm width %d too large", h);
+  const int blocks = ln_bwd_blocks(rows, kBwdWaves / sh.wr);
+  const size_t lds = ((size_t)2 * sh.wr * sh.nc * Vec<T>::N * 64 + 4 * kBwdWaves) * sizeof(float);
+#define LN_BWD_CASE(NC, WR)                                                                                  \
+  case NC * 16 + WR:                                                                                         \
+    if (lds > 48 * 1024 &&                                                                                   \
+        hipFuncSetAttribute(reinterpret_cast<const void*>(ln_bwd_kernel<T, NC, WR>),                         \
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)             \
+      return fail(PMC_ERR_HIP, "layernorm_backward: cannot reserve %zu bytes of LDS", lds);                  \
+    ln_bwd_kernel<T, NC, WR><<<dim3(blocks), dim3(kBwdWaves * 64), lds, st>>>(                               \
+        rows, h, (const T*)dy, (const T*)x, (const T*)gain, mean, rstd, (const T*)resid, (T*)dx, partial);   \
     break;
-  switch (nc) {
-    LN_BWD_CASE(1) LN_BWD_CASE(2) LN_BWD_CASE(3) LN_BWD_CASE(4) LN_BWD_CASE(6) LN_BWD_CASE(8) LN_BWD_CASE(12)
-    LN_BWD_CASE(16)
+  switch (sh.nc * 16 + sh.wr) {
+    LN_BWD_CASE(1, 1) LN_BWD_CASE(2, 1) LN_BWD_CASE(3, 1) LN_BWD_CASE(2, 2) LN_BWD_CASE(3, 2) LN_BWD_CASE(2, 4)
+    LN_BWD_CASE(3, 4) LN_BWD_CASE(2, 8) LN_BWD_CASE(3, 8)
     default:
-      return fail(PMC_ERR_INVALID, "LayerNorm width %d too large", h);
+      return fail(PMC_ERR_INVALID, "LayerNorm width %d: no kernel for %d chunks x %d waves", h, sh.nc, sh.wr);
   }
 #undef LN_BWD_CASE
   PMC_LAUNCH_CHECK("layernorm_backward");
@@ -302,7 +374,10 @@ int layernorm_forward(hipStream_t st, int dtype, int rows, int h, const void* x,
   return fail(PMC_ERR_INVALID, "layernorm: bad dtype %d", dtype);
 }
 
-size_t layernorm_backward_scratch_floats(int rows, int h) { return (size_t)ln_bwd_blocks(rows) * 2 * h; }
+size_t layernorm_backward_scratch_floats(int rows, int h) {
+  // Bound over both element types: at most one workgroup per row and kLnBwdMaxBlocks in all.
+  return (size_t)ln_bwd_blocks(rows, 1) * 2 * h;
+}
 
 int layernorm_backward(hipStream_t st, int dtype, int rows, int h, const void* dy, const void* x, const void* gain,
                        const float* mean, const float* rstd, const void* resid, void* dx, float* dgain, float* dbias,

@@ -134,7 +134,7 @@ def test_gemm_rejects_bad_arguments(ctx):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("rows,h", [(37, 16), (64, 256), (5, 320), (130, 2048), (33, 5120), (9, 8192)])
+@pytest.mark.parametrize("rows,h", [(37, 16), (64, 256), (5, 320), (1100, 1032), (130, 2048), (2100, 4096), (33, 5120), (9, 8192)])
 def test_layernorm_forward_backward(ctx, dtype, rows, h):
     if dtype == "f32" and h > 4096:
         # a wave keeps its row in registers: 16 vectors of 16 bytes per lane at most

@@ -194,6 +194,101 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, f32x16 (&acc)[TM][
   }
 }
 
+__device__ __forceinline__ void unpack8(u32x4 v, float* f) {
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    f[2 * e] = bf16lo_to_f32(v[e]);
+    f[2 * e + 1] = bf16hi_to_f32(v[e]);
+  }
+}
+__device__ __forceinline__ u32x4 pack8(const float* f) {
+  u32x4 v = {pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7])};
+  return v;
+}
+
+// Applies epilogue EPI to eight consecutive output columns n .. n+7 of row m and stores them
+// (16 bytes per lane for bf16 results, 32 for fp32 ones).  Same arithmetic as store_quad.
+template <int EPI>
+__device__ __forceinline__ void store_oct(const GemmParams& p, float (&v)[8], int m, int n) {
+  const size_t idx = (size_t)m * p.ldc + n;
+  if (EPI == kEpiPartial || EPI == PMC_EPI_ACCUM_F32) {
+    float* c = EPI == kEpiPartial
+                   ? reinterpret_cast<float*>(p.C) + (size_t)blockIdx.y * p.M * p.N + (size_t)m * p.N + n
+                   : reinterpret_cast<float*>(p.C) + idx;
+    f32x4 lo = {v[0], v[1], v[2], v[3]}, hi = {v[4], v[5], v[6], v[7]};
+    if (EPI == PMC_EPI_ACCUM_F32) {
+      const f32x4 old_lo = *reinterpret_cast<const f32x4*>(c), old_hi = *reinterpret_cast<const f32x4*>(c + 4);
+      lo = old_lo + lo;
+      hi = old_hi + hi;
+    }
+    *reinterpret_cast<f32x4*>(c) = lo;
+    *reinterpret_cast<f32x4*>(c + 4) = hi;
+    return;
+  }
+  if (EPI == PMC_EPI_BIAS || EPI == PMC_EPI_BIAS_RESID || EPI == PMC_EPI_BIAS_GELU) {
+    float b[8];
+    unpack8(*reinterpret_cast<const u32x4*>(p.bias + n), b);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] += b[e];
+  }
+  if (EPI == PMC_EPI_BIAS_RESID) {
+    float r[8];
+    unpack8(*reinterpret_cast<const u32x4*>(p.resid + idx), r);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] += r[e];
+  }
+  if (EPI == PMC_EPI_DGELU) {
+    float u[8];
+    unpack8(*reinterpret_cast<const u32x4*>(p.aux + idx), u);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_fast(u[e]);
+  }
+  *reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(p.C) + idx) = pack8(v);
+  if (EPI == PMC_EPI_BIAS_GELU) {
+    float g[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) g[e] = gelu_fast(v[e]);
+    *reinterpret_cast<u32x4*>(p.aux + idx) = pack8(g);
+  }
+}
+
+// Epilogue of the fast path.  In the accumulator layout a store instruction would touch 32 rows
+// with 16 bytes each; instead each wave passes its tile, 32 rows at a time, through a private
+// LDS slab [32][32 TN + 4] of fp32 and reads it back with 8 consecutive columns per lane, so a
+// store instruction covers whole 128-byte (bf16) or 256-byte (fp32) row segments.  The pitch of
+// 32 TN + 4 words spreads both the column-quad writes and the row-major reads over all banks.
+// Only the wave itself touches its slab: LDS operations of one wave complete in order, so no
+// barrier is needed between the passes.
+template <int TM, int TN, int EPI>
+__device__ __forceinline__ void epilogue_staged(const GemmParams& p, f32x16 (&acc)[TM][TN], float* slab, int mw0,
+                                                int nw0, int lane) {
+  constexpr int WN = 32 * TN, PITCH = WN + 4;
+  constexpr int LPR = WN / 8;     // lanes per row on the way out
+  constexpr int RPP = 64 / LPR;   // rows per pass
+  const int orow = lane / LPR, ocol = 8 * (lane % LPR);
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        f32x4 t = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+        *reinterpret_cast<f32x4*>(slab + (lane & 31) * PITCH + 32 * j + 8 * q + 4 * (lane >> 5)) = t;
+      }
+#pragma unroll
+    for (int pass = 0; pass < 32 / RPP; ++pass) {
+      const int row = pass * RPP + orow;
+      const f32x4 lo = *reinterpret_cast<const f32x4*>(slab + row * PITCH + ocol);
+      const f32x4 hi = *reinterpret_cast<const f32x4*>(slab + row * PITCH + ocol + 4);
+      const int m = mw0 + 32 * i + row, n = nw0 + ocol;
+      if (m < p.M && n < p.N) {
+        float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        store_oct<EPI>(p, v, m, n);
+      }
+    }
+  }
+}
+
 // Second half of a split-K product: adds the fp32 partials of the splits in ascending order (a
 // fixed order, so the result does not depend on scheduling) and applies the epilogue.
 template <int EPI>
@@ -391,8 +486,13 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_bf16_dma_kernel(G
     step(1, smem + nxt * STAGE, smem + nxt * STAGE + TA, 0);  // after the last tile: a clamped tile, unused
     cur = nxt;
   }
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): drain the clamped tail loads
-  epilogue<TM, TN, EPI>(p, acc, m0 + wm0, n0 + wn0, lane);
+  // vmcnt(0): drain the clamped tail loads; after the barrier no wave reads or fills a stage any
+  // more and the ring is reused for the epilogue slabs.
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  __syncthreads();
+  static_assert(NW * 32 * (WN + 4) * 4 <= NSTAGE * STAGE * 2, "epilogue slabs must fit in the stage ring");
+  float* slab = reinterpret_cast<float*>(smem) + wave * (32 * (WN + 4));
+  epilogue_staged<TM, TN, EPI>(p, acc, slab, m0 + wm0, n0 + wn0, lane);
 #endif
 }
 

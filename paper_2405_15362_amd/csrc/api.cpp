@@ -166,8 +166,7 @@ WorkspaceLayout workspace_of(const pmc_chunk_cfg& c) {
   w.attn = at;
   at += k::attention_backward_scratch_bytes(c.dtype, c.microbatch, c.seq, c.heads, c.hidden / c.heads);
   w.partial = at;
-  const int widest = std::max(3 * c.hidden, c.ffn);
-  const size_t pf = std::max(k::layernorm_backward_scratch_floats(t, c.hidden), k::column_sum_scratch_floats(t, widest));
+  const size_t pf = k::layernorm_backward_scratch_floats(t, c.hidden);
   at += align256(pf * sizeof(float));
   // split-K partial products of the skinny projections (F and B write [tokens, hidden] outputs)
   size_t g = 0;
@@ -352,19 +351,26 @@ int chunk_backward_weight_one(pmc_chunk* ch, int32_t mb, bool release) {
   hipStream_t st = ch->ctx->stream;
   const int T = ch->tokens, h = c.hidden, f = c.ffn, L = c.layers;
   char* s = m.slab;
-  float* partial = (float*)(ch->ctx->ws + ch->wsl.partial);
   for (int l = L - 1; l >= 0; --l) {
     const LayerOffsets& o = ch->off[l];
     const void* dxout = s + (l == L - 1 ? ch->off[0].x : ch->off[l + 1].x);
+    // the four bias gradients of the layer in one launch
+    k::ColumnSumJobs jobs = {};
+    jobs.count = 4;
+    const void* src[4] = {dxout, s + o.u, s + o.xmid, s + o.qkv};
+    const int width[4] = {h, f, h, 3 * h};
+    const int which[4] = {B_2, B_1, B_O, B_QKV};
+    for (int j = 0; j < 4; ++j) {
+      jobs.a[j] = src[j];
+      jobs.out[j] = G(ch, l, which[j]);
+      jobs.n[j] = jobs.lda[j] = width[j];
+    }
+    PMC_TRY(traced(ch->ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sums(st, c.dtype, T, jobs); }));
     PMC_TRY(t_gemm(ch->ctx, PMC_W, gemm_args(ch, true, false, f, h, T, s + o.g, f, dxout, h, G(ch, l, W_2), h, PMC_EPI_ACCUM_F32), ch->wsl));
-    PMC_TRY(traced(ch->ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sum(st, c.dtype, T, h, dxout, h, G(ch, l, B_2), partial); }));
     PMC_TRY(t_gemm(ch->ctx, PMC_W, gemm_args(ch, true, false, h, f, T, s + o.c, h, s + o.u, f, G(ch, l, W_1), f, PMC_EPI_ACCUM_F32), ch->wsl));
-    PMC_TRY(traced(ch->ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sum(st, c.dtype, T, f, s + o.u, f, G(ch, l, B_1), partial); }));
     PMC_TRY(t_gemm(ch->ctx, PMC_W, gemm_args(ch, true, false, h, h, T, s + o.o, h, s + o.xmid, h, G(ch, l, W_O), h, PMC_EPI_ACCUM_F32), ch->wsl));
-    PMC_TRY(traced(ch->ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sum(st, c.dtype, T, h, s + o.xmid, h, G(ch, l, B_O), partial); }));
     PMC_TRY(t_gemm(ch->ctx, PMC_W, gemm_args(ch, true, false, h, 3 * h, T, s + o.a, h, s + o.qkv, 3 * h, G(ch, l, W_QKV), 3 * h,
                                   PMC_EPI_ACCUM_F32), ch->wsl));
-    PMC_TRY(traced(ch->ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sum(st, c.dtype, T, 3 * h, s + o.qkv, 3 * h, G(ch, l, B_QKV), partial); }));
   }
   if (release) {
     ch->ctx->pool.give(m.slab, m.device, (int64_t)(ch->unit_bytes - ch->stats_bytes));
@@ -624,9 +630,7 @@ int pmc_attention_backward(pmc_ctx* ctx, int32_t dtype, int32_t batch, int32_t s
 int pmc_column_sum(pmc_ctx* ctx, int32_t dtype, int32_t rows, int32_t n, const void* a, int32_t lda, float* out) {
   if (!ctx) return fail(PMC_ERR_INVALID, "ctx is NULL");
   if (rows <= 0 || n <= 0) return fail(PMC_ERR_INVALID, "column_sum: rows=%d n=%d", rows, n);
-  const size_t need = k::column_sum_scratch_floats(rows, n) * sizeof(float);
-  if (!ctx->ws || ctx->ws_bytes < need) return fail(PMC_ERR_NOMEM, "column_sum: workspace needs %zu bytes", need);
-  return k::column_sum(ctx->stream, dtype, rows, n, a, lda, out, (float*)ctx->ws);
+  return k::column_sum(ctx->stream, dtype, rows, n, a, lda, out);
 }
 
 }  // extern "C"

@@ -49,8 +49,18 @@ int attention_backward(hipStream_t stream, int dtype, int batch, int seq, int he
                        const void* qkv, const void* o, const float* lse, const void* d_o, void* dqkv,
                        void* scratch);
 
-size_t column_sum_scratch_floats(int rows, int n);
-int column_sum(hipStream_t stream, int dtype, int rows, int n, const void* a, int lda, float* out, float* partial);
+// out[c] += sum over rows of a[row][c] (fp32 out), for up to four matrices of `rows` rows in one
+// launch; first_block is filled in by column_sums.
+struct ColumnSumJobs {
+  const void* a[4];
+  float* out[4];
+  int n[4];
+  int lda[4];
+  int first_block[5];
+  int count;
+};
+int column_sums(hipStream_t stream, int dtype, int rows, ColumnSumJobs jobs);
+int column_sum(hipStream_t stream, int dtype, int rows, int n, const void* a, int lda, float* out);
 
 int copy_rows(hipStream_t stream, int dtype, int rows, int cols, const void* src, int ld_src, void* dst, int ld_dst);
 

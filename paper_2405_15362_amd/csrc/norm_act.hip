@@ -225,36 +225,53 @@ __global__ __launch_bounds__(256) void sum_partials_kernel(int parts, int width,
   }
 }
 
-// partial[blockIdx.y][col] = sum over the block's slice of rows of a[row][col].
+// Column sums of up to four matrices with the same row count in one launch: out_j[c] += sum over
+// rows of a_j[row][c].  A workgroup owns 64 columns of one matrix; its 256 threads form 256/LPR
+// row slots of LPR lanes (16 bytes of a row each), slot s adds rows s, s + slots, ... in that
+// order (sixteen loads in flight), and 64 threads then add the slots in slot order: the result
+// depends on the shapes alone.
 template <typename T>
-__global__ __launch_bounds__(256) void colsum_kernel(int rows, int n, const T* __restrict__ a, int lda,
-                                                      int rows_per_part, float* __restrict__ partial) {
-  constexpr int V = Vec<T>::N;
-  const int col = (blockIdx.x * 256 + threadIdx.x) * V;
-  if (col >= n) return;
-  const int r0 = blockIdx.y * rows_per_part;
-  const int r1 = min(rows, r0 + rows_per_part);
+__global__ __launch_bounds__(256) void colsum_kernel(int rows, ColumnSumJobs jobs) {
+  constexpr int V = Vec<T>::N, LPR = 64 / V, SLOTS = 256 / LPR, UNROLL = 16;
+  __shared__ float red[SLOTS][64 + 1];
+  int j = 0;
+  while (j + 1 < jobs.count && (int)blockIdx.x >= jobs.first_block[j + 1]) ++j;
+  const T* a = static_cast<const T*>(jobs.a[j]);
+  const int n = jobs.n[j], lda = jobs.lda[j];
+  const int slot = threadIdx.x / LPR, sub = (threadIdx.x % LPR) * V;
+  const int col = ((int)blockIdx.x - jobs.first_block[j]) * 64 + sub;
   float acc[V];
 #pragma unroll
   for (int i = 0; i < V; ++i) acc[i] = 0.f;
-  int r = r0;
-  for (; r + 4 <= r1; r += 4) {  // four independent loads in flight, added in row order
-    float v[4][V];
+  if (col < n) {
+    const T* p = a + col;
+    int r = slot;
+    for (; r + (UNROLL - 1) * SLOTS < rows; r += UNROLL * SLOTS) {
+      float v[UNROLL][V];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) Vec<T>::load(a + (size_t)(r + u) * lda + col, v[u]);
+      for (int u = 0; u < UNROLL; ++u) Vec<T>::load(p + (size_t)(r + u * SLOTS) * lda, v[u]);
 #pragma unroll
-    for (int u = 0; u < 4; ++u)
+      for (int u = 0; u < UNROLL; ++u)
 #pragma unroll
-      for (int i = 0; i < V; ++i) acc[i] += v[u][i];
+        for (int i = 0; i < V; ++i) acc[i] += v[u][i];
+    }
+    for (; r < rows; r += SLOTS) {
+      float v[V];
+      Vec<T>::load(p + (size_t)r * lda, v);
+#pragma unroll
+      for (int i = 0; i < V; ++i) acc[i] += v[i];
+    }
   }
-  for (; r < r1; ++r) {
-    float v[V];
-    Vec<T>::load(a + (size_t)r * lda + col, v);
 #pragma unroll
-    for (int i = 0; i < V; ++i) acc[i] += v[i];
+  for (int i = 0; i < V; ++i) red[slot][sub + i] = acc[i];
+  __syncthreads();
+  const int c = ((int)blockIdx.x - jobs.first_block[j]) * 64 + threadIdx.x;
+  if (threadIdx.x < 64 && c < n) {
+    float total = 0.f;
+#pragma unroll
+    for (int sl = 0; sl < SLOTS; ++sl) total += red[sl][threadIdx.x];
+    jobs.out[j][c] += total;
   }
-#pragma unroll
-  for (int i = 0; i < V; ++i) partial[(size_t)blockIdx.y * n + col + i] = acc[i];
 }
 
 template <typename T>
@@ -354,11 +371,6 @@ int ln_bwd_t(hipStream_t st, int rows, int h, const void* dy, const void* x, con
   return PMC_OK;
 }
 
-int colsum_parts(int rows) {
-  int p = rows / 16;
-  return p < 1 ? 1 : (p > 128 ? 128 : p);
-}
-
 }  // namespace
 
 int layernorm_forward(hipStream_t st, int dtype, int rows, int h, const void* x, const void* gain, const void* bias,
@@ -395,23 +407,34 @@ int layernorm_backward(hipStream_t st, int dtype, int rows, int h, const void* d
   return fail(PMC_ERR_INVALID, "layernorm_backward: bad dtype %d", dtype);
 }
 
-size_t column_sum_scratch_floats(int rows, int n) { return (size_t)colsum_parts(rows) * n; }
-
-int column_sum(hipStream_t st, int dtype, int rows, int n, const void* a, int lda, float* out, float* partial) {
-  if (rows <= 0 || n <= 0) return fail(PMC_ERR_INVALID, "column_sum: rows=%d n=%d", rows, n);
+int column_sums(hipStream_t st, int dtype, int rows, ColumnSumJobs jobs) {
+  if (rows <= 0 || jobs.count < 1 || jobs.count > 4) return fail(PMC_ERR_INVALID, "column_sum: rows=%d jobs=%d", rows, jobs.count);
+  if (dtype != PMC_F32 && dtype != PMC_BF16) return fail(PMC_ERR_INVALID, "column_sum: bad dtype %d", dtype);
   const int vec = dtype == PMC_F32 ? 4 : 8;
-  if (n % vec || lda % vec || lda < n) return fail(PMC_ERR_INVALID, "column_sum: n=%d lda=%d must be multiples of %d", n, lda, vec);
-  if (!a || !out || !partial || !aligned16(a)) return fail(PMC_ERR_INVALID, "column_sum: bad pointer");
-  const int parts = colsum_parts(rows);
-  const int rpp = (rows + parts - 1) / parts;
-  dim3 grid((n / vec + 255) / 256, parts), block(256);
-  if (dtype == PMC_F32) colsum_kernel<float><<<grid, block, 0, st>>>(rows, n, (const float*)a, lda, rpp, partial);
-  else if (dtype == PMC_BF16) colsum_kernel<bf16_t><<<grid, block, 0, st>>>(rows, n, (const bf16_t*)a, lda, rpp, partial);
-  else return fail(PMC_ERR_INVALID, "column_sum: bad dtype %d", dtype);
+  int blocks = 0;
+  for (int j = 0; j < jobs.count; ++j) {
+    const int n = jobs.n[j], lda = jobs.lda[j];
+    if (n <= 0 || n % vec || lda % vec || lda < n)
+      return fail(PMC_ERR_INVALID, "column_sum: n=%d lda=%d must be multiples of %d", n, lda, vec);
+    if (!jobs.a[j] || !jobs.out[j] || !aligned16(jobs.a[j])) return fail(PMC_ERR_INVALID, "column_sum: bad pointer");
+    jobs.first_block[j] = blocks;
+    blocks += (n + 63) / 64;
+  }
+  for (int j = jobs.count; j < 5; ++j) jobs.first_block[j] = blocks;
+  if (dtype == PMC_F32) colsum_kernel<float><<<dim3(blocks), dim3(256), 0, st>>>(rows, jobs);
+  else colsum_kernel<bf16_t><<<dim3(blocks), dim3(256), 0, st>>>(rows, jobs);
   PMC_LAUNCH_CHECK("column_sum");
-  sum_partials_kernel<<<dim3((n + 63) / 64), dim3(256), 0, st>>>(parts, n, n, (size_t)n, partial, out, out);
-  PMC_LAUNCH_CHECK("column_sum reduce");
   return PMC_OK;
+}
+
+int column_sum(hipStream_t st, int dtype, int rows, int n, const void* a, int lda, float* out) {
+  ColumnSumJobs jobs = {};
+  jobs.count = 1;
+  jobs.a[0] = a;
+  jobs.out[0] = out;
+  jobs.n[0] = n;
+  jobs.lda[0] = lda;
+  return column_sums(st, dtype, rows, jobs);
 }
 
 int copy_rows(hipStream_t st, int dtype, int rows, int cols, const void* src, int ld_src, void* dst, int ld_dst) {

@@ -99,16 +99,25 @@ constexpr int PAD_ROWS = 8;    // tile read only with frag_rows: pitch DH + 8
 constexpr int PAD_COLS = 32;   // tile read only with frag_cols: pitch DH + 32
 constexpr int PAD_BOTH = 40;   // tile read both ways: pitch DH + 40
 
-template <int DH>
-__global__ __launch_bounds__(256, 2) void attn_fwd_mfma(int seq, int heads, int causal, const bf16_t* __restrict__ qkv,
-                                                         bf16_t* __restrict__ o, float* __restrict__ lse,
-                                                         float scale_log2) {
+// Forward.  The workgroup is a QW x KW grid of waves: wave (qg, kg) owns queries 32 qg .. 32 qg + 31
+// of the workgroup's 32 QW queries and, of every streamed block of 32 NKT KW keys, the 32 NKT keys
+// starting at 32 NKT kg.
+// Each wave runs its own online softmax over the keys it sees; at the end the KW partial results of
+// a query group are merged in key-group order through LDS.  Splitting the keys over waves puts two
+// waves on every SIMD even when there are few (query block, head) pairs, and shortens the serial
+// chain of a long row of key blocks.
+template <int DH, int QW, int KW, int NKT>
+__global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_fwd_mfma(int seq, int heads, int causal, const bf16_t* __restrict__ qkv,
+                                                               bf16_t* __restrict__ o, float* __restrict__ lse,
+                                                               float scale_log2) {
+  constexpr int NT = QW * KW * 64, BQW = 32 * QW, WK = 32 * NKT, BSW = WK * KW;
   constexpr int KP = DH + PAD_ROWS, VP = DH + PAD_COLS;
-  constexpr int KT = BS * KP, VT = BS * VP;
+  constexpr int KT = BSW * KP, VT = BSW * VP;
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];  // [2][K tile | V tile]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hl = lane >> 5;
+  const int qg = wave % QW, kg = wave / QW;
   const int h = heads * DH, head = blockIdx.y, b = blockIdx.z;
-  const int q0 = blockIdx.x * BQ, qw0 = q0 + 32 * wave, qrow = qw0 + (lane & 31);
+  const int q0 = blockIdx.x * BQW, qw0 = q0 + 32 * qg, qrow = qw0 + (lane & 31);
   const size_t ld = (size_t)3 * h;
   const bf16_t* base = qkv + (size_t)b * seq * ld + (size_t)head * DH;
 
@@ -121,86 +130,82 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma(int seq, int heads, int 
   f32x16 oacc[DH / 32];
 #pragma unroll
   for (int dt = 0; dt < DH / 32; ++dt) zero(oacc[dt]);
-  float m2 = -INFINITY, lsum = 0.f;
+  float m2 = -INFINITY, lsum = 0.f;  // running maximum (in log2 units, scale applied) and sum
 
-  const int kend = causal ? min(seq, q0 + BQ) : seq;
-  const int nblk = (kend + BS - 1) / BS;
-  BlockStager<BS, DH, KP, 256> sk;
-  BlockStager<BS, DH, VP, 256> sv;
+  const int kend = causal ? min(seq, q0 + BQW) : seq;
+  const int nblk = (kend + BSW - 1) / BSW;
+  BlockStager<BSW, DH, KP, NT> sk;
+  BlockStager<BSW, DH, VP, NT> sv;
   sk.load(base + h, ld, 0, seq, tid);
   sv.load(base + 2 * h, ld, 0, seq, tid);
   sk.store(smem, tid);
   sv.store(smem + KT, tid);
   __syncthreads();
   for (int blk = 0; blk < nblk; ++blk) {
-    const int k0 = blk * BS;
+    const int k0 = blk * BSW + WK * kg;  // this wave's 32 NKT keys
     const bf16_t* kt_ = smem + (blk & 1) * (KT + VT);
     const bf16_t* vt_ = kt_ + KT;
     if (blk + 1 < nblk) {
-      sk.load(base + h, ld, k0 + BS, seq, tid);
-      sv.load(base + 2 * h, ld, k0 + BS, seq, tid);
+      sk.load(base + h, ld, (blk + 1) * BSW, seq, tid);
+      sv.load(base + 2 * h, ld, (blk + 1) * BSW, seq, tid);
     }
-    if (!causal || k0 <= qw0 + 31) {
-      f32x16 s[2];
+    if (k0 < seq && (!causal || k0 <= qw0 + 31)) {
+      f32x16 s[NKT];
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
+      for (int kt = 0; kt < NKT; ++kt) {
         zero(s[kt]);
 #pragma unroll
         for (int ks = 0; ks < DH / 16; ++ks)
-          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(kt_, KP, 32 * kt, 16 * ks, lane), qf[ks], s[kt], 0, 0, 0);
+          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(kt_, KP, WK * kg + 32 * kt, 16 * ks, lane), qf[ks],
+                                                          s[kt], 0, 0, 0);
       }
-      float mx = -INFINITY;
       // only blocks that cross the diagonal of this wave's rows or the end of the sequence need masks
-      const bool need_mask = (causal && k0 + BS - 1 > qw0) || (k0 + BS > seq);
-      if (need_mask) {
+      if ((causal && k0 + WK - 1 > qw0) || (k0 + WK > seq)) {
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
+        for (int kt = 0; kt < NKT; ++kt)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int key = k0 + 32 * kt + 8 * (r >> 2) + 4 * hl + (r & 3);
-            float v = s[kt][r] * scale_log2;
-            if (key >= seq || (causal && key > qrow)) v = -INFINITY;
-            s[kt][r] = v;
-            mx = fmaxf(mx, v);
-          }
-      } else {
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            s[kt][r] *= scale_log2;
-            mx = fmaxf(mx, s[kt][r]);
+            if (key >= seq || (causal && key > qrow)) s[kt][r] = -INFINITY;
           }
       }
+      float mx = s[0][0];
+#pragma unroll
+      for (int kt = 0; kt < NKT; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m2, mx);
+      const float m_new = fmaxf(m2, mx * scale_log2);
       const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = exp2f(m2 - m_use);
       float rowsum = 0.f;
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
+      for (int kt = 0; kt < NKT; ++kt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float p = exp2f(s[kt][r] - m_use);
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kt][r], scale_log2, -m_use));
           s[kt][r] = p;
           rowsum += p;
         }
       rowsum += __shfl_xor(rowsum, 32, 64);
-      lsum = lsum * alpha + rowsum;
-      m2 = m_new;
+      if (__any(m_new != m2)) {  // the running maximum moved for some query: rescale what is summed so far
+        const float alpha = __builtin_amdgcn_exp2f(m2 - m_use);
+        lsum *= alpha;
 #pragma unroll
-      for (int dt = 0; dt < DH / 32; ++dt)
+        for (int dt = 0; dt < DH / 32; ++dt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+          for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+        m2 = m_new;
+      }
+      lsum += rowsum;
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
+      for (int kt = 0; kt < NKT; ++kt)
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
           const bf16x8 pb = acc_to_frag(s[kt], t);
 #pragma unroll
           for (int dt = 0; dt < DH / 32; ++dt)
-            oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(vt_, VP, 32 * dt, 32 * kt + 16 * t, lane), pb,
-                                                               oacc[dt], 0, 0, 0);
+            oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                frag_cols(vt_, VP, 32 * dt, WK * kg + 32 * kt + 16 * t, lane), pb, oacc[dt], 0, 0, 0);
         }
     }
     if (blk + 1 < nblk) {
@@ -209,6 +214,38 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_mfma(int seq, int heads, int 
       sv.store(nxt + KT, tid);
     }
     __syncthreads();
+  }
+  if (KW > 1) {
+    // Merge the key groups of each query group: groups 1.. park (O, m, l) in LDS (the tiles are no
+    // longer read), group 0 folds them in ascending order.  Slot layout: [DH/2 + 2][64 lanes] fp32.
+    constexpr int SLOT = (DH / 2 + 2) * 64;
+    static_assert((size_t)QW * (KW - 1) * SLOT * 4 <= (size_t)2 * (KT + VT) * 2, "merge slots must fit in the tiles");
+    float* slots = reinterpret_cast<float*>(smem);
+    if (kg > 0) {
+      float* my = slots + ((kg - 1) * QW + qg) * SLOT;
+#pragma unroll
+      for (int dt = 0; dt < DH / 32; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) my[(dt * 16 + r) * 64 + lane] = oacc[dt][r];
+      my[(DH / 2) * 64 + lane] = m2;
+      my[(DH / 2 + 1) * 64 + lane] = lsum;
+    }
+    __syncthreads();
+    if (kg > 0) return;
+#pragma unroll 1
+    for (int g = 1; g < KW; ++g) {
+      const float* other = slots + ((g - 1) * QW + qg) * SLOT;
+      const float mo = other[(DH / 2) * 64 + lane], lo = other[(DH / 2 + 1) * 64 + lane];
+      const float m_new = fmaxf(m2, mo);
+      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      const float a = __builtin_amdgcn_exp2f(m2 - m_use), bo = __builtin_amdgcn_exp2f(mo - m_use);
+      lsum = lsum * a + lo * bo;
+#pragma unroll
+      for (int dt = 0; dt < DH / 32; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[dt][r] = oacc[dt][r] * a + other[(dt * 16 + r) * 64 + lane] * bo;
+      m2 = m_new;
+    }
   }
   if (qrow < seq) {
     const float inv = 1.0f / lsum;
@@ -465,17 +502,28 @@ int reserve_lds(K kern, size_t bytes, bool& done, const char* what) {
   return PMC_OK;
 }
 
-template <int DH>
-int fwd_t(hipStream_t st, int batch, int seq, int heads, int causal, const void* qkv, void* o, float* lse) {
-  constexpr size_t lds = 2 * sizeof(bf16_t) * BS * ((DH + PAD_ROWS) + (DH + PAD_COLS));
+template <int DH, int QW, int KW, int NKT>
+int fwd_launch(hipStream_t st, int batch, int seq, int heads, int causal, const void* qkv, void* o, float* lse) {
+  constexpr size_t lds = 2 * sizeof(bf16_t) * 32 * NKT * KW * ((DH + PAD_ROWS) + (DH + PAD_COLS));
   static bool done = false;
-  if (int rc = reserve_lds(attn_fwd_mfma<DH>, lds, done, "attention_forward")) return rc;
+  if (int rc = reserve_lds(attn_fwd_mfma<DH, QW, KW, NKT>, lds, done, "attention_forward")) return rc;
   const float scale_log2 = kLog2e / sqrtf((float)DH);
-  attn_fwd_mfma<DH><<<dim3((seq + BQ - 1) / BQ, heads, batch), dim3(256), lds, st>>>(seq, heads, causal, (const bf16_t*)qkv,
-                                                                                    (bf16_t*)o, lse, scale_log2);
+  attn_fwd_mfma<DH, QW, KW, NKT><<<dim3((seq + 32 * QW - 1) / (32 * QW), heads, batch), dim3(QW * KW * 64), lds, st>>>(
+      seq, heads, causal, (const bf16_t*)qkv, (bf16_t*)o, lse, scale_log2);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(PMC_ERR_HIP, "attention_forward launch failed: %s", hipGetErrorString(e));
   return PMC_OK;
+}
+
+// Few (128-query block, head) pairs: 64-query workgroups whose 8 waves split 128-key blocks four
+// ways, so that every compute unit gets work; otherwise 128-query workgroups of 4 waves, each
+// taking whole 64-key blocks, two workgroups to a compute unit.
+bool few_blocks(int batch, int seq, int heads) { return (long)((seq + 127) / 128) * heads * batch < 512; }
+
+template <int DH>
+int fwd_t(hipStream_t st, int batch, int seq, int heads, int causal, const void* qkv, void* o, float* lse) {
+  if (few_blocks(batch, seq, heads)) return fwd_launch<DH, 2, 4, 1>(st, batch, seq, heads, causal, qkv, o, lse);
+  return fwd_launch<DH, 4, 1, 2>(st, batch, seq, heads, causal, qkv, o, lse);
 }
 
 template <int DH>

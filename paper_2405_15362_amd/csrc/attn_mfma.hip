@@ -256,17 +256,23 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_fwd_m
   }
 }
 
-template <int DH>
-__global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dq_mfma(int seq, int heads, int causal, const bf16_t* __restrict__ qkv,
-                                                            const bf16_t* __restrict__ o, const float* __restrict__ lse,
-                                                            const bf16_t* __restrict__ d_o, bf16_t* __restrict__ dq,
-                                                            float* __restrict__ delta, float scale, float scale_log2) {
+// Backward, dQ.  Same wave grid as the forward kernel: wave (qg, kg) owns 32 queries and the 32 NKT
+// keys starting at 32 NKT kg of every streamed block; 32-key tiles are taken one at a time
+// (S and dP, then dS, then dQ^T += K^T dS^T) to keep the register footprint at two waves per SIMD.
+// The KW partial dQ of a query group are added in key-group order through LDS at the end.
+template <int DH, int QW, int KW, int NKT>
+__global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_bwd_dq_mfma(
+    int seq, int heads, int causal, const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ o,
+    const float* __restrict__ lse, const bf16_t* __restrict__ d_o, bf16_t* __restrict__ dq, float* __restrict__ delta,
+    float scale, float scale_log2) {
+  constexpr int NT = QW * KW * 64, BQW = 32 * QW, WK = 32 * NKT, BSW = WK * KW;
   constexpr int KP = DH + PAD_BOTH, VP = DH + PAD_ROWS;
-  constexpr int KT = BS * KP, VT = BS * VP;
+  constexpr int KT = BSW * KP, VT = BSW * VP;
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hl = lane >> 5;
+  const int qg = wave % QW, kg = wave / QW;
   const int h = heads * DH, head = blockIdx.y, b = blockIdx.z;
-  const int q0 = blockIdx.x * BQ, qw0 = q0 + 32 * wave, qrow = qw0 + (lane & 31);
+  const int q0 = blockIdx.x * BQW, qw0 = q0 + 32 * qg, qrow = qw0 + (lane & 31);
   const int qclamp = min(qrow, seq - 1);
   const size_t ld = (size_t)3 * h;
   const bf16_t* base = qkv + (size_t)b * seq * ld + (size_t)head * DH;
@@ -287,68 +293,61 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dq_mfma(int s
   }
   dl += __shfl_xor(dl, 32, 64);
   const size_t stat = ((size_t)b * heads + head) * seq + qclamp;
-  if (hl == 0 && qrow < seq) delta[stat] = dl;
+  if (kg == 0 && hl == 0 && qrow < seq) delta[stat] = dl;
   const float lse2 = lse[stat] * kLog2e;
   f32x16 acc[DH / 32];
 #pragma unroll
   for (int dt = 0; dt < DH / 32; ++dt) zero(acc[dt]);
 
-  const int kend = causal ? min(seq, q0 + BQ) : seq;
-  const int nblk = (kend + BS - 1) / BS;
-  BlockStager<BS, DH, KP, 256> sk;
-  BlockStager<BS, DH, VP, 256> sv;
+  const int kend = causal ? min(seq, q0 + BQW) : seq;
+  const int nblk = (kend + BSW - 1) / BSW;
+  BlockStager<BSW, DH, KP, NT> sk;
+  BlockStager<BSW, DH, VP, NT> sv;
   sk.load(base + h, ld, 0, seq, tid);
   sv.load(base + 2 * h, ld, 0, seq, tid);
   sk.store(smem, tid);
   sv.store(smem + KT, tid);
   __syncthreads();
   for (int blk = 0; blk < nblk; ++blk) {
-    const int k0 = blk * BS;
     const bf16_t* kt_ = smem + (blk & 1) * (KT + VT);
     const bf16_t* vt_ = kt_ + KT;
     if (blk + 1 < nblk) {
-      sk.load(base + h, ld, k0 + BS, seq, tid);
-      sv.load(base + 2 * h, ld, k0 + BS, seq, tid);
+      sk.load(base + h, ld, (blk + 1) * BSW, seq, tid);
+      sv.load(base + 2 * h, ld, (blk + 1) * BSW, seq, tid);
     }
-    if (!causal || k0 <= qw0 + 31) {
-      f32x16 s[2], dp[2];
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt) {
-        zero(s[kt]);
-        zero(dp[kt]);
+    for (int kt = 0; kt < NKT; ++kt) {
+      const int trow = WK * kg + 32 * kt;   // tile row of this 32-key tile
+      const int k0 = blk * BSW + trow;      // its first key
+      if (k0 >= seq || (causal && k0 > qw0 + 31)) continue;
+      f32x16 s, dp;
+      zero(s);
+      zero(dp);
 #pragma unroll
-        for (int ks = 0; ks < DH / 16; ++ks) {
-          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(kt_, KP, 32 * kt, 16 * ks, lane), qf[ks], s[kt], 0, 0, 0);
-          dp[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(vt_, VP, 32 * kt, 16 * ks, lane), dof[ks], dp[kt], 0, 0, 0);
-        }
+      for (int ks = 0; ks < DH / 16; ++ks) {
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(kt_, KP, trow, 16 * ks, lane), qf[ks], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(vt_, VP, trow, 16 * ks, lane), dof[ks], dp, 0, 0, 0);
       }
-      const bool need_mask = (causal && k0 + BS - 1 > qw0) || (k0 + BS > seq);
-      if (need_mask) {
+      if ((causal && k0 + 31 > qw0) || (k0 + 32 > seq)) {
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int key = k0 + 32 * kt + 8 * (r >> 2) + 4 * hl + (r & 3);
-            const bool dead = key >= seq || (causal && key > qrow);
-            const float p = dead ? 0.f : exp2f(s[kt][r] * scale_log2 - lse2);
-            s[kt][r] = p * (dp[kt][r] - dl);
-          }
+        for (int r = 0; r < 16; ++r) {
+          const int key = k0 + 8 * (r >> 2) + 4 * hl + (r & 3);
+          const bool dead = key >= seq || (causal && key > qrow);
+          const float p = dead ? 0.f : __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, -lse2));
+          s[r] = p * (dp[r] - dl);
+        }
       } else {
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) s[kt][r] = exp2f(s[kt][r] * scale_log2 - lse2) * (dp[kt][r] - dl);
+        for (int r = 0; r < 16; ++r) s[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, -lse2)) * (dp[r] - dl);
       }
 #pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
+      for (int t = 0; t < 2; ++t) {
+        const bf16x8 dsb = acc_to_frag(s, t);
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const bf16x8 dsb = acc_to_frag(s[kt], t);
-#pragma unroll
-          for (int dt = 0; dt < DH / 32; ++dt)
-            acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(kt_, KP, 32 * dt, 32 * kt + 16 * t, lane), dsb,
-                                                              acc[dt], 0, 0, 0);
-        }
+        for (int dt = 0; dt < DH / 32; ++dt)
+          acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(kt_, KP, 32 * dt, trow + 16 * t, lane), dsb, acc[dt],
+                                                            0, 0, 0);
+      }
     }
     if (blk + 1 < nblk) {
       bf16_t* nxt = smem + ((blk + 1) & 1) * (KT + VT);
@@ -357,6 +356,28 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dq_mfma(int s
     }
     __syncthreads();
   }
+  if (KW > 1) {
+    constexpr int SLOT = (DH / 2) * 64;  // [DH/2 registers][64 lanes] fp32
+    static_assert((size_t)QW * (KW - 1) * SLOT * 4 <= (size_t)2 * (KT + VT) * 2, "merge slots must fit in the tiles");
+    float* slots = reinterpret_cast<float*>(smem);
+    if (kg > 0) {
+      float* my = slots + ((kg - 1) * QW + qg) * SLOT;
+#pragma unroll
+      for (int dt = 0; dt < DH / 32; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) my[(dt * 16 + r) * 64 + lane] = acc[dt][r];
+    }
+    __syncthreads();
+    if (kg > 0) return;
+#pragma unroll 1
+    for (int g = 1; g < KW; ++g) {
+      const float* other = slots + ((g - 1) * QW + qg) * SLOT;
+#pragma unroll
+      for (int dt = 0; dt < DH / 32; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[dt][r] += other[(dt * 16 + r) * 64 + lane];
+    }
+  }
   if (qrow < seq) {
     bf16_t* row = dq + ((size_t)b * seq + qrow) * h + (size_t)head * DH;
 #pragma unroll
@@ -364,18 +385,26 @@ __global__ __launch_bounds__(256, DH == 128 ? 1 : 2) void attn_bwd_dq_mfma(int s
   }
 }
 
-template <int DH>
-__global__ __launch_bounds__(256, 1) void attn_bwd_dkv_mfma(int seq, int heads, int causal, const bf16_t* qkv,
-                                                             const float* __restrict__ lse, const float* __restrict__ delta,
-                                                             const bf16_t* __restrict__ d_o, bf16_t* dqkv, float scale,
-                                                             float scale_log2) {
+// Backward, dK and dV.  A workgroup owns 32 KG keys of one head; wave (kg, qg) keeps K and V of keys
+// 32 kg .. 32 kg + 31 as operand fragments and, of every streamed block of 32 QG queries (Q and dO
+// tiles plus their log-sum-exp and delta), takes queries 32 qg .. 32 qg + 31: dV^T += dO^T P and
+// dK^T += Q^T dS.  The QG partial sums of a key group are added in query-group order through LDS
+// at the end and written in place over K and V (a key block is read only by its own workgroup).
+template <int DH, int KG, int QG>
+__global__ __launch_bounds__(KG * QG * 64, 1) void attn_bwd_dkv_mfma(int seq, int heads, int causal, const bf16_t* qkv,
+                                                                      const float* __restrict__ lse,
+                                                                      const float* __restrict__ delta,
+                                                                      const bf16_t* __restrict__ d_o, bf16_t* dqkv,
+                                                                      float scale, float scale_log2) {
+  constexpr int NT = KG * QG * 64, BK = 32 * KG, BSQ = 32 * QG;
   constexpr int QP = DH + PAD_BOTH;
-  constexpr int QT = BS * QP;
+  constexpr int QT = BSQ * QP;
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];  // [2][Q tile | dO tile], then stats
-  float* stats = reinterpret_cast<float*>(smem + 4 * QT);       // [2][lse2[64] | delta[64]]
+  float* stats = reinterpret_cast<float*>(smem + 4 * QT);       // [2][lse2[BSQ] | delta[BSQ]]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hl = lane >> 5;
+  const int kg = wave % KG, qg = wave / KG;
   const int h = heads * DH, head = blockIdx.y, b = blockIdx.z;
-  const int k0 = blockIdx.x * BQ, kw0 = k0 + 32 * wave, krow = kw0 + (lane & 31);
+  const int k0 = blockIdx.x * BK, kw0 = k0 + 32 * kg, krow = kw0 + (lane & 31);
   const size_t ld = (size_t)3 * h;
   const bf16_t* base = qkv + (size_t)b * seq * ld + (size_t)head * DH;
   const bf16_t* dob = d_o + (size_t)b * seq * h + (size_t)head * DH;
@@ -397,14 +426,14 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_mfma(int seq, int heads, 
     zero(dk[dt]);
     zero(dv[dt]);
   }
-  const int qstart = causal ? (k0 / BS) * BS : 0;
-  const int nblk = (seq - qstart + BS - 1) / BS;
-  BlockStager<BS, DH, QP, 256> sq, sdo;
-  float st_reg = 0.f;  // threads 0..63: lse2 of query tid; 64..127: delta of query tid-64
+  const int qstart = causal ? (k0 / BSQ) * BSQ : 0;
+  const int nblk = (seq - qstart + BSQ - 1) / BSQ;
+  BlockStager<BSQ, DH, QP, NT> sq, sdo;
+  float st_reg = 0.f;  // threads 0..BSQ-1: lse2 of query tid; BSQ..2 BSQ-1: delta of query tid-BSQ
   auto load_stats = [&](int q0) {
-    if (tid < 128) {
-      const int qi = q0 + (tid & 63);
-      st_reg = qi < seq ? (tid < 64 ? lse_b[qi] * kLog2e : delta_b[qi]) : 0.f;
+    if (tid < 2 * BSQ) {
+      const int qi = q0 + (tid % BSQ);
+      st_reg = qi < seq ? (tid < BSQ ? lse_b[qi] * kLog2e : delta_b[qi]) : 0.f;
     }
   };
   sq.load(base, ld, qstart, seq, tid);
@@ -412,78 +441,96 @@ __global__ __launch_bounds__(256, 1) void attn_bwd_dkv_mfma(int seq, int heads, 
   load_stats(qstart);
   sq.store(smem, tid);
   sdo.store(smem + QT, tid);
-  if (tid < 128) stats[tid] = st_reg;
+  if (tid < 2 * BSQ) stats[tid] = st_reg;
   __syncthreads();
   for (int blk = 0; blk < nblk; ++blk) {
-    const int q0 = qstart + blk * BS;
+    const int q0 = qstart + blk * BSQ + 32 * qg;  // this wave's 32 queries
+    const int trow = 32 * qg;
     const bf16_t* qt_ = smem + (blk & 1) * 2 * QT;
     const bf16_t* dot_ = qt_ + QT;
-    const float* st_ = stats + (blk & 1) * 128;
+    const float* st_ = stats + (blk & 1) * 2 * BSQ + trow;
     if (blk + 1 < nblk) {
-      sq.load(base, ld, q0 + BS, seq, tid);
-      sdo.load(dob, (size_t)h, q0 + BS, seq, tid);
-      load_stats(q0 + BS);
+      sq.load(base, ld, qstart + (blk + 1) * BSQ, seq, tid);
+      sdo.load(dob, (size_t)h, qstart + (blk + 1) * BSQ, seq, tid);
+      load_stats(qstart + (blk + 1) * BSQ);
     }
-    if (!causal || q0 + BS - 1 >= kw0) {
-      f32x16 s[2], dp[2];
+    if (q0 < seq && (!causal || q0 + 31 >= kw0)) {
+      f32x16 s, dp;
+      zero(s);
+      zero(dp);
 #pragma unroll
-      for (int qt = 0; qt < 2; ++qt) {
-        zero(s[qt]);
-        zero(dp[qt]);
-#pragma unroll
-        for (int ks = 0; ks < DH / 16; ++ks) {
-          s[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(qt_, QP, 32 * qt, 16 * ks, lane), kf[ks], s[qt], 0, 0, 0);
-          dp[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(dot_, QP, 32 * qt, 16 * ks, lane), vf[ks], dp[qt], 0, 0, 0);
-        }
+      for (int ks = 0; ks < DH / 16; ++ks) {
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(qt_, QP, trow, 16 * ks, lane), kf[ks], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(dot_, QP, trow, 16 * ks, lane), vf[ks], dp, 0, 0, 0);
       }
-      const bool need_mask = (causal && q0 < kw0 + 31) || (q0 + BS > seq) || (kw0 + 32 > seq);
-      if (need_mask) {
+      if ((causal && q0 < kw0 + 31) || (q0 + 32 > seq) || (kw0 + 32 > seq)) {
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int qi = 32 * qt + 8 * (r >> 2) + 4 * hl + (r & 3);
-            const int query = q0 + qi;
-            const bool dead = query >= seq || krow >= seq || (causal && krow > query);
-            const float p = dead ? 0.f : exp2f(s[qt][r] * scale_log2 - st_[qi]);
-            s[qt][r] = p;
-            dp[qt][r] = p * (dp[qt][r] - st_[64 + qi]);
-          }
+        for (int r = 0; r < 16; ++r) {
+          const int qi = 8 * (r >> 2) + 4 * hl + (r & 3);
+          const int query = q0 + qi;
+          const bool dead = query >= seq || krow >= seq || (causal && krow > query);
+          const float p = dead ? 0.f : __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, -st_[qi]));
+          s[r] = p;
+          dp[r] = p * (dp[r] - st_[BSQ + qi]);
+        }
       } else {
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int qi = 32 * qt + 8 * (r >> 2) + 4 * hl + (r & 3);
-            const float p = exp2f(s[qt][r] * scale_log2 - st_[qi]);
-            s[qt][r] = p;
-            dp[qt][r] = p * (dp[qt][r] - st_[64 + qi]);
-          }
+        for (int r = 0; r < 16; ++r) {
+          const int qi = 8 * (r >> 2) + 4 * hl + (r & 3);
+          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, -st_[qi]));
+          s[r] = p;
+          dp[r] = p * (dp[r] - st_[BSQ + qi]);
+        }
       }
 #pragma unroll
-      for (int qt = 0; qt < 2; ++qt)
+      for (int t = 0; t < 2; ++t) {
+        const bf16x8 pb = acc_to_frag(s, t);
+        const bf16x8 dsb = acc_to_frag(dp, t);
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const bf16x8 pb = acc_to_frag(s[qt], t);
-          const bf16x8 dsb = acc_to_frag(dp[qt], t);
-#pragma unroll
-          for (int dt = 0; dt < DH / 32; ++dt) {
-            dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(dot_, QP, 32 * dt, 32 * qt + 16 * t, lane), pb,
-                                                             dv[dt], 0, 0, 0);
-            dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(qt_, QP, 32 * dt, 32 * qt + 16 * t, lane), dsb,
-                                                             dk[dt], 0, 0, 0);
-          }
+        for (int dt = 0; dt < DH / 32; ++dt) {
+          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(dot_, QP, 32 * dt, trow + 16 * t, lane), pb, dv[dt], 0, 0, 0);
+          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(qt_, QP, 32 * dt, trow + 16 * t, lane), dsb, dk[dt], 0, 0, 0);
         }
+      }
     }
     if (blk + 1 < nblk) {
       bf16_t* nxt = smem + ((blk + 1) & 1) * 2 * QT;
       sq.store(nxt, tid);
       sdo.store(nxt + QT, tid);
-      if (tid < 128) stats[((blk + 1) & 1) * 128 + tid] = st_reg;
+      if (tid < 2 * BSQ) stats[((blk + 1) & 1) * 2 * BSQ + tid] = st_reg;
     }
     __syncthreads();
   }
-  if (krow < seq) {
+  // Merge the query groups, one group after the other so that one set of slots is enough:
+  // slot of key group kg = [DH registers (dK then dV)][64 lanes] fp32.
+  constexpr int SLOT = DH * 64;
+  float* slots = reinterpret_cast<float*>(smem);
+#pragma unroll 1
+  for (int g = 1; g < QG; ++g) {
+    if (qg == g) {
+      float* my = slots + kg * SLOT;
+#pragma unroll
+      for (int dt = 0; dt < DH / 32; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          my[(dt * 16 + r) * 64 + lane] = dk[dt][r];
+          my[(DH / 2 + dt * 16 + r) * 64 + lane] = dv[dt][r];
+        }
+    }
+    __syncthreads();
+    if (qg == 0) {
+      const float* other = slots + kg * SLOT;
+#pragma unroll
+      for (int dt = 0; dt < DH / 32; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          dk[dt][r] += other[(dt * 16 + r) * 64 + lane];
+          dv[dt][r] += other[(DH / 2 + dt * 16 + r) * 64 + lane];
+        }
+    }
+    __syncthreads();
+  }
+  if (qg == 0 && krow < seq) {
     bf16_t* row = dqkv + ((size_t)b * seq + krow) * ld + (size_t)head * DH + h;
 #pragma unroll
     for (int dt = 0; dt < DH / 32; ++dt) {
@@ -526,23 +573,34 @@ int fwd_t(hipStream_t st, int batch, int seq, int heads, int causal, const void*
   return fwd_launch<DH, 4, 1, 2>(st, batch, seq, heads, causal, qkv, o, lse);
 }
 
-template <int DH>
-int bwd_t(hipStream_t st, int batch, int seq, int heads, int causal, const void* qkv, const void* o, const float* lse,
-          const void* d_o, void* dqkv, void* dq_stage, float* delta) {
-  constexpr size_t lds_dq = 2 * sizeof(bf16_t) * BS * ((DH + PAD_BOTH) + (DH + PAD_ROWS));
-  constexpr size_t lds_dkv = 4 * sizeof(bf16_t) * BS * (DH + PAD_BOTH) + 2 * 128 * sizeof(float);
+template <int DH, int QW, int KW, int NKT, int KG, int QG>
+int bwd_launch(hipStream_t st, int batch, int seq, int heads, int causal, const void* qkv, const void* o, const float* lse,
+               const void* d_o, void* dqkv, void* dq_stage, float* delta) {
+  constexpr size_t lds_dq = 2 * sizeof(bf16_t) * 32 * NKT * KW * ((DH + PAD_BOTH) + (DH + PAD_ROWS));
+  constexpr size_t tiles_dkv = 4 * sizeof(bf16_t) * 32 * QG * (DH + PAD_BOTH) + 2 * 2 * 32 * QG * sizeof(float);
+  constexpr size_t merge_dkv = (size_t)KG * DH * 64 * sizeof(float);
+  constexpr size_t lds_dkv = tiles_dkv > merge_dkv ? tiles_dkv : merge_dkv;
+  static_assert(lds_dq <= 160 * 1024 && lds_dkv <= 160 * 1024, "tiles exceed the LDS of a compute unit");
   static bool done_dq = false, done_dkv = false;
-  if (int rc = reserve_lds(attn_bwd_dq_mfma<DH>, lds_dq, done_dq, "attention_backward")) return rc;
-  if (int rc = reserve_lds(attn_bwd_dkv_mfma<DH>, lds_dkv, done_dkv, "attention_backward")) return rc;
+  if (int rc = reserve_lds(attn_bwd_dq_mfma<DH, QW, KW, NKT>, lds_dq, done_dq, "attention_backward")) return rc;
+  if (int rc = reserve_lds(attn_bwd_dkv_mfma<DH, KG, QG>, lds_dkv, done_dkv, "attention_backward")) return rc;
   const float scale = 1.0f / sqrtf((float)DH), scale_log2 = kLog2e * scale;
-  dim3 grid((seq + BQ - 1) / BQ, heads, batch), block(256);
-  attn_bwd_dq_mfma<DH><<<grid, block, lds_dq, st>>>(seq, heads, causal, (const bf16_t*)qkv, (const bf16_t*)o, lse,
-                                                    (const bf16_t*)d_o, (bf16_t*)dq_stage, delta, scale, scale_log2);
-  attn_bwd_dkv_mfma<DH><<<grid, block, lds_dkv, st>>>(seq, heads, causal, (const bf16_t*)qkv, lse, delta,
-                                                      (const bf16_t*)d_o, (bf16_t*)dqkv, scale, scale_log2);
+  attn_bwd_dq_mfma<DH, QW, KW, NKT><<<dim3((seq + 32 * QW - 1) / (32 * QW), heads, batch), dim3(QW * KW * 64), lds_dq, st>>>(
+      seq, heads, causal, (const bf16_t*)qkv, (const bf16_t*)o, lse, (const bf16_t*)d_o, (bf16_t*)dq_stage, delta, scale,
+      scale_log2);
+  attn_bwd_dkv_mfma<DH, KG, QG><<<dim3((seq + 32 * KG - 1) / (32 * KG), heads, batch), dim3(KG * QG * 64), lds_dkv, st>>>(
+      seq, heads, causal, (const bf16_t*)qkv, lse, delta, (const bf16_t*)d_o, (bf16_t*)dqkv, scale, scale_log2);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(PMC_ERR_HIP, "attention_backward launch failed: %s", hipGetErrorString(e));
   return PMC_OK;
+}
+
+template <int DH>
+int bwd_t(hipStream_t st, int batch, int seq, int heads, int causal, const void* qkv, const void* o, const float* lse,
+          const void* d_o, void* dqkv, void* dq_stage, float* delta) {
+  if (few_blocks(batch, seq, heads))
+    return bwd_launch<DH, 2, 4, 1, 2, 2>(st, batch, seq, heads, causal, qkv, o, lse, d_o, dqkv, dq_stage, delta);
+  return bwd_launch<DH, 4, 1, 2, 4, 2>(st, batch, seq, heads, causal, qkv, o, lse, d_o, dqkv, dq_stage, delta);
 }
 
 int check(const char* what, int batch, int seq, int heads, int dh, const void* qkv) {

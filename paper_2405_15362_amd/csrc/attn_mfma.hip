@@ -1,19 +1,22 @@
 // Fused flash-style attention for bf16 storage on the gfx950 matrix cores
 // (v_mfma_f32_32x32x16_bf16), head size 64 or 128, packed qkv [batch*seq, 3h].
 //
-// Forward: a workgroup owns 128 queries of one head (32 per wave) and streams 64-key blocks of K
-// and V through LDS (double buffered).  Scores are produced transposed, S^T[key][query], so every
-// lane owns ONE query column: the online-softmax max/sum over keys are in-lane reductions plus one
-// exchange between the two half-waves, and the probabilities already sit in the register layout of
-// the B operand of the second product O^T = V^T . P^T.  V^T is never formed in memory: the V tile
-// stays [key][dh] in LDS and is read with the transposing LDS load.  Saves O and the log-sum-exp.
+// Forward: a workgroup owns a block of queries of one head and streams blocks of K and V through
+// LDS (double buffered); its waves form a grid over (32-query group, key group).  Scores are
+// produced transposed, S^T[key][query], so every lane owns ONE query column: the online-softmax
+// max/sum over keys are in-lane reductions plus one exchange between the two half-waves, and the
+// probabilities already sit in the register layout of the B operand of the second product
+// O^T = V^T . P^T.  V^T is never formed in memory: the V tile stays [key][dh] in LDS and is read
+// with the transposing LDS load.  Saves O and the log-sum-exp.
 //
 // Backward is two kernels, each output element having one writer and a fixed summation order
 // (results are reproducible run to run):
-//   dQ   per 128-query block, streaming K/V blocks: recomputes P from the saved log-sum-exp,
+//   dQ   per query block, streaming K/V blocks: recomputes P from the saved log-sum-exp,
 //        dS = P * (dO.V^T - delta), dQ^T += K^T . dS^T; also emits delta = rowsum(dO * O).
-//   dKdV per 128-key block, streaming Q/dO blocks: dV^T += dO^T . P, dK^T += Q^T . dS, written
+//   dKdV per key block, streaming Q/dO blocks: dV^T += dO^T . P, dK^T += Q^T . dS, written
 //        in place over K and V (a key block is read only by the workgroup that owns it).
+// The launch shapes are chosen by the number of (128-row block, head) pairs: few pairs get small
+// row blocks and more waves per block so that all compute units have work.
 #include "dev_common.h"
 #include "kernels.h"
 
@@ -93,8 +96,6 @@ __device__ __forceinline__ void store_tile_t(bf16_t* row_ptr, const f32x16& a, f
   }
 }
 
-constexpr int BQ = 128;   // rows owned by a workgroup (32 per wave)
-constexpr int BS = 64;    // rows of a streamed block
 constexpr int PAD_ROWS = 8;    // tile read only with frag_rows: pitch DH + 8
 constexpr int PAD_COLS = 32;   // tile read only with frag_cols: pitch DH + 32
 constexpr int PAD_BOTH = 40;   // tile read both ways: pitch DH + 40
@@ -385,24 +386,27 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_bwd_d
   }
 }
 
-// Backward, dK and dV.  A workgroup owns 32 KG keys of one head; wave (kg, qg) keeps K and V of keys
-// 32 kg .. 32 kg + 31 as operand fragments and, of every streamed block of 32 QG queries (Q and dO
-// tiles plus their log-sum-exp and delta), takes queries 32 qg .. 32 qg + 31: dV^T += dO^T P and
-// dK^T += Q^T dS.  The QG partial sums of a key group are added in query-group order through LDS
-// at the end and written in place over K and V (a key block is read only by its own workgroup).
+// Backward, dK and dV.  A workgroup owns 32 KG keys of one head and streams blocks of 32 QG queries
+// (Q and dO tiles plus their log-sum-exp and delta).  Each (key group, query group) pair is served
+// by TWO waves with different roles, which halves the accumulators a wave has to hold:
+//   role 0 keeps K:  S = Q K^T,  P = exp2(S scale - lse),  dV^T += dO^T P;   hands P over through LDS;
+//   role 1 keeps V:  dP = dO V^T,  dS = P (dP - delta),     dK^T += Q^T dS.
+// Both roles run the same two matrix products per tile (one against Q, one against dO); only the
+// elementwise step between them differs.  The QG partial sums of a key group are added in
+// query-group order through LDS at the end and written in place over K and V (a key block is read
+// only by its own workgroup).
 template <int DH, int KG, int QG>
-__global__ __launch_bounds__(KG * QG * 64, 1) void attn_bwd_dkv_mfma(int seq, int heads, int causal, const bf16_t* qkv,
-                                                                      const float* __restrict__ lse,
-                                                                      const float* __restrict__ delta,
-                                                                      const bf16_t* __restrict__ d_o, bf16_t* dqkv,
-                                                                      float scale, float scale_log2) {
-  constexpr int NT = KG * QG * 64, BK = 32 * KG, BSQ = 32 * QG;
+__global__ __launch_bounds__(KG * QG * 128, KG * QG == 2 ? 3 : 1) void attn_bwd_dkv_mfma(
+    int seq, int heads, int causal, const bf16_t* qkv, const float* __restrict__ lse, const float* __restrict__ delta,
+    const bf16_t* __restrict__ d_o, bf16_t* dqkv, float scale, float scale_log2) {
+  constexpr int NP = KG * QG, NT = NP * 128, BK = 32 * KG, BSQ = 32 * QG;
   constexpr int QP = DH + PAD_BOTH;
   constexpr int QT = BSQ * QP;
-  extern __shared__ __attribute__((aligned(16))) bf16_t smem[];  // [2][Q tile | dO tile], then stats
+  extern __shared__ __attribute__((aligned(16))) bf16_t smem[];  // [2][Q tile | dO tile], stats, P exchange
   float* stats = reinterpret_cast<float*>(smem + 4 * QT);       // [2][lse2[BSQ] | delta[BSQ]]
+  float* xch = stats + 4 * BSQ;                                  // [NP][16 registers][64 lanes]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hl = lane >> 5;
-  const int kg = wave % KG, qg = wave / KG;
+  const int role = wave / NP, pair = wave % NP, kg = pair % KG, qg = pair / KG;
   const int h = heads * DH, head = blockIdx.y, b = blockIdx.z;
   const int k0 = blockIdx.x * BK, kw0 = k0 + 32 * kg, krow = kw0 + (lane & 31);
   const size_t ld = (size_t)3 * h;
@@ -411,21 +415,15 @@ __global__ __launch_bounds__(KG * QG * 64, 1) void attn_bwd_dkv_mfma(int seq, in
   const float* lse_b = lse + ((size_t)b * heads + head) * seq;
   const float* delta_b = delta + ((size_t)b * heads + head) * seq;
 
-  bf16x8 kf[DH / 16], vf[DH / 16];
+  bf16x8 kvf[DH / 16];  // role 0: K rows of this key group; role 1: V rows
   {
-    const bf16_t* kp = base + (size_t)min(krow, seq - 1) * ld + h + 8 * hl;
+    const bf16_t* kp = base + (size_t)min(krow, seq - 1) * ld + (role ? 2 * h : h) + 8 * hl;
 #pragma unroll
-    for (int ks = 0; ks < DH / 16; ++ks) {
-      kf[ks] = *reinterpret_cast<const bf16x8*>(kp + 16 * ks);
-      vf[ks] = *reinterpret_cast<const bf16x8*>(kp + h + 16 * ks);
-    }
+    for (int ks = 0; ks < DH / 16; ++ks) kvf[ks] = *reinterpret_cast<const bf16x8*>(kp + 16 * ks);
   }
-  f32x16 dk[DH / 32], dv[DH / 32];
+  f32x16 acc[DH / 32];  // role 0: dV^T, role 1: dK^T (unscaled)
 #pragma unroll
-  for (int dt = 0; dt < DH / 32; ++dt) {
-    zero(dk[dt]);
-    zero(dv[dt]);
-  }
+  for (int dt = 0; dt < DH / 32; ++dt) zero(acc[dt]);
   const int qstart = causal ? (k0 / BSQ) * BSQ : 0;
   const int nblk = (seq - qstart + BSQ - 1) / BSQ;
   BlockStager<BSQ, DH, QP, NT> sq, sdo;
@@ -443,54 +441,63 @@ __global__ __launch_bounds__(KG * QG * 64, 1) void attn_bwd_dkv_mfma(int seq, in
   sdo.store(smem + QT, tid);
   if (tid < 2 * BSQ) stats[tid] = st_reg;
   __syncthreads();
+  float* my_xch = xch + pair * (16 * 64) + lane;
   for (int blk = 0; blk < nblk; ++blk) {
-    const int q0 = qstart + blk * BSQ + 32 * qg;  // this wave's 32 queries
+    const int q0 = qstart + blk * BSQ + 32 * qg;  // the pair's 32 queries
     const int trow = 32 * qg;
     const bf16_t* qt_ = smem + (blk & 1) * 2 * QT;
     const bf16_t* dot_ = qt_ + QT;
-    const float* st_ = stats + (blk & 1) * 2 * BSQ + trow;
+    const bf16_t* first = role ? dot_ : qt_;    // role 0: S = Q K^T        role 1: dP = dO V^T
+    const bf16_t* second = role ? qt_ : dot_;   // role 0: dV^T += dO^T P   role 1: dK^T += Q^T dS
+    const float* st_ = stats + (blk & 1) * 2 * BSQ + (role ? BSQ : 0) + trow;  // lse2 (role 0) or delta (role 1)
     if (blk + 1 < nblk) {
       sq.load(base, ld, qstart + (blk + 1) * BSQ, seq, tid);
       sdo.load(dob, (size_t)h, qstart + (blk + 1) * BSQ, seq, tid);
       load_stats(qstart + (blk + 1) * BSQ);
     }
-    if (q0 < seq && (!causal || q0 + 31 >= kw0)) {
-      f32x16 s, dp;
-      zero(s);
-      zero(dp);
+    const bool active = q0 < seq && (!causal || q0 + 31 >= kw0);  // the same for both waves of a pair
+    f32x16 t;
+    if (active) {
+      zero(t);
 #pragma unroll
-      for (int ks = 0; ks < DH / 16; ++ks) {
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(qt_, QP, trow, 16 * ks, lane), kf[ks], s, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(dot_, QP, trow, 16 * ks, lane), vf[ks], dp, 0, 0, 0);
+      for (int ks = 0; ks < DH / 16; ++ks)
+        t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(first, QP, trow, 16 * ks, lane), kvf[ks], t, 0, 0, 0);
+      if (role == 0) {
+        if ((causal && q0 < kw0 + 31) || (q0 + 32 > seq) || (kw0 + 32 > seq)) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int qi = 8 * (r >> 2) + 4 * hl + (r & 3);
+            const int query = q0 + qi;
+            const bool dead = query >= seq || krow >= seq || (causal && krow > query);
+            t[r] = dead ? 0.f : __builtin_amdgcn_exp2f(__builtin_fmaf(t[r], scale_log2, -st_[qi]));
+          }
+        } else {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int qi = 8 * (r >> 2) + 4 * hl + (r & 3);
+            t[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(t[r], scale_log2, -st_[qi]));
+          }
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) my_xch[r * 64] = t[r];
       }
-      if ((causal && q0 < kw0 + 31) || (q0 + 32 > seq) || (kw0 + 32 > seq)) {
+    }
+    __syncthreads();  // P of every active pair is in LDS
+    if (active) {
+      if (role == 1) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int qi = 8 * (r >> 2) + 4 * hl + (r & 3);
-          const int query = q0 + qi;
-          const bool dead = query >= seq || krow >= seq || (causal && krow > query);
-          const float p = dead ? 0.f : __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, -st_[qi]));
-          s[r] = p;
-          dp[r] = p * (dp[r] - st_[BSQ + qi]);
-        }
-      } else {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int qi = 8 * (r >> 2) + 4 * hl + (r & 3);
-          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, -st_[qi]));
-          s[r] = p;
-          dp[r] = p * (dp[r] - st_[BSQ + qi]);
+          t[r] = my_xch[r * 64] * (t[r] - st_[qi]);
         }
       }
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const bf16x8 pb = acc_to_frag(s, t);
-        const bf16x8 dsb = acc_to_frag(dp, t);
+      for (int tt = 0; tt < 2; ++tt) {
+        const bf16x8 fb = acc_to_frag(t, tt);
 #pragma unroll
-        for (int dt = 0; dt < DH / 32; ++dt) {
-          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(dot_, QP, 32 * dt, trow + 16 * t, lane), pb, dv[dt], 0, 0, 0);
-          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(qt_, QP, 32 * dt, trow + 16 * t, lane), dsb, dk[dt], 0, 0, 0);
-        }
+        for (int dt = 0; dt < DH / 32; ++dt)
+          acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(second, QP, 32 * dt, trow + 16 * tt, lane), fb,
+                                                            acc[dt], 0, 0, 0);
       }
     }
     if (blk + 1 < nblk) {
@@ -499,44 +506,36 @@ __global__ __launch_bounds__(KG * QG * 64, 1) void attn_bwd_dkv_mfma(int seq, in
       sdo.store(nxt + QT, tid);
       if (tid < 2 * BSQ) stats[((blk + 1) & 1) * 2 * BSQ + tid] = st_reg;
     }
-    __syncthreads();
+    __syncthreads();  // next tiles staged; the exchange slots may be rewritten
   }
-  // Merge the query groups, one group after the other so that one set of slots is enough:
-  // slot of key group kg = [DH registers (dK then dV)][64 lanes] fp32.
-  constexpr int SLOT = DH * 64;
-  float* slots = reinterpret_cast<float*>(smem);
+  // Merge the query groups, one after the other so that one set of slots is enough:
+  // slot of (role, key group) = [DH/2 registers][64 lanes] fp32.
+  if (QG > 1) {
+    constexpr int SLOT = (DH / 2) * 64;
+    float* slot = reinterpret_cast<float*>(smem) + (role * KG + kg) * SLOT + lane;
 #pragma unroll 1
-  for (int g = 1; g < QG; ++g) {
-    if (qg == g) {
-      float* my = slots + kg * SLOT;
+    for (int g = 1; g < QG; ++g) {
+      if (qg == g) {
 #pragma unroll
-      for (int dt = 0; dt < DH / 32; ++dt)
+        for (int dt = 0; dt < DH / 32; ++dt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          my[(dt * 16 + r) * 64 + lane] = dk[dt][r];
-          my[(DH / 2 + dt * 16 + r) * 64 + lane] = dv[dt][r];
-        }
+          for (int r = 0; r < 16; ++r) slot[(dt * 16 + r) * 64] = acc[dt][r];
+      }
+      __syncthreads();
+      if (qg == 0) {
+#pragma unroll
+        for (int dt = 0; dt < DH / 32; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[dt][r] += slot[(dt * 16 + r) * 64];
+      }
+      __syncthreads();
     }
-    __syncthreads();
-    if (qg == 0) {
-      const float* other = slots + kg * SLOT;
-#pragma unroll
-      for (int dt = 0; dt < DH / 32; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          dk[dt][r] += other[(dt * 16 + r) * 64 + lane];
-          dv[dt][r] += other[(DH / 2 + dt * 16 + r) * 64 + lane];
-        }
-    }
-    __syncthreads();
   }
   if (qg == 0 && krow < seq) {
-    bf16_t* row = dqkv + ((size_t)b * seq + krow) * ld + (size_t)head * DH + h;
+    bf16_t* row = dqkv + ((size_t)b * seq + krow) * ld + (size_t)head * DH + (role ? h : 2 * h);
+    const float mul = role ? scale : 1.0f;
 #pragma unroll
-    for (int dt = 0; dt < DH / 32; ++dt) {
-      store_tile_t(row + 32 * dt, dk[dt], scale, lane);
-      store_tile_t(row + h + 32 * dt, dv[dt], 1.0f, lane);
-    }
+    for (int dt = 0; dt < DH / 32; ++dt) store_tile_t(row + 32 * dt, acc[dt], mul, lane);
   }
 }
 
@@ -577,8 +576,9 @@ template <int DH, int QW, int KW, int NKT, int KG, int QG>
 int bwd_launch(hipStream_t st, int batch, int seq, int heads, int causal, const void* qkv, const void* o, const float* lse,
                const void* d_o, void* dqkv, void* dq_stage, float* delta) {
   constexpr size_t lds_dq = 2 * sizeof(bf16_t) * 32 * NKT * KW * ((DH + PAD_BOTH) + (DH + PAD_ROWS));
-  constexpr size_t tiles_dkv = 4 * sizeof(bf16_t) * 32 * QG * (DH + PAD_BOTH) + 2 * 2 * 32 * QG * sizeof(float);
-  constexpr size_t merge_dkv = (size_t)KG * DH * 64 * sizeof(float);
+  constexpr size_t tiles_dkv =
+      4 * sizeof(bf16_t) * 32 * QG * (DH + PAD_BOTH) + (4 * 32 * QG + (size_t)KG * QG * 16 * 64) * sizeof(float);
+  constexpr size_t merge_dkv = QG > 1 ? (size_t)2 * KG * (DH / 2) * 64 * sizeof(float) : 0;
   constexpr size_t lds_dkv = tiles_dkv > merge_dkv ? tiles_dkv : merge_dkv;
   static_assert(lds_dq <= 160 * 1024 && lds_dkv <= 160 * 1024, "tiles exceed the LDS of a compute unit");
   static bool done_dq = false, done_dkv = false;
@@ -588,7 +588,7 @@ int bwd_launch(hipStream_t st, int batch, int seq, int heads, int causal, const 
   attn_bwd_dq_mfma<DH, QW, KW, NKT><<<dim3((seq + 32 * QW - 1) / (32 * QW), heads, batch), dim3(QW * KW * 64), lds_dq, st>>>(
       seq, heads, causal, (const bf16_t*)qkv, (const bf16_t*)o, lse, (const bf16_t*)d_o, (bf16_t*)dq_stage, delta, scale,
       scale_log2);
-  attn_bwd_dkv_mfma<DH, KG, QG><<<dim3((seq + 32 * KG - 1) / (32 * KG), heads, batch), dim3(KG * QG * 64), lds_dkv, st>>>(
+  attn_bwd_dkv_mfma<DH, KG, QG><<<dim3((seq + 32 * KG - 1) / (32 * KG), heads, batch), dim3(KG * QG * 128), lds_dkv, st>>>(
       seq, heads, causal, (const bf16_t*)qkv, lse, delta, (const bf16_t*)d_o, (bf16_t*)dqkv, scale, scale_log2);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(PMC_ERR_HIP, "attention_backward launch failed: %s", hipGetErrorString(e));
@@ -600,7 +600,7 @@ int bwd_t(hipStream_t st, int batch, int seq, int heads, int causal, const void*
           const void* d_o, void* dqkv, void* dq_stage, float* delta) {
   if (few_blocks(batch, seq, heads))
     return bwd_launch<DH, 2, 4, 1, 2, 2>(st, batch, seq, heads, causal, qkv, o, lse, d_o, dqkv, dq_stage, delta);
-  return bwd_launch<DH, 4, 1, 2, 4, 2>(st, batch, seq, heads, causal, qkv, o, lse, d_o, dqkv, dq_stage, delta);
+  return bwd_launch<DH, 4, 1, 2, 2, 1>(st, batch, seq, heads, causal, qkv, o, lse, d_o, dqkv, dq_stage, delta);
 }
 
 int check(const char* what, int batch, int seq, int heads, int dh, const void* qkv) {

@@ -17,6 +17,8 @@
 //        in place over K and V (a key block is read only by the workgroup that owns it).
 // The launch shapes are chosen by the number of (128-row block, head) pairs: few pairs get small
 // row blocks and more waves per block so that all compute units have work.
+#include <cstdlib>
+
 #include "dev_common.h"
 #include "kernels.h"
 
@@ -117,8 +119,10 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_fwd_m
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];  // [2][K tile | V tile]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hl = lane >> 5;
   const int qg = wave % QW, kg = wave / QW;
-  const int h = heads * DH, head = blockIdx.y, b = blockIdx.z;
-  const int q0 = blockIdx.x * BQW, qw0 = q0 + 32 * qg, qrow = qw0 + (lane & 31);
+  // grid = (heads * batch, query blocks); under a causal mask late query blocks see the most keys,
+  // so they are dealt out first and the short ones fill the tail
+  const int h = heads * DH, head = blockIdx.x % heads, b = blockIdx.x / heads;
+  const int q0 = (causal ? (int)(gridDim.y - 1 - blockIdx.y) : (int)blockIdx.y) * BQW, qw0 = q0 + 32 * qg, qrow = qw0 + (lane & 31);
   const size_t ld = (size_t)3 * h;
   const bf16_t* base = qkv + (size_t)b * seq * ld + (size_t)head * DH;
 
@@ -272,8 +276,10 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_bwd_d
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hl = lane >> 5;
   const int qg = wave % QW, kg = wave / QW;
-  const int h = heads * DH, head = blockIdx.y, b = blockIdx.z;
-  const int q0 = blockIdx.x * BQW, qw0 = q0 + 32 * qg, qrow = qw0 + (lane & 31);
+  // grid = (heads * batch, query blocks); under a causal mask late query blocks see the most keys,
+  // so they are dealt out first and the short ones fill the tail
+  const int h = heads * DH, head = blockIdx.x % heads, b = blockIdx.x / heads;
+  const int q0 = (causal ? (int)(gridDim.y - 1 - blockIdx.y) : (int)blockIdx.y) * BQW, qw0 = q0 + 32 * qg, qrow = qw0 + (lane & 31);
   const int qclamp = min(qrow, seq - 1);
   const size_t ld = (size_t)3 * h;
   const bf16_t* base = qkv + (size_t)b * seq * ld + (size_t)head * DH;
@@ -407,8 +413,9 @@ __global__ __launch_bounds__(KG * QG * 128, KG * QG == 2 ? 3 : 1) void attn_bwd_
   float* xch = stats + 4 * BSQ;                                  // [NP][16 registers][64 lanes]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hl = lane >> 5;
   const int role = wave / NP, pair = wave % NP, kg = pair % KG, qg = pair / KG;
-  const int h = heads * DH, head = blockIdx.y, b = blockIdx.z;
-  const int k0 = blockIdx.x * BK, kw0 = k0 + 32 * kg, krow = kw0 + (lane & 31);
+  // grid = (heads * batch, key blocks): early key blocks see the most queries and go first
+  const int h = heads * DH, head = blockIdx.x % heads, b = blockIdx.x / heads;
+  const int k0 = blockIdx.y * BK, kw0 = k0 + 32 * kg, krow = kw0 + (lane & 31);
   const size_t ld = (size_t)3 * h;
   const bf16_t* base = qkv + (size_t)b * seq * ld + (size_t)head * DH;
   const bf16_t* dob = d_o + (size_t)b * seq * h + (size_t)head * DH;
@@ -554,7 +561,7 @@ int fwd_launch(hipStream_t st, int batch, int seq, int heads, int causal, const 
   static bool done = false;
   if (int rc = reserve_lds(attn_fwd_mfma<DH, QW, KW, NKT>, lds, done, "attention_forward")) return rc;
   const float scale_log2 = kLog2e / sqrtf((float)DH);
-  attn_fwd_mfma<DH, QW, KW, NKT><<<dim3((seq + 32 * QW - 1) / (32 * QW), heads, batch), dim3(QW * KW * 64), lds, st>>>(
+  attn_fwd_mfma<DH, QW, KW, NKT><<<dim3(heads * batch, (seq + 32 * QW - 1) / (32 * QW)), dim3(QW * KW * 64), lds, st>>>(
       seq, heads, causal, (const bf16_t*)qkv, (bf16_t*)o, lse, scale_log2);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(PMC_ERR_HIP, "attention_forward launch failed: %s", hipGetErrorString(e));
@@ -564,11 +571,17 @@ int fwd_launch(hipStream_t st, int batch, int seq, int heads, int causal, const 
 // Few (128-query block, head) pairs: 64-query workgroups whose 8 waves split 128-key blocks four
 // ways, so that every compute unit gets work; otherwise 128-query workgroups of 4 waves, each
 // taking whole 64-key blocks, two workgroups to a compute unit.
-bool few_blocks(int batch, int seq, int heads) { return (long)((seq + 127) / 128) * heads * batch < 512; }
+// PMC_ATTN_SHAPE=0|1|2 in the environment forces a family of launch shapes (tests and tuning).
+int shape_family(int batch, int seq, int heads) {
+  if (const char* f = std::getenv("PMC_ATTN_SHAPE")) {
+    if (f[0] >= '0' && f[0] <= '2' && f[1] == 0) return f[0] - '0';
+  }
+  return (long)((seq + 127) / 128) * heads * batch < 512 ? 0 : 1;
+}
 
 template <int DH>
 int fwd_t(hipStream_t st, int batch, int seq, int heads, int causal, const void* qkv, void* o, float* lse) {
-  if (few_blocks(batch, seq, heads)) return fwd_launch<DH, 2, 4, 1>(st, batch, seq, heads, causal, qkv, o, lse);
+  if (shape_family(batch, seq, heads) == 0) return fwd_launch<DH, 2, 4, 1>(st, batch, seq, heads, causal, qkv, o, lse);
   return fwd_launch<DH, 4, 1, 2>(st, batch, seq, heads, causal, qkv, o, lse);
 }
 
@@ -585,10 +598,10 @@ int bwd_launch(hipStream_t st, int batch, int seq, int heads, int causal, const 
   if (int rc = reserve_lds(attn_bwd_dq_mfma<DH, QW, KW, NKT>, lds_dq, done_dq, "attention_backward")) return rc;
   if (int rc = reserve_lds(attn_bwd_dkv_mfma<DH, KG, QG>, lds_dkv, done_dkv, "attention_backward")) return rc;
   const float scale = 1.0f / sqrtf((float)DH), scale_log2 = kLog2e * scale;
-  attn_bwd_dq_mfma<DH, QW, KW, NKT><<<dim3((seq + 32 * QW - 1) / (32 * QW), heads, batch), dim3(QW * KW * 64), lds_dq, st>>>(
+  attn_bwd_dq_mfma<DH, QW, KW, NKT><<<dim3(heads * batch, (seq + 32 * QW - 1) / (32 * QW)), dim3(QW * KW * 64), lds_dq, st>>>(
       seq, heads, causal, (const bf16_t*)qkv, (const bf16_t*)o, lse, (const bf16_t*)d_o, (bf16_t*)dq_stage, delta, scale,
       scale_log2);
-  attn_bwd_dkv_mfma<DH, KG, QG><<<dim3((seq + 32 * KG - 1) / (32 * KG), heads, batch), dim3(KG * QG * 128), lds_dkv, st>>>(
+  attn_bwd_dkv_mfma<DH, KG, QG><<<dim3(heads * batch, (seq + 32 * KG - 1) / (32 * KG)), dim3(KG * QG * 128), lds_dkv, st>>>(
       seq, heads, causal, (const bf16_t*)qkv, lse, delta, (const bf16_t*)d_o, (bf16_t*)dqkv, scale, scale_log2);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(PMC_ERR_HIP, "attention_backward launch failed: %s", hipGetErrorString(e));
@@ -598,15 +611,16 @@ int bwd_launch(hipStream_t st, int batch, int seq, int heads, int causal, const 
 template <int DH>
 int bwd_t(hipStream_t st, int batch, int seq, int heads, int causal, const void* qkv, const void* o, const float* lse,
           const void* d_o, void* dqkv, void* dq_stage, float* delta) {
-  if (few_blocks(batch, seq, heads))
-    return bwd_launch<DH, 2, 4, 1, 2, 2>(st, batch, seq, heads, causal, qkv, o, lse, d_o, dqkv, dq_stage, delta);
+  const int fam = shape_family(batch, seq, heads);
+  if (fam == 0) return bwd_launch<DH, 2, 4, 1, 2, 2>(st, batch, seq, heads, causal, qkv, o, lse, d_o, dqkv, dq_stage, delta);
+  if (fam == 2) return bwd_launch<DH, 4, 1, 2, 4, 1>(st, batch, seq, heads, causal, qkv, o, lse, d_o, dqkv, dq_stage, delta);
   return bwd_launch<DH, 4, 1, 2, 2, 1>(st, batch, seq, heads, causal, qkv, o, lse, d_o, dqkv, dq_stage, delta);
 }
 
 int check(const char* what, int batch, int seq, int heads, int dh, const void* qkv) {
   if (batch <= 0 || seq <= 0 || heads <= 0) return fail(PMC_ERR_INVALID, "%s: batch=%d seq=%d heads=%d", what, batch, seq, heads);
   if (dh != 64 && dh != 128) return fail(PMC_ERR_INVALID, "%s: matrix-core path needs head size 64 or 128, got %d", what, dh);
-  if (heads > 65535 || batch > 65535) return fail(PMC_ERR_INVALID, "%s: heads/batch exceed the grid limit", what);
+  if (seq > 65535 * 32 || (long)heads * batch > 0x7fffffffL) return fail(PMC_ERR_INVALID, "%s: seq or heads*batch exceed the grid limit", what);
   if (reinterpret_cast<uintptr_t>(qkv) & 15) return fail(PMC_ERR_INVALID, "%s: qkv must be 16-byte aligned", what);
   return PMC_OK;
 }

@@ -64,12 +64,15 @@ __device__ __forceinline__ bf16x8 acc_to_frag(const f32x16& a, int t) {
 // row (no branches around the loads); whatever they contribute is masked by the caller.
 template <int ROWS, int DH, int P, int NT>
 struct BlockStager {
-  static constexpr int CH = ROWS * DH / 8 / NT;
+  static constexpr int CHUNKS = ROWS * DH / 8;          // 16-byte chunks in the block
+  static constexpr int CH = (CHUNKS + NT - 1) / NT;     // per thread (threads past the end idle)
+  static_assert(CHUNKS % NT == 0 || CHUNKS < NT, "block must split evenly over the threads");
   u32x4 r[CH];
   __device__ __forceinline__ void load(const bf16_t* __restrict__ base, size_t ld, int row0, int row_limit, int tid) {
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
       const int c = tid + i * NT, row = c / (DH / 8), cc = (c % (DH / 8)) * 8;
+      if (CHUNKS < NT && c >= CHUNKS) continue;
       const int gr = min(row0 + row, row_limit - 1);
       r[i] = *reinterpret_cast<const u32x4*>(base + (size_t)gr * ld + cc);
     }
@@ -78,6 +81,7 @@ struct BlockStager {
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
       const int c = tid + i * NT, row = c / (DH / 8), cc = (c % (DH / 8)) * 8;
+      if (CHUNKS < NT && c >= CHUNKS) continue;
       *reinterpret_cast<u32x4*>(tile + row * P + cc) = r[i];
     }
   }

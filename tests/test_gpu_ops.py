@@ -210,6 +210,35 @@ def test_attention_forward_backward(ctx, dtype, dh, causal):
     assert torch.equal(inplace, dq)
 
 
+@pytest.mark.parametrize("family", ["0", "1", "2"])
+@pytest.mark.parametrize("dh,causal", [(128, True), (64, True), (128, False)])
+def test_attention_launch_shapes(ctx, monkeypatch, family, dh, causal):
+    """Every family of workgroup shapes (key/query splits, merges through LDS) on a ragged
+    sequence that spans several streamed blocks; the library reads the override at each call."""
+    monkeypatch.setenv("PMC_ATTN_SHAPE", family)
+    batch, seq, heads = 2, 333, 2
+    h = heads * dh
+    key = ("attn-shape", dh, causal)
+    print("attention shape case", key, family, flush=True)
+    qkv = mat(key + ("qkv",), (batch * seq, 3 * h), "bf16")
+    d_o = mat(key + ("do",), (batch * seq, h), "bf16")
+    q64 = qkv.astype(np.float64)
+    o_ref, probs, lse_ref = OL.attention(q64, heads, causal, batch)
+    dqkv_ref = OL.attention_input_grad(d_o.astype(np.float64), q64, probs, heads, batch)
+    qd = dev(qkv, "bf16")
+    o = dev(np.zeros((batch * seq, h)), "bf16")
+    lse = torch.zeros(batch * heads * seq, device="cuda")
+    P.pmc_attention_forward(ctx, qd, o, lse, batch, seq, heads, dh, causal)
+    torch.cuda.synchronize()
+    assert rel_l2(host(o), o_ref) <= tol("bf16")
+    assert np.abs(host(lse) - lse_ref.reshape(-1)).max() <= 2e-2
+    dq = dev(np.zeros_like(qkv), "bf16")
+    P.pmc_attention_backward(ctx, qd, o, lse, dev(d_o, "bf16"), dq, batch, seq, heads, dh, causal)
+    torch.cuda.synchronize()
+    for name, cols in (("dq", slice(0, h)), ("dk", slice(h, 2 * h)), ("dv", slice(2 * h, 3 * h))):
+        assert rel_l2(host(dq)[:, cols], dqkv_ref[:, cols]) <= tol("bf16"), name
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_column_sum(ctx, dtype):
     for rows, n in ((1, 8), (50, 264), (1000, 2048), (300, 6144)):

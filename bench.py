@@ -26,10 +26,10 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix-core peak
 def flops_per_layer(h: int, ffn: int, s: int):
     """Algorithmic FLOP of one layer per pass.  GEMMs: 2*s*h*(3h + h + 2 ffn) in each of F, B, W.
     Attention (causal): F 2*s^2*h; B twice that (the model-FLOPs convention the paper inherits for
-    its MFU, Appendix D.1), the flash-style kernels execute 2.5x (score recomputation)."""
+    its MFU, Appendix D.1); the two backward kernels execute 3.5x (scores and dP are recomputed in both)."""
     gemm = 2 * s * h * (4 * h + 2 * ffn)
     return {"F": gemm + 2 * s * s * h, "B": gemm + 4 * s * s * h, "W": gemm,
-            "B_executed": gemm + 5 * s * s * h, "gemm": gemm}
+            "B_executed": gemm + 7 * s * s * h, "gemm": gemm}
 
 
 def main() -> int:

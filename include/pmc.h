@@ -168,6 +168,15 @@ int32_t pmc_schedule_microbatches(const pmc_schedule* s);
 int32_t pmc_schedule_num_passes(const pmc_schedule* s); /* 6 * n * d */
 /* Cell index of each pass of microbatch 0: out[6][d] in the row order F0, F1, B1, B0, W1, W0. */
 int pmc_schedule_block(const pmc_schedule* s, int32_t* out, int32_t capacity);
+/* The optional third step of the construction (Section 2 "Reordering", Appendix C): a new schedule
+ * in which, on the squeezed grid at unit pass times, warm-up bubbles before a device's first B are
+ * filled with later passes of that device (refused where the device's peak of live units would
+ * rise) and the W passes after a device's last F are re-placed into the bubbles of the cool-down,
+ * each after its own B.  The `time` of the result's passes is their cell in the final squeezed
+ * grid; per-device and global orders, accounting, makespan and replay take it like any schedule.
+ * A 1F1B schedule (fused B and W) is returned squeezed, its orders unchanged.  Host-only; the
+ * caller destroys *out. */
+int pmc_schedule_reorder(const pmc_schedule* s, pmc_schedule** out);
 /* One device's order (6n passes), sorted by cell; squeezing keeps this order (Section 2). */
 int pmc_schedule_device_order(const pmc_schedule* s, int32_t device, pmc_pass* out, int32_t capacity);
 /* The one-stream replay order: all passes by (cell, device). */

@@ -21,12 +21,16 @@ Readings where the paper is unclear (all listed in the design notes of the repos
    text is followed (the literal table reading collides for every d).
  * The same-device offsets of V-ZB are found by brute force in the paper and never printed;
    (1, 1, 1) is used.  best_vzb_offsets() below repeats the brute force and is pinned to that.
- * The optional reordering step of Section 2 is not applied.
+ * The optional reordering step of Section 2 is not part of build(); reordered() applies it, with
+   the readings stated there (warm-up moves may not raise a device's peak; the cool-down phase of
+   a device starts after its last F).
  * A 1F1B stage is two consecutive chunks with B and W fused per chunk, upper chunk first.
 
 Parity pins (tests/test_oracle_schedule.py): Section 3.2's exact peak formulas for every d, Table
 1's peaks for 1F1B and V-ZB, Equation 1 as an upper bound, independence of n, balance across
-devices, Table 1's bubble column, the bubble rate formula of Appendix D.3 for 1F1B.
+devices, Table 1's bubble column, the bubble rate formula of Appendix D.3 for 1F1B, Appendix E.1's
+condition for V-Half to have no repeating bubble, and for the reordering: unchanged peaks, the
+least possible makespan for V-ZB.
 """
 from __future__ import annotations
 
@@ -153,30 +157,35 @@ def build(kind: str, d: int, n: int):
 
 # --------------------------------------------------------------------------- lifetime accounting
 
+def _order_peak(order, kind: str) -> int:
+    live = peak = 0
+    for p in order:
+        if kind == "1f1b":
+            if p.op == "F" and p.chunk == 0:
+                live += 2
+            elif p.op == "W" and p.chunk == 0:
+                peak = max(peak, live)
+                live -= 2
+        else:
+            if p.op == "F":
+                live += 1
+            elif p.op == "W":
+                peak = max(peak, live)
+                live -= 1
+        peak = max(peak, live)
+    return peak
+
+
+def peak_units_of(passes, kind: str, d: int):
+    """Peak number of live activation units per device for any pass list (Section 2.2: a unit is
+    allocated when its F starts and retained until both its B and W are done).  For 1F1B the unit
+    of allocation is the stage: both chunks' units are taken when the stage's F starts and returned
+    when its fused backward ends."""
+    return [_order_peak(order, kind) for order in device_orders(passes, d)]
+
+
 def peak_units(kind: str, d: int, n: int):
-    """Peak number of live activation units per device (Section 2.2: a unit is allocated when its
-    F starts and retained until both its B and W are done).  For 1F1B the unit of allocation is the
-    stage: both chunks' units are taken when the stage's F starts and returned when its fused
-    backward ends."""
-    peaks = []
-    for order in device_orders(build(kind, d, n), d):
-        live = peak = 0
-        for p in order:
-            if kind == "1f1b":
-                if p.op == "F" and p.chunk == 0:
-                    live += 2
-                elif p.op == "W" and p.chunk == 0:
-                    peak = max(peak, live)
-                    live -= 2
-            else:
-                if p.op == "F":
-                    live += 1
-                elif p.op == "W":
-                    peak = max(peak, live)
-                    live -= 1
-            peak = max(peak, live)
-        peaks.append(peak)
-    return peaks
+    return peak_units_of(build(kind, d, n), kind, d)
 
 
 def peak_bytes(kind: str, d: int, n: int, unit_bytes: int, stats_bytes: int):
@@ -233,45 +242,59 @@ def equation1_bound(kind: str, d: int):
 
 # --------------------------------------------------------------------------- squeezing (unit times)
 
-def _asap_finish(passes, kind: str, d: int, dur):
-    """Run every device's order as early as dependencies allow and return the finish time.
+def _dependencies(p: Pass, kind: str, d: int):
+    """Keys (op, model chunk, microbatch) of the passes p waits for.  F of a model chunk needs F of
+    the previous chunk (same microbatch); B needs B of the next chunk (the last chunk's B needs its
+    own F); W needs its own B.  In 1F1B a stage's backward is one fused pass, so the stage before
+    it waits for the end of that pass."""
+    mc = model_chunk(kind, d, p.device, p.chunk)
+    last = 2 * d - 1
+    if p.op == "F":
+        return [("F", mc - 1, p.mb)] if mc > 0 else []
+    if p.op == "B":
+        if mc == last:
+            return [("F", mc, p.mb)]
+        if kind == "1f1b" and p.chunk == 1:
+            # B and W are one fused pass: the next stage hands its gradient over only when that
+            # whole pass (which ends with its lower chunk's W) is done
+            return [("W", mc + 1, p.mb)]
+        return [("B", mc + 1, p.mb)]
+    return [("B", mc, p.mb)]
 
-    Dependencies: F of a model chunk needs F of the previous chunk (same microbatch); B needs B of
-    the next chunk (the last chunk's B needs its own F); W needs its own B; a device runs one pass
-    at a time in its fixed order.  In 1F1B a stage's backward is one fused pass, so the stage
-    before it waits for the end of that pass."""
-    orders = device_orders(passes, d)
-    end = {}
+
+def _asap(orders, kind: str, d: int, dur):
+    """Run every device's order as early as dependencies allow: a device runs one pass at a time in
+    its fixed order.  Returns ({key: start}, {key: end}, finish time)."""
+    start, end = {}, {}
     nxt = [0] * d
     free_at = [0.0] * d
-    remaining = len(passes)
-    last = 2 * d - 1
+    remaining = sum(len(o) for o in orders)
     while remaining:
         progressed = False
         for i in range(d):
             while nxt[i] < len(orders[i]):
                 p = orders[i][nxt[i]]
-                mc = model_chunk(kind, d, p.device, p.chunk)
-                if p.op == "F":
-                    deps = [("F", mc - 1, p.mb)] if mc > 0 else []
-                elif p.op == "B":
-                    deps = [("B", mc + 1, p.mb)] if mc < last else [("F", mc, p.mb)]
-                    if kind == "1f1b" and p.chunk == 1 and mc < last:
-                        # B and W are one fused pass: the next stage hands its gradient over
-                        # only when that whole pass (which ends with its lower chunk's W) is done
-                        deps = [("W", mc + 1, p.mb)]
-                else:
-                    deps = [("B", mc, p.mb)]
+                deps = _dependencies(p, kind, d)
                 if any(dep not in end for dep in deps):
                     break
-                start = max([free_at[i]] + [end[dep] for dep in deps])
-                end[(p.op, mc, p.mb)] = free_at[i] = start + dur[p.op]
+                k = (p.op, model_chunk(kind, d, p.device, p.chunk), p.mb)
+                start[k] = max([free_at[i]] + [end[dep] for dep in deps])
+                end[k] = free_at[i] = start[k] + dur[p.op]
                 nxt[i] += 1
                 remaining -= 1
                 progressed = True
         if not progressed:
             raise RuntimeError("deadlock: orders contradict dependencies")
-    return max(free_at)
+    return start, end, max(free_at)
+
+
+def _asap_finish(passes, kind: str, d: int, dur):
+    return _asap(device_orders(passes, d), kind, d, dur)[2]
+
+
+def makespan_of(passes, kind: str, d: int, tf: float = 1.0, tb: float = 1.0, tw: float = 1.0):
+    """Finish time of any pass list when every device runs its order as early as it can."""
+    return _asap_finish(passes, kind, d, {"F": tf, "B": tb, "W": tw})
 
 
 def squeezed_makespan(kind: str, d: int, n: int, tf: float = 1.0, tb: float = 1.0, tw: float = 1.0):
@@ -306,3 +329,68 @@ def best_vzb_offsets(d: int, n: int | None = None):
         scored.append(((peak, span), (a, b, c)))
     best = min(s for s, _ in scored)
     return sorted(t for s, t in scored if s == best)
+
+
+# --------------------------------------------------------------------------- reordering (Appendix C)
+
+def reordered(kind: str, d: int, n: int):
+    """The optional third step of Section 2, after the two greedy heuristics of Appendix C, on the
+    squeezed grid with unit pass times.  Returns the passes with `time` set to their cell in the
+    final squeezed grid (so device_orders / global_order apply unchanged).
+
+    Warm-up: cells are visited left to right (devices in index order within a column); a vacant
+    cell of a device that lies before that device's first B is filled with the first later pass of
+    the same device whose dependencies have all ended by that cell, every other pass staying where
+    it is.  Reading: a move is refused if it would lift the device's peak of live units above its
+    peak before reordering (the paper states that reordering leaves the peak unchanged, Section 2).
+    Cool-down: on every device the W passes after its last F are taken out, the rest is squeezed,
+    and the vacant cells after the last F are then filled left to right, each with the first
+    removed W (in their former order) whose B has ended; what is left goes to the end.
+    A 1F1B stage runs B and W fused, so nothing of it can move: it is returned squeezed only."""
+    unit = {"F": 1, "B": 1, "W": 1}
+    key = lambda p: (p.op, model_chunk(kind, d, p.device, p.chunk), p.mb)
+    orders = device_orders(build(kind, d, n), d)
+    start, end, _ = _asap(orders, kind, d, unit)
+    if kind != "1f1b":
+        base_peak = [_order_peak(o, kind) for o in orders]
+        cells = [{int(start[key(p)]): p for p in orders[i]} for i in range(d)]
+        first_b = [min(c for c, p in cells[i].items() if p.op == "B") for i in range(d)]
+        for t in range(max(first_b)):
+            for i in range(d):
+                if t >= first_b[i] or t in cells[i]:
+                    continue
+                for c in sorted(c for c in cells[i] if c > t):
+                    p = cells[i][c]
+                    if any(end[dep] > t for dep in _dependencies(p, kind, d)):
+                        continue
+                    trial = dict(cells[i])
+                    del trial[c]
+                    trial[t] = p
+                    if _order_peak([trial[x] for x in sorted(trial)], kind) > base_peak[i]:
+                        continue
+                    cells[i] = trial
+                    start[key(p)], end[key(p)] = t, t + 1
+                    break
+        orders = [[cells[i][c] for c in sorted(cells[i])] for i in range(d)]
+        kept, removed = [], []
+        for order in orders:
+            last_f = max(j for j, p in enumerate(order) if p.op == "F")
+            kept.append([p for j, p in enumerate(order) if not (p.op == "W" and j > last_f)])
+            removed.append([p for j, p in enumerate(order) if p.op == "W" and j > last_f])
+        start, end, _ = _asap(kept, kind, d, unit)
+        orders = []
+        for i in range(d):
+            cells_i = {int(start[key(p)]): p for p in kept[i]}
+            pending = list(removed[i])
+            t = max(c for c, p in cells_i.items() if p.op == "F") + 1
+            while pending:
+                if t not in cells_i:
+                    ready = [w for w in pending if end[("B", model_chunk(kind, d, w.device, w.chunk), w.mb)] <= t]
+                    if ready:
+                        cells_i[t] = ready[0]
+                        pending.remove(ready[0])
+                t += 1
+            orders.append([cells_i[c] for c in sorted(cells_i)])
+        start, end, _ = _asap(orders, kind, d, unit)
+    return [Pass(int(start[key(p)]), p.device, p.op, p.chunk, p.mb) for order in orders for p in order]
+

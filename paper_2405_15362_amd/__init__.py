@@ -81,6 +81,7 @@ _SIGS = {
     "stage_backward_weight": (C.c_int, [_vp, C.POINTER(_i32), _i32]),
     "pmc_schedule_build": (C.c_int, [_i32, _i32, _i32, C.POINTER(_vp)]),
     "pmc_schedule_build_vshape": (C.c_int, [_i32] * 7 + [C.POINTER(_vp)]),
+    "pmc_schedule_reorder": (C.c_int, [_vp, C.POINTER(_vp)]),
     "pmc_schedule_destroy": (None, [_vp]),
     "pmc_schedule_devices": (_i32, [_vp]),
     "pmc_schedule_microbatches": (_i32, [_vp]),
@@ -246,6 +247,13 @@ def pmc_schedule_build(kind, d: int, n: int):
 def pmc_schedule_build_vshape(d, n, delta0, delta1, turn_f, turn_fb, turn_b):
     out = _vp()
     _check(lib.pmc_schedule_build_vshape(d, n, delta0, delta1, turn_f, turn_fb, turn_b, C.byref(out)))
+    return out
+
+
+def pmc_schedule_reorder(s):
+    """A new schedule with the warm-up and cool-down reordered; the caller destroys it."""
+    out = _vp()
+    _check(lib.pmc_schedule_reorder(s, C.byref(out)))
     return out
 
 

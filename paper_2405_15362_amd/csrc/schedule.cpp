@@ -229,6 +229,181 @@ int makespan(const Schedule& s, double tf, double tb, double tw, double* out) {
   return PMC_OK;
 }
 
+namespace {
+
+// Integer-cell view of a schedule at unit pass times, used by the reordering heuristics.
+struct Grid {
+  int d, n, last;
+  bool fused;
+  std::vector<int32_t> end;  // [3][2d][n]: end cell of (op, model chunk, microbatch), -1 = not placed
+  size_t idx(int op, int mc, int mb) const { return ((size_t)op * 2 * d + mc) * n + mb; }
+  // the one pass p waits for, or op = -1
+  void dependency(const pmc_pass& p, int& op, int& mc) const {
+    op = -1;
+    mc = 0;
+    if (p.op == PMC_F) {
+      if (p.model_chunk > 0) op = PMC_F, mc = p.model_chunk - 1;
+    } else if (p.op == PMC_B) {
+      if (p.model_chunk == last) op = PMC_F, mc = last;
+      else if (fused && p.chunk == 1) op = PMC_W, mc = p.model_chunk + 1;
+      else op = PMC_B, mc = p.model_chunk + 1;
+    } else {
+      op = PMC_B, mc = p.model_chunk;
+    }
+  }
+};
+
+// Squeezes the given per-device orders at unit times: writes every pass's start cell into
+// pass.time and its end into g.end.  False if the orders contradict the dependencies.
+bool squeeze_unit(Grid& g, std::vector<std::vector<pmc_pass>>& orders) {
+  std::fill(g.end.begin(), g.end.end(), -1);
+  std::vector<size_t> next(g.d, 0);
+  std::vector<int32_t> free_at(g.d, 0);
+  size_t remaining = 0;
+  for (auto& o : orders) remaining += o.size();
+  while (remaining) {
+    bool progressed = false;
+    for (int i = 0; i < g.d; ++i) {
+      while (next[i] < orders[i].size()) {
+        pmc_pass& p = orders[i][next[i]];
+        int op, mc;
+        g.dependency(p, op, mc);
+        int32_t start = free_at[i];
+        if (op >= 0) {
+          const int32_t e = g.end[g.idx(op, mc, p.mb)];
+          if (e < 0) break;
+          start = std::max(start, e);
+        }
+        p.time = start;
+        free_at[i] = g.end[g.idx(p.op, p.model_chunk, p.mb)] = start + 1;
+        ++next[i];
+        --remaining;
+        progressed = true;
+      }
+    }
+    if (!progressed) return false;
+  }
+  return true;
+}
+
+int64_t peak_units_of(const std::vector<pmc_pass>& order) {
+  int64_t live = 0, peak = 0;
+  for (const pmc_pass& p : order) {
+    if (p.op == PMC_F) peak = std::max(peak, ++live);
+    else if (p.op == PMC_W) --live;
+  }
+  return peak;
+}
+
+void sort_by_cell(std::vector<pmc_pass>& v) {
+  std::sort(v.begin(), v.end(), [](const pmc_pass& a, const pmc_pass& b) { return a.time < b.time; });
+}
+
+}  // namespace
+
+// Section 2 "Reordering" with the two greedy heuristics of Appendix C, on the squeezed grid at
+// unit pass times.  Warm-up: vacant cells before a device's first B are filled, left to right, with
+// the first later pass of that device whose dependency has ended, all other passes staying put; a
+// move that would raise the device's peak of live units is refused (the reordering is stated to
+// leave the peak unchanged).  Cool-down: the W passes after a device's last F are taken out, the
+// rest is squeezed, and the vacant cells after the last F are filled left to right with the first
+// removed W whose B has ended; the remainder goes to the end.  The result's `time` fields are the
+// cells of the final squeezed grid.  A fused-backward (1F1B) schedule is only squeezed.
+int reorder(const Schedule& in, Schedule& out) {
+  out = in;
+  const int d = in.d, n = in.n;
+  Grid g{d, n, 2 * d - 1, in.grouped_bw, std::vector<int32_t>((size_t)3 * 2 * d * n, -1)};
+  auto& orders = out.per_device;
+  if (!squeeze_unit(g, orders)) return fail(PMC_ERR_ILLEGAL_BLOCK, "orders contradict the dependencies");
+  if (!in.grouped_bw) {
+    std::vector<int64_t> base_peak(d);
+    std::vector<int32_t> first_b(d, 0);
+    int32_t horizon = 0;
+    for (int i = 0; i < d; ++i) {
+      base_peak[i] = peak_units_of(orders[i]);
+      for (const pmc_pass& p : orders[i])
+        if (p.op == PMC_B) {
+          first_b[i] = p.time;
+          break;
+        }
+      horizon = std::max(horizon, first_b[i]);
+    }
+    // warm-up: orders[i] stays sorted by cell throughout
+    for (int32_t t = 0; t < horizon; ++t)
+      for (int i = 0; i < d; ++i) {
+        if (t >= first_b[i]) continue;
+        auto& o = orders[i];
+        auto at = std::lower_bound(o.begin(), o.end(), t, [](const pmc_pass& p, int32_t c) { return p.time < c; });
+        if (at != o.end() && at->time == t) continue;  // occupied
+        const size_t pos = at - o.begin();               // the moved pass is inserted here
+        for (size_t k = pos; k < o.size(); ++k) {
+          pmc_pass p = o[k];
+          int op, mc;
+          g.dependency(p, op, mc);
+          if (op >= 0 && g.end[g.idx(op, mc, p.mb)] > t) continue;
+          std::vector<pmc_pass> trial(o);
+          trial.erase(trial.begin() + k);
+          p.time = t;
+          trial.insert(trial.begin() + pos, p);
+          if (peak_units_of(trial) > base_peak[i]) continue;
+          o.swap(trial);
+          g.end[g.idx(p.op, p.model_chunk, p.mb)] = t + 1;
+          break;
+        }
+      }
+    if (!squeeze_unit(g, orders)) return fail(PMC_ERR_ILLEGAL_BLOCK, "warm-up reordering broke a dependency");
+    // cool-down
+    std::vector<std::vector<pmc_pass>> removed(d);
+    for (int i = 0; i < d; ++i) {
+      auto& o = orders[i];
+      size_t last_f = 0;
+      for (size_t k = 0; k < o.size(); ++k)
+        if (o[k].op == PMC_F) last_f = k;
+      std::vector<pmc_pass> kept;
+      for (size_t k = 0; k < o.size(); ++k) {
+        if (o[k].op == PMC_W && k > last_f) removed[i].push_back(o[k]);
+        else kept.push_back(o[k]);
+      }
+      o.swap(kept);
+    }
+    if (!squeeze_unit(g, orders)) return fail(PMC_ERR_ILLEGAL_BLOCK, "cool-down reordering broke a dependency");
+    for (int i = 0; i < d; ++i) {
+      auto& o = orders[i];
+      int32_t t = 0;
+      for (const pmc_pass& p : o)
+        if (p.op == PMC_F) t = p.time + 1;
+      std::vector<pmc_pass>& pending = removed[i];
+      size_t scan = 0;  // first kept pass at or after cell t
+      while (scan < o.size() && o[scan].time < t) ++scan;
+      std::vector<pmc_pass> placed;
+      while (!pending.empty()) {
+        if (scan < o.size() && o[scan].time == t) {
+          ++scan;
+        } else {
+          for (size_t k = 0; k < pending.size(); ++k)
+            if (g.end[g.idx(PMC_B, pending[k].model_chunk, pending[k].mb)] <= t) {
+              pmc_pass w = pending[k];
+              w.time = t;
+              placed.push_back(w);
+              pending.erase(pending.begin() + k);
+              break;
+            }
+        }
+        ++t;
+      }
+      o.insert(o.end(), placed.begin(), placed.end());
+      sort_by_cell(o);
+    }
+    if (!squeeze_unit(g, orders)) return fail(PMC_ERR_ILLEGAL_BLOCK, "reordering broke a dependency");
+  }
+  out.passes.clear();
+  for (auto& v : orders) out.passes.insert(out.passes.end(), v.begin(), v.end());
+  std::sort(out.passes.begin(), out.passes.end(), [](const pmc_pass& a, const pmc_pass& b) {
+    return a.time != b.time ? a.time < b.time : a.device < b.device;
+  });
+  return PMC_OK;
+}
+
 }  // namespace pmc
 
 using pmc::fail;
@@ -259,6 +434,19 @@ int pmc_schedule_build_vshape(int32_t d, int32_t n, int32_t delta0, int32_t delt
     return rc;
   }
   *out = s;
+  return PMC_OK;
+}
+
+int pmc_schedule_reorder(const pmc_schedule* s, pmc_schedule** out) {
+  if (!s || !out) return fail(PMC_ERR_INVALID, "NULL argument");
+  auto* r = new (std::nothrow) pmc_schedule;
+  if (!r) return fail(PMC_ERR_NOMEM, "host allocation failed");
+  int rc = pmc::reorder(s->s, r->s);
+  if (rc != PMC_OK) {
+    delete r;
+    return rc;
+  }
+  *out = r;
   return PMC_OK;
 }
 

@@ -115,3 +115,34 @@ def test_bad_cfg_is_rejected():
     assert P.pmc_activation_bytes(P.make_cfg(1, 100, 3, 400, 64)) == 0       # hidden % heads
     assert P.pmc_activation_bytes(P.make_cfg(1, 2048, 4, 8192, 64)) == 0     # head size 512
     assert P.pmc_activation_bytes(P.make_cfg(0, 256, 4, 1024, 64)) == 0
+
+
+@pytest.mark.parametrize("kind", S.KINDS)
+@pytest.mark.parametrize("d,n", [(1, 3), (2, 5), (3, 7), (4, 16), (6, 24), (8, 20), (9, 12)])
+def test_reorder_matches_oracle(kind, d, n):
+    """Warm-up / cool-down reordering: the library's orders, cells, accounting and makespan against
+    the oracle's, pass for pass."""
+    s = P.pmc_schedule_build(kind, d, n)
+    r = P.pmc_schedule_reorder(s)
+    try:
+        ref = S.reordered(kind, d, n)
+        got = [(p.time, p.device, p.op, p.chunk, p.mb) for p in P.pmc_schedule_global_order(r)]
+        assert got == [(p.time, p.device, p.op, p.chunk, p.mb) for p in S.global_order(ref)]
+        for i, order in enumerate(S.device_orders(ref, d)):
+            dev = [(p.time, p.op, p.chunk, p.mb, p.model_chunk) for p in P.pmc_schedule_device_order(r, i)]
+            assert dev == [(p.time, p.op, p.chunk, p.mb, S.model_chunk(kind, d, i, p.chunk)) for p in order]
+        assert [a[0] for a in P.pmc_schedule_account(r, 1000, 40)] == S.peak_units_of(ref, kind, d)
+        for times in ((1.0, 1.0, 1.0), (1.0, 1.3, 0.6)):
+            assert P.pmc_schedule_makespan(r, *times) == pytest.approx(S.makespan_of(ref, kind, d, *times), rel=1e-12)
+        # the input schedule is left as it was
+        assert P.pmc_schedule_global_order(s) == P.pmc_schedule_global_order(P.pmc_schedule_build(kind, d, n))
+    finally:
+        P.pmc_schedule_destroy(s)
+        P.pmc_schedule_destroy(r)
+
+
+def test_reorder_rejects_null():
+    with pytest.raises(P.PmcError) as e:
+        P.pmc_schedule_reorder(None)
+    assert e.value.code == P.PMC_ERR_INVALID
+

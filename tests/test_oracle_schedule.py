@@ -152,6 +152,38 @@ def test_1f1b_bubble_rate(p, n):
     assert (span - 6 * n) / span == pytest.approx((p - 1) / (p + n - 1))
 
 
+def _bubble_growth(kind, d, tf, tb, tw):
+    """How much the idle time of the squeezed schedule grows from n = 6d to n = 10d microbatches."""
+    def idle(n):
+        return S.squeezed_makespan(kind, d, n, tf, tb, tw) - 2 * n * (tf + tb + tw)
+    return idle(10 * d) - idle(6 * d)
+
+
+_TIMES = [(tf, tb, tw) for tf in (0.5, 1.0, 2.0, 3.0) for tb in (0.5, 1.0, 2.0, 3.0) for tw in (0.25, 0.5, 1.0, 2.0, 3.0)]
+
+
+@pytest.mark.parametrize("d", [2, 3, 4, 5, 6, 8])
+def test_vhalf_repeating_bubble_condition(d):
+    """Appendix E.1: V-Half has no repeating bubble (idle time independent of n) exactly when
+    T_W + 2 T_B >= 2 T_F and T_W + 2 T_F >= 2 T_B.  The timed simulation must reproduce that
+    boundary for every combination of pass times tried, in both directions."""
+    for tf, tb, tw in _TIMES:
+        no_repeat = tw + 2 * tb >= 2 * tf and tw + 2 * tf >= 2 * tb
+        g = _bubble_growth("vhalf", d, tf, tb, tw)
+        assert (abs(g) < 1e-9) == no_repeat, (d, tf, tb, tw, g)
+        assert g >= -1e-9
+
+
+@pytest.mark.parametrize("d", [3, 4, 8])
+def test_vzb_and_vmin_repeating_bubbles(d):
+    """Section 3.3 / Appendix E.1: V-ZB's bubbles never grow with the number of microbatches;
+    V-Min's do not grow with equal pass times but do when W is much shorter than F and B."""
+    for tf, tb, tw in _TIMES:
+        assert abs(_bubble_growth("vzb", d, tf, tb, tw)) < 1e-9, (tf, tb, tw)
+    assert abs(_bubble_growth("vmin", d, 1.0, 1.0, 1.0)) < 1e-9
+    assert _bubble_growth("vmin", d, 1.0, 1.0, 0.25) > d
+
+
 @pytest.mark.parametrize("kind", S.KINDS)
 @pytest.mark.parametrize("d", [4, 8])
 def test_runtime_lower_bound(kind, d):
@@ -196,3 +228,61 @@ def test_peak_bytes_table():
         assert [g[0] for g in got] == [u * m for u in units]
         for (pool, tensor), u in zip(got, units):
             assert pool - u * st <= tensor <= pool
+
+
+# --------------------------------------------------------------------------- reordering (Appendix C)
+
+def _keys(passes):
+    return sorted((p.device, p.op, p.chunk, p.mb) for p in passes)
+
+
+@pytest.mark.parametrize("kind", S.KINDS)
+@pytest.mark.parametrize("d,n", [(1, 3), (2, 2), (2, 7), (3, 9), (4, 16), (5, 11), (6, 24), (8, 32), (10, 20)])
+def test_reordering_is_a_valid_schedule(kind, d, n):
+    """Reordering permutes each device's passes and nothing else: same multiset of passes, one per
+    cell, every dependency in an earlier cell (so W follows its own B), and - Section 2 - the peak
+    of live units of every device is what it was before."""
+    base = S.build(kind, d, n)
+    r = S.reordered(kind, d, n)
+    assert _keys(r) == _keys(base)
+    assert len({(p.device, p.time) for p in r}) == len(r)
+    cell = {(p.op, S.model_chunk(kind, d, p.device, p.chunk), p.mb): p.time for p in r}
+    for p in r:
+        for dep in S._dependencies(p, kind, d):
+            assert cell[dep] < p.time, (p, dep)
+    assert S.peak_units_of(r, kind, d) == S.peak_units(kind, d, n)
+    # the cells ARE the squeezed grid of the new order: squeezing again moves nothing
+    assert S.makespan_of(r, kind, d) == max(p.time for p in r) + 1
+
+
+@pytest.mark.parametrize("d", [2, 3, 4, 6, 8, 12])
+def test_reordering_bubbles(d):
+    """Never slower than squeezing alone; 1F1B (fused backward) is untouched; V-ZB reaches the least
+    any V-shape schedule can have at unit times - the last device cannot start before cell d-1 (its
+    first F waits for d-1 others) and has 6n cells of work - which is Table 1's "0" up to the
+    constants it ignores, with the first device never idle; and Appendix E.2's bound holds."""
+    n = 4 * d
+    span = {}
+    for kind in S.KINDS:
+        r = S.reordered(kind, d, n)
+        span[kind] = S.makespan_of(r, kind, d)
+        assert span[kind] <= S.squeezed_makespan(kind, d, n)
+        k = max(S.peak_units_of(r, kind, d))
+        assert span[kind] >= 6 * n + 6 * d - 3 * k - 1
+    assert span["1f1b"] == S.squeezed_makespan("1f1b", d, n) == 6 * n + 6 * (d - 1)
+    assert span["vzb"] == 6 * n + d - 1
+    first_device = sorted(p.time for p in S.reordered("vzb", d, n) if p.device == 0)
+    assert first_device == list(range(6 * n))
+    assert span["vzb"] <= span["vhalf"] <= span["vmin"] <= span["1f1b"]
+
+
+def test_reordering_keeps_weight_gradient_order_per_chunk():
+    """W passes of one chunk stay in microbatch order, so fp32 accumulation of dW adds the
+    microbatches in the same order with and without reordering."""
+    for kind in ("vzb", "vhalf", "vmin"):
+        for d, n in ((2, 6), (4, 16), (6, 13)):
+            for order in S.device_orders(S.reordered(kind, d, n), d):
+                for chunk in (0, 1):
+                    mbs = [p.mb for p in order if p.op == "W" and p.chunk == chunk]
+                    assert mbs == sorted(mbs)
+

@@ -194,8 +194,16 @@ def main() -> int:
         mem[kind] = {"peak_units": [a[0] for a in acc], "max_peak_bytes": max(a[1] for a in acc),
                      "bubble_rate": round(1.0 - work / span, 4),
                      "bubble_rate_reordered": round(1.0 - work / span_reo, 4)}
-    for kind in mem:
+    for kind in list(mem):
         mem[kind]["vs_1f1b"] = round(mem[kind]["max_peak_bytes"] / mem["1f1b"]["max_peak_bytes"], 4)
+    # the adaptive scheduler (Appendix A/B) under a limit of k live units per device, same pass times
+    adaptive = {}
+    for k in range(4, 9):
+        sch, res = P.pmc_schedule_search(d_sim, n_sim, k, t_f, t_b, t_w)
+        P.pmc_schedule_destroy(sch)
+        adaptive[str(k)] = {"peak_units": res["peak_units"], "vs_1f1b": round(res["peak_units"] / 8.0, 4),
+                            "bubble_rate": round(1.0 - 2 * n_sim * (t_f + t_b + t_w) / res["makespan"], 4)}
+    mem["adaptive_by_limit_units"] = adaptive
     out["peak_activation"] = {"config": "d=4, n=16, 2-layer chunks hidden 4096 seq 2048 bf16 (accounting); "
                                         f"bubble rate from this workload's measured F/B/W = {t_f}/{t_b}/{t_w} ms", **mem}
 

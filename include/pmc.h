@@ -177,6 +177,25 @@ int pmc_schedule_block(const pmc_schedule* s, int32_t* out, int32_t capacity);
  * A 1F1B schedule (fused B and W) is returned squeezed, its orders unchanged.  Host-only; the
  * caller destroys *out. */
 int pmc_schedule_reorder(const pmc_schedule* s, pmc_schedule** out);
+/* Adaptive V-shape scheduler (Appendix A): minimises the finish time under an activation-memory
+ * limit.  Search space: the split K (first K devices / the rest), the four offsets
+ * delta^0_{<K}, delta^1_{<=K}, delta^0_{>=K}, delta^1_{>K} in 1..max_delta, and the three
+ * same-device offsets in 1..6 (the residues of the first device's passes).  A block is dropped if
+ * it collides when repeated or if some device's peak of live units over the n microbatches exceeds
+ * limit_units (units of one chunk's activation, m = M / 2d); the others are squeezed, reordered if
+ * `reorder` is non-zero, and timed with t_f, t_b, t_w; the first block (loops nested in the order
+ * of pmc_search_result's fields) with the least finish time wins.  Host-only, allocates host memory
+ * only; cost grows as d * max_delta^4 * 216 blocks.  Returns PMC_ERR_ILLEGAL_BLOCK if no block
+ * fits the limit.  result may be NULL; the caller destroys *out. */
+typedef struct pmc_search_result {
+  int32_t split, delta0_lo, delta1_lo, delta0_hi, delta1_hi, turn_f, turn_fb, turn_b;
+  int64_t peak_units;   /* largest per-device peak of the winning block                        */
+  double makespan;      /* its finish time with the given pass times                            */
+  int64_t candidates;   /* blocks visited                                                       */
+  int64_t feasible;     /* of those: collision-free and within the limit                        */
+} pmc_search_result;
+int pmc_schedule_search(int32_t d, int32_t n, int64_t limit_units, double t_f, double t_b, double t_w,
+                        int32_t max_delta, int32_t reorder, pmc_search_result* result, pmc_schedule** out);
 /* One device's order (6n passes), sorted by cell; squeezing keeps this order (Section 2). */
 int pmc_schedule_device_order(const pmc_schedule* s, int32_t device, pmc_pass* out, int32_t capacity);
 /* The one-stream replay order: all passes by (cell, device). */

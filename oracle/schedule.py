@@ -334,6 +334,11 @@ def best_vzb_offsets(d: int, n: int | None = None):
 # --------------------------------------------------------------------------- reordering (Appendix C)
 
 def reordered(kind: str, d: int, n: int):
+    """Reordering applied to the schedule that build(kind, d, n) gives; see reordered_passes."""
+    return reordered_passes(build(kind, d, n), kind, d)
+
+
+def reordered_passes(passes, kind: str, d: int):
     """The optional third step of Section 2, after the two greedy heuristics of Appendix C, on the
     squeezed grid with unit pass times.  Returns the passes with `time` set to their cell in the
     final squeezed grid (so device_orders / global_order apply unchanged).
@@ -349,7 +354,7 @@ def reordered(kind: str, d: int, n: int):
     A 1F1B stage runs B and W fused, so nothing of it can move: it is returned squeezed only."""
     unit = {"F": 1, "B": 1, "W": 1}
     key = lambda p: (p.op, model_chunk(kind, d, p.device, p.chunk), p.mb)
-    orders = device_orders(build(kind, d, n), d)
+    orders = device_orders(passes, d)
     start, end, _ = _asap(orders, kind, d, unit)
     if kind != "1f1b":
         base_peak = [_order_peak(o, kind) for o in orders]
@@ -393,4 +398,80 @@ def reordered(kind: str, d: int, n: int):
             orders.append([cells_i[c] for c in sorted(cells_i)])
         start, end, _ = _asap(orders, kind, d, unit)
     return [Pass(int(start[key(p)]), p.device, p.op, p.chunk, p.mb) for order in orders for p in order]
+
+
+# --------------------------------------------------------------------------- adaptive search (Appendix A)
+
+def vshape_block_split(d: int, K: int, d0_lo: int, d1_lo: int, d0_hi: int, d1_hi: int, a: int, b: int, c: int):
+    """V-shape block whose offsets differ between the first K devices and the rest (Appendix A's
+    two-part constraint, devices numbered 1..d there):
+        delta F_i^0 = delta B_i^1 = d0_lo for 1 <= i < K,   d0_hi for K <= i < d,
+        delta F_i^1 = delta B_i^0 = d1_lo for 1 < i <= K,   d1_hi for K < i <= d,
+    with the three same-device offsets a, b, c of vshape_block (they fix which residue modulo T each
+    pass of the first device takes: the "permutation of the first device").  K = d is the uniform
+    block.  Returns None on a collision."""
+    down = [d0_lo if i + 1 < K else d0_hi for i in range(d - 1)]      # device i -> i+1 (0-based i)
+    up = [d1_lo if i + 1 <= K else d1_hi for i in range(1, d)]        # device i -> i-1, stored at i-1
+    tF0 = [0] * d
+    for i in range(d - 1):
+        tF0[i + 1] = tF0[i] + down[i]
+    tF1 = [0] * d
+    tF1[d - 1] = tF0[d - 1] + a
+    for i in range(d - 1, 0, -1):
+        tF1[i - 1] = tF1[i] + up[i - 1]
+    tB1 = [0] * d
+    tB1[0] = tF1[0] + b
+    for i in range(d - 1):
+        tB1[i + 1] = tB1[i] + down[i]
+    tB0 = [0] * d
+    tB0[d - 1] = tB1[d - 1] + c
+    for i in range(d - 1, 0, -1):
+        tB0[i - 1] = tB0[i] + up[i - 1]
+    tW1, tW0 = [0] * d, [0] * d
+    for i in range(d):
+        used = {tF0[i] % T, tF1[i] % T, tB1[i] % T, tB0[i] % T}
+        if len(used) != 4:
+            return None
+        for tB, tW in ((tB1, tW1), (tB0, tW0)):
+            t = tB[i] + 1
+            while t % T in used:
+                t += 1
+            used.add(t % T)
+            tW[i] = t
+    return {("F", 0): tF0, ("F", 1): tF1, ("B", 1): tB1, ("B", 0): tB0, ("W", 1): tW1, ("W", 0): tW0}
+
+
+def search_candidates(d: int, max_delta: int):
+    """Parameter tuples (K, d0_lo, d1_lo, d0_hi, d1_hi, a, b, c) in the order the search visits
+    them.  K = 1 would use the `hi` offsets everywhere and K = d the `lo` ones, so the uniform
+    blocks are visited once, as K = d with hi = lo."""
+    deltas = range(1, max_delta + 1)
+    for K in range(2 if d > 1 else 1, d + 1):
+        for d0_lo, d1_lo in product(deltas, deltas):
+            for d0_hi, d1_hi in (product(deltas, deltas) if K < d else [(d0_lo, d1_lo)]):
+                for a, b, c in product(range(1, T + 1), repeat=3):
+                    yield K, d0_lo, d1_lo, d0_hi, d1_hi, a, b, c
+
+
+def adaptive_search(d: int, n: int, limit_units: int, tf: float = 1.0, tb: float = 1.0, tw: float = 1.0,
+                    max_delta: int = T, reorder: bool = True):
+    """Appendix A as an exhaustive loop: every two-part block within the offset range is repeated
+    (collisions dropped), dropped if some device's peak of live units over the n microbatches
+    exceeds the limit, squeezed and (optionally) reordered, and timed with the given pass times;
+    the first block with the least finish time wins.  Returns (finish time, parameters, passes)
+    or None when no block fits the limit."""
+    best = None
+    for params in search_candidates(d, max_delta):
+        blk = vshape_block_split(d, *params)
+        if blk is None:
+            continue
+        passes = repeat(blk, d, n)
+        if max(peak_units_of(passes, "vshape", d)) > limit_units:
+            continue
+        if reorder:
+            passes = reordered_passes(passes, "vshape", d)
+        span = makespan_of(passes, "vshape", d, tf, tb, tw)
+        if best is None or span < best[0]:
+            best = (span, params, passes)
+    return best
 

@@ -82,6 +82,8 @@ _SIGS = {
     "pmc_schedule_build": (C.c_int, [_i32, _i32, _i32, C.POINTER(_vp)]),
     "pmc_schedule_build_vshape": (C.c_int, [_i32] * 7 + [C.POINTER(_vp)]),
     "pmc_schedule_reorder": (C.c_int, [_vp, C.POINTER(_vp)]),
+    "pmc_schedule_search": (C.c_int, [_i32, _i32, C.c_int64, C.c_double, C.c_double, C.c_double, _i32, _i32, _vp,
+                                      C.POINTER(_vp)]),
     "pmc_schedule_destroy": (None, [_vp]),
     "pmc_schedule_devices": (_i32, [_vp]),
     "pmc_schedule_microbatches": (_i32, [_vp]),
@@ -255,6 +257,19 @@ def pmc_schedule_reorder(s):
     out = _vp()
     _check(lib.pmc_schedule_reorder(s, C.byref(out)))
     return out
+
+
+class SearchResult(C.Structure):
+    _fields_ = [("split", C.c_int32), ("delta0_lo", C.c_int32), ("delta1_lo", C.c_int32), ("delta0_hi", C.c_int32),
+                ("delta1_hi", C.c_int32), ("turn_f", C.c_int32), ("turn_fb", C.c_int32), ("turn_b", C.c_int32),
+                ("peak_units", C.c_int64), ("makespan", C.c_double), ("candidates", C.c_int64), ("feasible", C.c_int64)]
+
+
+def pmc_schedule_search(d, n, limit_units, t_f=1.0, t_b=1.0, t_w=1.0, max_delta=6, reorder=True):
+    """Adaptive V-shape search under a memory limit: (schedule handle, dict of the winning block)."""
+    out, res = _vp(), SearchResult()
+    _check(lib.pmc_schedule_search(d, n, limit_units, t_f, t_b, t_w, max_delta, int(reorder), C.byref(res), C.byref(out)))
+    return out, {k: getattr(res, k) for k, _ in SearchResult._fields_}
 
 
 def pmc_schedule_destroy(s) -> None:

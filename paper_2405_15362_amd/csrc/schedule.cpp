@@ -53,6 +53,66 @@ bool vshape_block(int d, int delta0, int delta1, int turn_f, int turn_fb, int tu
   return true;
 }
 
+// Two-part V-shape block of the adaptive scheduler (Appendix A, devices numbered 1..d there):
+//   delta F_i^0 = delta B_i^1 = d0_lo for 1 <= i < K, d0_hi for K <= i < d;
+//   delta F_i^1 = delta B_i^0 = d1_lo for 1 < i <= K, d1_hi for K < i <= d;
+// K = d is the uniform block.  The same-device offsets pick the residue modulo T of each pass of
+// the first device ("the permutation of the first device").
+bool vshape_block_split(int d, int K, int d0_lo, int d1_lo, int d0_hi, int d1_hi, int turn_f, int turn_fb, int turn_b,
+                        std::vector<int32_t>& blk) {
+  blk.assign(6 * d, 0);
+  auto at = [&](int row, int i) -> int32_t& { return blk[row * d + i]; };
+  auto down = [&](int i) { return i + 1 < K ? d0_lo : d0_hi; };  // device i -> i + 1 (0-based i)
+  auto up = [&](int i) { return i + 1 <= K ? d1_lo : d1_hi; };   // device i -> i - 1
+  for (int i = 0; i + 1 < d; ++i) at(F0, i + 1) = at(F0, i) + down(i);
+  at(F1, d - 1) = at(F0, d - 1) + turn_f;
+  for (int i = d - 1; i > 0; --i) at(F1, i - 1) = at(F1, i) + up(i);
+  at(B1, 0) = at(F1, 0) + turn_fb;
+  for (int i = 0; i + 1 < d; ++i) at(B1, i + 1) = at(B1, i) + down(i);
+  at(B0, d - 1) = at(B1, d - 1) + turn_b;
+  for (int i = d - 1; i > 0; --i) at(B0, i - 1) = at(B0, i) + up(i);
+  for (int i = 0; i < d; ++i) {
+    bool used[T] = {false, false, false, false, false, false};
+    for (int row : {F0, F1, B1, B0}) {
+      int r = at(row, i) % T;
+      if (used[r]) return false;
+      used[r] = true;
+    }
+    const int b_rows[2] = {B1, B0}, w_rows[2] = {W1, W0};
+    for (int k = 0; k < 2; ++k) {
+      int t = at(b_rows[k], i) + 1;
+      while (used[t % T]) ++t;
+      used[t % T] = true;
+      at(w_rows[k], i) = t;
+    }
+  }
+  return true;
+}
+
+// Largest number of live units any device reaches when the block is repeated for n microbatches:
+// the live count can only peak when an F starts, and a unit of chunk c, microbatch j is live in
+// cells F_c + jT .. W_c + jT.
+int64_t block_peak_units(const std::vector<int32_t>& blk, int d, int n) {
+  const int f_rows[2] = {F0, F1}, w_rows[2] = {W0, W1};
+  int64_t peak = 0;
+  for (int i = 0; i < d; ++i)
+    for (int c = 0; c < 2; ++c)
+      for (int j = 0; j < n; ++j) {
+        const int64_t t = blk[f_rows[c] * d + i] + (int64_t)j * T;
+        int64_t live = 0;
+        for (int c2 = 0; c2 < 2; ++c2) {
+          const int64_t f = blk[f_rows[c2] * d + i], w = blk[w_rows[c2] * d + i];
+          // microbatches j2 with f + j2 T <= t <= w + j2 T
+          int64_t hi = (t - f) >= 0 ? (t - f) / T : -1;
+          int64_t lo = (t - w) > 0 ? (t - w + T - 1) / T : 0;
+          hi = std::min<int64_t>(hi, n - 1);
+          if (hi >= lo) live += hi - lo + 1;
+        }
+        peak = std::max(peak, live);
+      }
+  return peak;
+}
+
 // 1F1B at chunk granularity: a stage (two consecutive chunks) runs F of both chunks in two cells
 // and its fused backward in four (B, W of the upper chunk, then of the lower one).  Adjacent
 // stages' forwards are 2 cells apart, their backwards 4 (Table 1's delta0, delta1 for 1F1B).
@@ -404,6 +464,72 @@ int reorder(const Schedule& in, Schedule& out) {
   return PMC_OK;
 }
 
+// Adaptive scheduler (Appendix A): every two-part block within the offset range, in a fixed
+// order; blocks that collide or whose peak exceeds the limit are dropped; the rest are repeated,
+// squeezed, optionally reordered and timed with the given pass times; the first block with the
+// least finish time wins.
+int search(int d, int n, int64_t limit_units, double tf, double tb, double tw, int max_delta, bool do_reorder,
+           pmc_search_result* res, Schedule& best) {
+  if (d < 1 || n < 1) return fail(PMC_ERR_INVALID, "need d >= 1 and n >= 1 (got d=%d n=%d)", d, n);
+  if ((int64_t)d * n > (1 << 20)) return fail(PMC_ERR_INVALID, "d*n too large for a search");
+  if (max_delta < 1 || max_delta > 4 * T) return fail(PMC_ERR_INVALID, "max_delta %d out of range", max_delta);
+  if (tf < 0 || tb < 0 || tw < 0) return fail(PMC_ERR_INVALID, "negative duration");
+  bool found = false;
+  double best_span = 0.0;
+  int64_t candidates = 0, feasible = 0;
+  Schedule cand, reordered;
+  for (int K = d > 1 ? 2 : 1; K <= d; ++K)
+    for (int d0_lo = 1; d0_lo <= max_delta; ++d0_lo)
+      for (int d1_lo = 1; d1_lo <= max_delta; ++d1_lo)
+        for (int d0_hi = (K < d ? 1 : d0_lo); d0_hi <= (K < d ? max_delta : d0_lo); ++d0_hi)
+          for (int d1_hi = (K < d ? 1 : d1_lo); d1_hi <= (K < d ? max_delta : d1_lo); ++d1_hi)
+            for (int a = 1; a <= T; ++a)
+              for (int b = 1; b <= T; ++b)
+                for (int c = 1; c <= T; ++c) {
+                  ++candidates;
+                  if (!vshape_block_split(d, K, d0_lo, d1_lo, d0_hi, d1_hi, a, b, c, cand.block)) continue;
+                  const int64_t peak = block_peak_units(cand.block, d, n);
+                  if (peak > limit_units) continue;
+                  ++feasible;
+                  cand.kind = -1;
+                  cand.d = d;
+                  cand.n = n;
+                  cand.grouped_bw = false;
+                  if (int rc = finish(cand)) return rc;
+                  const Schedule* timed = &cand;
+                  if (do_reorder) {
+                    if (int rc = reorder(cand, reordered)) return rc;
+                    timed = &reordered;
+                  }
+                  double span = 0.0;
+                  if (int rc = makespan(*timed, tf, tb, tw, &span)) return rc;
+                  if (!found || span < best_span) {
+                    found = true;
+                    best_span = span;
+                    best = *timed;
+                    if (res) {
+                      res->split = K;
+                      res->delta0_lo = d0_lo;
+                      res->delta1_lo = d1_lo;
+                      res->delta0_hi = d0_hi;
+                      res->delta1_hi = d1_hi;
+                      res->turn_f = a;
+                      res->turn_fb = b;
+                      res->turn_b = c;
+                      res->peak_units = peak;
+                      res->makespan = span;
+                    }
+                  }
+                }
+  if (res) {
+    res->candidates = candidates;
+    res->feasible = feasible;
+  }
+  if (!found) return fail(PMC_ERR_ILLEGAL_BLOCK, "no V-shape block with offsets up to %d fits %lld live units on d=%d", max_delta,
+                          (long long)limit_units, d);
+  return PMC_OK;
+}
+
 }  // namespace pmc
 
 using pmc::fail;
@@ -447,6 +573,20 @@ int pmc_schedule_reorder(const pmc_schedule* s, pmc_schedule** out) {
     return rc;
   }
   *out = r;
+  return PMC_OK;
+}
+
+int pmc_schedule_search(int32_t d, int32_t n, int64_t limit_units, double t_f, double t_b, double t_w, int32_t max_delta,
+                        int32_t reorder, pmc_search_result* result, pmc_schedule** out) {
+  if (!out) return fail(PMC_ERR_INVALID, "out is NULL");
+  auto* s = new (std::nothrow) pmc_schedule;
+  if (!s) return fail(PMC_ERR_NOMEM, "host allocation failed");
+  int rc = pmc::search(d, n, limit_units, t_f, t_b, t_w, max_delta, reorder != 0, result, s->s);
+  if (rc != PMC_OK) {
+    delete s;
+    return rc;
+  }
+  *out = s;
   return PMC_OK;
 }
 

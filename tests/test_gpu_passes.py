@@ -131,14 +131,16 @@ def _oracle_model(cfg, chunk_params, xs, dys):
     return ys, dxs, grads
 
 
-def _replay(cfg, tag, kind, d, n, chunk_params, xs, dys, reorder=False):
-    sched = P.pmc_schedule_build(kind, d, n)
-    if reorder:
-        plain = sched
-        sched = P.pmc_schedule_reorder(plain)
-        P.pmc_schedule_destroy(plain)
+def _replay(cfg, tag, kind, d, n, chunk_params, xs, dys, reorder=False, sched=None, slabs=None):
+    if sched is None:
+        sched = P.pmc_schedule_build(kind, d, n)
+        if reorder:
+            plain = sched
+            sched = P.pmc_schedule_reorder(plain)
+            P.pmc_schedule_destroy(plain)
     pcfg = R.cfg_from_synth(cfg)
-    ctx = R.Context(pcfg, slabs=sum(OS.peak_units(kind, d, n)), workspace_bytes=P.pmc_replay_workspace_bytes(sched, pcfg))
+    ctx = R.Context(pcfg, slabs=slabs if slabs is not None else sum(OS.peak_units(kind, d, n)),
+                    workspace_bytes=P.pmc_replay_workspace_bytes(sched, pcfg))
     chunks = [ctx.add_chunk(p, cfg.dtype) for p in chunk_params]
     xd = [dev(x, cfg.dtype) for x in xs]
     dyd = [dev(g, cfg.dtype) for g in dys]
@@ -236,4 +238,25 @@ def test_replay_reordered_schedules():
         for c in range(2 * d):
             for k in OL.PARAM_NAMES:
                 assert np.array_equal(grads[c][0][k], first[c][0][k]), (kind, c, k)
+
+
+def test_replay_adaptive_schedule():
+    """A schedule found by the adaptive search under a limit of 5 live units per device (between
+    V-Min's 4 and V-Half's 6 at d = 4), replayed with exactly that many slabs per device: the pool's
+    measured peaks stay within the limit and the gradients are the plain V-ZB replay's, bit for bit."""
+    cfg = synth.ChunkCfg(layers=1, hidden=128, heads=2, ffn=512, seq=64, dtype="bf16")
+    d, n, limit = 4, 16, 5
+    chunk_params = [synth.chunk_params(cfg, "C5o", c) for c in range(2 * d)]
+    xs = [synth.chunk_input(cfg, "C5o", j) for j in range(n)]
+    dys = [synth.upstream_grad(cfg, "C5o", j) for j in range(n)]
+    _, _, first, _, _ = _replay(cfg, "C5o", "vzb", d, n, chunk_params, xs, dys)
+    sched, res = P.pmc_schedule_search(d, n, limit, 1.0, 1.2, 0.8)
+    print("adaptive block", res, flush=True)
+    assert res["peak_units"] <= limit
+    ys, dxs, grads, report, peaks = _replay(cfg, "C5o", None, d, n, chunk_params, xs, dys, sched=sched, slabs=limit * d)
+    assert max(p[0] for p in peaks) == res["peak_units"]
+    assert report["passes"] == 6 * d * n
+    for c in range(2 * d):
+        for k in OL.PARAM_NAMES:
+            assert np.array_equal(grads[c][0][k], first[c][0][k]), (c, k)
 

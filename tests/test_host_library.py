@@ -146,3 +146,52 @@ def test_reorder_rejects_null():
         P.pmc_schedule_reorder(None)
     assert e.value.code == P.PMC_ERR_INVALID
 
+
+@pytest.mark.parametrize("d,n", [(2, 6), (3, 7)])
+@pytest.mark.parametrize("times", [(1.0, 1.0, 1.0), (1.0, 1.3, 0.6)])
+@pytest.mark.parametrize("reorder", [True, False])
+def test_adaptive_search_matches_oracle(d, n, times, reorder):
+    """Appendix A's search: winning block, finish time and pass orders against the oracle's
+    exhaustive loop for every memory limit (offsets up to 3 so the oracle finishes in seconds)."""
+    for limit in range(3, 2 * d + 1):
+        ref = S.adaptive_search(d, n, limit, *times, max_delta=3, reorder=reorder)
+        if ref is None:
+            with pytest.raises(P.PmcError) as e:
+                P.pmc_schedule_search(d, n, limit, *times, max_delta=3, reorder=reorder)
+            assert e.value.code == P.PMC_ERR_ILLEGAL_BLOCK
+            continue
+        sch, res = P.pmc_schedule_search(d, n, limit, *times, max_delta=3, reorder=reorder)
+        try:
+            got = tuple(res[k] for k in ("split", "delta0_lo", "delta1_lo", "delta0_hi", "delta1_hi", "turn_f", "turn_fb", "turn_b"))
+            assert got == ref[1]
+            assert res["makespan"] == pytest.approx(ref[0], rel=1e-12)
+            assert res["peak_units"] == max(S.peak_units_of(ref[2], "vshape", d)) <= limit
+            for i, order in enumerate(S.device_orders(ref[2], d)):
+                assert [(p.op, p.chunk, p.mb) for p in P.pmc_schedule_device_order(sch, i)] == [(p.op, p.chunk, p.mb) for p in order]
+            assert [a[0] for a in P.pmc_schedule_account(sch, 1000, 40)] == S.peak_units_of(ref[2], "vshape", d)
+        finally:
+            P.pmc_schedule_destroy(sch)
+
+
+def test_adaptive_search_larger_and_bad_arguments():
+    """d = 4, n = 16 (the replay configuration): monotone in the limit, the uniform named schedules
+    never beat it at their own peaks, 6n + d - 1 with room for 2d units."""
+    spans = {}
+    for limit in (4, 5, 6, 7, 8):
+        sch, res = P.pmc_schedule_search(4, 16, limit)
+        spans[limit] = res["makespan"]
+        assert res["peak_units"] <= limit and res["feasible"] >= 1
+        assert P.pmc_schedule_num_passes(sch) == 6 * 4 * 16
+        P.pmc_schedule_destroy(sch)
+    assert all(spans[a] >= spans[b] for a, b in zip((4, 5, 6, 7), (5, 6, 7, 8)))
+    assert spans[8] == 6 * 16 + 3
+    for kind, limit in (("vmin", 4), ("vhalf", 6), ("vzb", 8)):
+        assert spans[limit] <= S.makespan_of(S.reordered(kind, 4, 16), kind, 4)
+    for bad in ((0, 4, 4), (4, 0, 4)):
+        with pytest.raises(P.PmcError):
+            P.pmc_schedule_search(*bad)
+    with pytest.raises(P.PmcError):
+        P.pmc_schedule_search(4, 8, 8, max_delta=0)
+    with pytest.raises(P.PmcError):
+        P.pmc_schedule_search(4, 8, 8, t_f=-1.0)
+

@@ -286,3 +286,56 @@ def test_reordering_keeps_weight_gradient_order_per_chunk():
                     mbs = [p.mb for p in order if p.op == "W" and p.chunk == chunk]
                     assert mbs == sorted(mbs)
 
+
+# --------------------------------------------------------------------------- adaptive search (Appendix A)
+
+def test_split_block_reduces_to_uniform_block():
+    """K = d (or equal offsets in both parts) is Section 3.1's uniform block."""
+    for d in (2, 3, 5, 8):
+        for kind in ("vmin", "vhalf", "vzb"):
+            d0, d1, a, b, c = S.vshape_params(kind, d)
+            assert S.vshape_block_split(d, d, d0, d1, d0, d1, a, b, c) == S.vshape_block(d, d0, d1, a, b, c)
+            assert S.vshape_block_split(d, 2, d0, d1, d0, d1, a, b, c) == S.vshape_block(d, d0, d1, a, b, c)
+
+
+def test_split_block_offsets_follow_appendix_a():
+    """Appendix A's constraint written out on a d = 5, K = 3 block (devices 1..5 there): forward and
+    backward offsets between neighbours, first part / second part."""
+    blk = S.vshape_block_split(5, 3, 1, 1, 2, 2, 1, 1, 1)
+    assert blk is not None
+    f0, f1, b1, b0 = blk[("F", 0)], blk[("F", 1)], blk[("B", 1)], blk[("B", 0)]
+    assert [f0[i + 1] - f0[i] for i in range(4)] == [1, 1, 2, 2]          # delta F_i^0, i = 1..4: i < K twice
+    assert [b1[i + 1] - b1[i] for i in range(4)] == [1, 1, 2, 2]          # delta B_i^1 = delta F_i^0
+    assert [f1[i - 1] - f1[i] for i in range(1, 5)] == [1, 1, 2, 2]       # delta F_i^1, i = 2..5: i <= K twice
+    assert [b0[i - 1] - b0[i] for i in range(1, 5)] == [1, 1, 2, 2]       # delta B_i^0 = delta F_i^1
+    assert (f1[4] - f0[4], b1[0] - f1[0], b0[4] - b1[4]) == (1, 1, 1)     # the three same-device offsets
+    for i in range(5):
+        assert len({blk[k][i] % S.T for k in blk}) == 6                     # one pass per residue: repeats without collision
+
+
+@pytest.mark.parametrize("d,n", [(2, 6), (3, 9)])
+def test_adaptive_search_properties(d, n):
+    """More memory never costs time; the result respects the limit and is a valid schedule; with
+    room for 2d units and unit times the search reaches V-ZB's least possible finish 6n + d - 1; at
+    the peak of a named schedule it is at least as good as that schedule; below the least peak any
+    V-shape block can have, nothing fits."""
+    spans = []
+    for limit in range(2, 2 * d + 2):
+        r = S.adaptive_search(d, n, limit, max_delta=4)
+        if r is None:
+            assert not spans                       # infeasible limits come first
+            continue
+        span, params, passes = r
+        assert max(S.peak_units_of(passes, "vshape", d)) <= limit
+        assert sorted((p.device, p.op, p.chunk, p.mb) for p in passes) == sorted(
+            (p.device, p.op, p.chunk, p.mb) for p in S.build("vzb", d, n))
+        assert span == S.makespan_of(passes, "vshape", d)
+        for kind in ("vmin", "vhalf", "vzb"):
+            if max(S.peak_units(kind, d, n)) <= limit:
+                assert span <= S.makespan_of(S.reordered(kind, d, n), kind, d)
+        if spans:
+            assert span <= spans[-1]
+        spans.append(span)
+    assert spans and spans[-1] == 6 * n + d - 1
+    assert S.adaptive_search(d, n, 1, max_delta=4) is None
+

@@ -23,13 +23,13 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix-core peak
 
 
-def flops_per_layer(h: int, ffn: int, s: int):
+def flops_per_layer(h: int, ffn: int, s: int, b: int = 1):
     """Algorithmic FLOP of one layer per pass.  GEMMs: 2*s*h*(3h + h + 2 ffn) in each of F, B, W.
     Attention (causal): F 2*s^2*h; B twice that (the model-FLOPs convention the paper inherits for
     its MFU, Appendix D.1); the two backward kernels execute 3.5x (scores and dP are recomputed in both)."""
-    gemm = 2 * s * h * (4 * h + 2 * ffn)
-    return {"F": gemm + 2 * s * s * h, "B": gemm + 4 * s * s * h, "W": gemm,
-            "B_executed": gemm + 7 * s * s * h, "gemm": gemm}
+    gemm = 2 * s * b * h * (4 * h + 2 * ffn)
+    att = b * s * s * h          # one causal score-sized product over all heads of b sequences
+    return {"F": gemm + 2 * att, "B": gemm + 4 * att, "W": gemm, "B_executed": gemm + 7 * att, "gemm": gemm}
 
 
 def main() -> int:
@@ -38,6 +38,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="C2", help="workload shape (C2 is the metric's; C3/C4 for study)")
+    ap.add_argument("--microbatch", type=int, default=0,
+                    help="override the workload's microbatch size (sequences per pass): the arithmetic-intensity "
+                         "sweep of Appendix D.2; 0 keeps the workload's own (1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--replay", action="store_true", help="also replay the d=4, n=16 schedules at the C5 shape")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
@@ -61,8 +64,12 @@ def main() -> int:
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.config]
     name = args.config
+    if args.microbatch > 0 and args.microbatch != cfg.microbatch:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, microbatch=args.microbatch)
+        name = f"{args.config}x{args.microbatch}"
     L, h, f, s = cfg.layers, cfg.hidden, cfg.ffn, cfg.seq
-    fl = flops_per_layer(h, f, s)
+    fl = flops_per_layer(h, f, s, cfg.microbatch)
 
     params = synth.chunk_params(cfg, name)
     x_h, dy_h = synth.chunk_input(cfg, name), synth.upstream_grad(cfg, name)

@@ -12,6 +12,7 @@
 // so the slab never grows.  Tensors that exist only inside B (dC, dO, dA, the dQ staging buffer,
 // partial sums) live in the workspace.
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 #include <set>
 
@@ -82,6 +83,14 @@ struct pmc_ctx {
   char* ws = nullptr;
   size_t ws_bytes = 0;
   int chunks_alive = 0;
+  // second stream for the W pass of small chunks (created on first use, default priority)
+  hipStream_t side = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
+  ~pmc_ctx() {
+    if (fork) (void)hipEventDestroy(fork);
+    if (join) (void)hipEventDestroy(join);
+    if (side) (void)hipStreamDestroy(side);
+  }
 };
 
 namespace pmc {
@@ -342,15 +351,51 @@ int chunk_backward_input(pmc_chunk* ch, int32_t mb, const void* dy, void* dx) {
   return PMC_OK;
 }
 
+// The weight-gradient products of a pass do not depend on each other.  When they are small (each
+// fills the compute units for two rounds of tiles at most) half of them go to a second stream:
+// workgroups of two different products then share the chip, one product's read-modify-write of dW
+// overlaps the other's matrix work, and the tail of one fills with the head of the next (measured
+// -15 % on the W products of a hidden-2048, 1024-token chunk; larger products gain nothing or
+// lose, so they stay on one stream).  Off while tracing, whose per-operation events assume one stream.
+bool w_pass_two_streams(const pmc_chunk* ch) {
+  if (ch->ctx->tracing || ch->cfg.dtype != PMC_BF16) return false;
+  if (const char* f = std::getenv("PMC_W_STREAMS")) return f[0] == '2';
+  const long tiles = (long)((ch->cfg.hidden + 255) / 256) * ((ch->cfg.ffn + 255) / 256);
+  return tiles <= 512;
+}
+
+int side_stream(pmc_ctx* ctx) {
+  if (ctx->side) return PMC_OK;
+  if (hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) != hipSuccess ||
+      hipEventCreateWithFlags(&ctx->fork, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&ctx->join, hipEventDisableTiming) != hipSuccess)
+    return fail(PMC_ERR_HIP, "cannot create the second stream of the W pass");
+  return PMC_OK;
+}
+
 int chunk_backward_weight_one(pmc_chunk* ch, int32_t mb, bool release) {
   auto it = ch->live.find(mb);
   if (it == ch->live.end() || it->second.state != kBackwardDone)
     return fail(PMC_ERR_STATE, "stage_backward_weight: microbatch %d has not had its backward-input pass", mb);
   Micro& m = it->second;
   const pmc_chunk_cfg& c = ch->cfg;
-  hipStream_t st = ch->ctx->stream;
+  pmc_ctx* ctx = ch->ctx;
+  hipStream_t st = ctx->stream;
   const int T = ch->tokens, h = c.hidden, f = c.ffn, L = c.layers;
   char* s = m.slab;
+  const bool two = w_pass_two_streams(ch);
+  if (two) {
+    PMC_TRY(side_stream(ctx));
+    if (hipEventRecord(ctx->fork, st) != hipSuccess || hipStreamWaitEvent(ctx->side, ctx->fork, 0) != hipSuccess)
+      return fail(PMC_ERR_HIP, "stage_backward_weight: cannot fork the second stream");
+  }
+  // a product on the second stream: no split-K scratch (the first stream's products own it)
+  auto side_gemm = [&](k::GemmArgs g) {
+    if (!two) return t_gemm(ctx, PMC_W, g, ch->wsl);
+    g.ws = nullptr;
+    g.ws_bytes = 0;
+    return k::gemm(ctx->side, g);
+  };
   for (int l = L - 1; l >= 0; --l) {
     const LayerOffsets& o = ch->off[l];
     const void* dxout = s + (l == L - 1 ? ch->off[0].x : ch->off[l + 1].x);
@@ -365,12 +410,16 @@ int chunk_backward_weight_one(pmc_chunk* ch, int32_t mb, bool release) {
       jobs.out[j] = G(ch, l, which[j]);
       jobs.n[j] = jobs.lda[j] = width[j];
     }
-    PMC_TRY(traced(ch->ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sums(st, c.dtype, T, jobs); }));
-    PMC_TRY(t_gemm(ch->ctx, PMC_W, gemm_args(ch, true, false, f, h, T, s + o.g, f, dxout, h, G(ch, l, W_2), h, PMC_EPI_ACCUM_F32), ch->wsl));
-    PMC_TRY(t_gemm(ch->ctx, PMC_W, gemm_args(ch, true, false, h, f, T, s + o.c, h, s + o.u, f, G(ch, l, W_1), f, PMC_EPI_ACCUM_F32), ch->wsl));
-    PMC_TRY(t_gemm(ch->ctx, PMC_W, gemm_args(ch, true, false, h, h, T, s + o.o, h, s + o.xmid, h, G(ch, l, W_O), h, PMC_EPI_ACCUM_F32), ch->wsl));
-    PMC_TRY(t_gemm(ch->ctx, PMC_W, gemm_args(ch, true, false, h, 3 * h, T, s + o.a, h, s + o.qkv, 3 * h, G(ch, l, W_QKV), 3 * h,
-                                  PMC_EPI_ACCUM_F32), ch->wsl));
+    PMC_TRY(traced(ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sums(st, c.dtype, T, jobs); }));
+    PMC_TRY(t_gemm(ctx, PMC_W, gemm_args(ch, true, false, f, h, T, s + o.g, f, dxout, h, G(ch, l, W_2), h, PMC_EPI_ACCUM_F32), ch->wsl));
+    PMC_TRY(side_gemm(gemm_args(ch, true, false, h, f, T, s + o.c, h, s + o.u, f, G(ch, l, W_1), f, PMC_EPI_ACCUM_F32)));
+    PMC_TRY(t_gemm(ctx, PMC_W, gemm_args(ch, true, false, h, h, T, s + o.o, h, s + o.xmid, h, G(ch, l, W_O), h, PMC_EPI_ACCUM_F32), ch->wsl));
+    PMC_TRY(side_gemm(gemm_args(ch, true, false, h, 3 * h, T, s + o.a, h, s + o.qkv, 3 * h, G(ch, l, W_QKV), 3 * h,
+                                PMC_EPI_ACCUM_F32)));
+  }
+  if (two) {
+    if (hipEventRecord(ctx->join, ctx->side) != hipSuccess || hipStreamWaitEvent(st, ctx->join, 0) != hipSuccess)
+      return fail(PMC_ERR_HIP, "stage_backward_weight: cannot join the second stream");
   }
   if (release) {
     ch->ctx->pool.give(m.slab, m.device, (int64_t)(ch->unit_bytes - ch->stats_bytes));

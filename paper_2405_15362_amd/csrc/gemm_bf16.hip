@@ -342,6 +342,7 @@ template <int ROWS, bool KMAJ, int NW>
 struct DmaLoader {
   static constexpr int NL = ROWS * 64 * 2 / 1024 / NW;  // 1 KB loads per wave per tile
   static_assert(ROWS * 64 * 2 / 1024 % NW == 0, "tile must split evenly over the waves");
+  static_assert(KMAJ || ROWS >= 128, "the [64 k][rows] swizzle moves chunks by up to 12 positions: needs 16 per row");
   uint32_t voff[NL];  // byte offset of this lane's chunk at K offset 0
 
   // Wave w issues loads w*NL .. w*NL+NL-1; load q fills tile bytes [1024 q, 1024 q + 1024).
@@ -627,16 +628,17 @@ int launch_dma(hipStream_t st, GemmParams p) {
 // (tiles per unit, rounded up) x (work of a tile) / (throughput of that shape on a busy unit); the
 // largest tile wins once there are enough tiles, smaller ones when units would otherwise idle.
 //   0: 256x256, 8 waves, 2 stages    1: 256x128, 8 waves, 3 stages    2: 128x128, 4 waves, 2 stages
-// PMC_GEMM_TILE=0|1|2 in the environment forces a shape (for tests and tuning).
+//   3: 64x128, 4 waves, 3 stages (skinny outputs: twice the tiles of shape 2)
+// PMC_GEMM_TILE=0|1|2|3 in the environment forces a shape (for tests and tuning).
 int pick_tile(int M, int N) {
   if (const char* f = std::getenv("PMC_GEMM_TILE")) {
-    if (f[0] >= '0' && f[0] <= '2' && f[1] == 0) return f[0] - '0';
+    if (f[0] >= '0' && f[0] <= '3' && f[1] == 0) return f[0] - '0';
   }
-  const int bm[3] = {256, 256, 128}, bn[3] = {256, 128, 128};
-  const double rate[3] = {1.0, 0.95, 0.75};
+  const int bm[4] = {256, 256, 128, 64}, bn[4] = {256, 128, 128, 128};
+  const double rate[4] = {1.0, 0.95, 0.75, 0.6};
   int best = 0;
   double best_t = 1e300;
-  for (int c = 0; c < 3; ++c) {
+  for (int c = 0; c < 4; ++c) {
     const long n = (long)((M + bm[c] - 1) / bm[c]) * ((N + bn[c] - 1) / bn[c]);
     const double t = (double)((n + 255) / 256) * bm[c] * bn[c] / rate[c];
     if (t < best_t) {
@@ -652,6 +654,9 @@ int launch_dma_tile(hipStream_t st, const GemmParams& p) {
   switch (pick_tile(p.M, p.N)) {
     case 0: return launch_dma<256, 256, 2, 4, A_KMAJ, B_KMAJ, 2, EPI>(st, p);
     case 1: return launch_dma<256, 128, 4, 2, A_KMAJ, B_KMAJ, 3, EPI>(st, p);
+    case 3:  // the [64 k][rows] swizzle needs 128 rows: a 64-row A tile only when A is contraction-contiguous
+      if constexpr (A_KMAJ) return launch_dma<64, 128, 1, 4, A_KMAJ, B_KMAJ, 3, EPI>(st, p);
+      else return launch_dma<128, 128, 2, 2, A_KMAJ, B_KMAJ, 2, EPI>(st, p);
     default: return launch_dma<128, 128, 2, 2, A_KMAJ, B_KMAJ, 2, EPI>(st, p);
   }
 }
@@ -664,6 +669,9 @@ int pick_splits(int M, int N, int K, size_t ws_bytes) {
   if (std::getenv("PMC_GEMM_TILE")) return 1;
   const long tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
   if (tiles >= 192) return 1;
+  // up to K = 6144 the 64x128 tiles (no partials, no second kernel) are faster once there are
+  // enough of them (measured at M = 1024, N = 2048: 15 / 38 us against 27 / 41 us at K = 2048 / 6144)
+  if (K < 8192 && (long)((M + 63) / 64) * ((N + 127) / 128) >= 192) return 1;
   const int nkt = K / 64;
   int best = 1;
   for (int s : {2, 4, 8}) {

@@ -239,6 +239,36 @@ def test_attention_launch_shapes(ctx, monkeypatch, family, dh, causal):
         assert rel_l2(host(dq)[:, cols], dqkv_ref[:, cols]) <= tol("bf16"), name
 
 
+@pytest.mark.parametrize("family", ["0", "1"])
+def test_attention_long_sequence(ctx, monkeypatch, family):
+    """Sequence length 4096 at head size 128 (the longest workload shape), four heads so that the
+    oracle's probabilities fit in host memory: 32 to 64 streamed blocks per query block, the
+    heaviest-first block order, both families of launch shapes."""
+    monkeypatch.setenv("PMC_ATTN_SHAPE", family)
+    batch, seq, heads, dh = 1, 4096, 4, 128
+    h = heads * dh
+    key = ("attn-long",)
+    print("attention long case", family, flush=True)
+    qkv = mat(key + ("qkv",), (seq, 3 * h), "bf16")
+    d_o = mat(key + ("do",), (seq, h), "bf16")
+    q64 = qkv.astype(np.float64)
+    o_ref, probs, lse_ref = OL.attention(q64, heads, True, batch)
+    dqkv_ref = OL.attention_input_grad(d_o.astype(np.float64), q64, probs, heads, batch)
+    del probs
+    qd = dev(qkv, "bf16")
+    o = dev(np.zeros((seq, h)), "bf16")
+    lse = torch.zeros(heads * seq, device="cuda")
+    P.pmc_attention_forward(ctx, qd, o, lse, batch, seq, heads, dh, True)
+    torch.cuda.synchronize()
+    assert rel_l2(host(o), o_ref) <= tol("bf16")
+    assert np.abs(host(lse) - lse_ref.reshape(-1)).max() <= 2e-2
+    dq = dev(np.zeros_like(qkv), "bf16")
+    P.pmc_attention_backward(ctx, qd, o, lse, dev(d_o, "bf16"), dq, batch, seq, heads, dh, True)
+    torch.cuda.synchronize()
+    for name, cols in (("dq", slice(0, h)), ("dk", slice(h, 2 * h)), ("dv", slice(2 * h, 3 * h))):
+        assert rel_l2(host(dq)[:, cols], dqkv_ref[:, cols]) <= tol("bf16"), name
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_column_sum(ctx, dtype):
     for rows, n in ((1, 8), (50, 264), (1000, 2048), (300, 6144)):

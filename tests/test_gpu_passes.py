@@ -19,6 +19,13 @@ CASES = {
     "noncausal_f32": synth.ChunkCfg(layers=1, hidden=96, heads=3, ffn=256, seq=52, dtype="f32", causal=False),
     "dh128_bf16": synth.ChunkCfg(layers=2, hidden=256, heads=2, ffn=1024, seq=192, dtype="bf16"),
     "dh64_ragged_bf16": synth.ChunkCfg(layers=3, hidden=192, heads=3, ffn=328, seq=104, microbatch=2, dtype="bf16"),
+    # the workload bench.py times, at full size and in the launch configuration it runs in (large GEMM
+    # tiles, 64x128 tiles, split K, short-sequence attention shapes, W pass on two streams): every
+    # output and gradient element against the oracle (a few seconds of fp64 numpy)
+    "c2_full_bf16": synth.CONFIGS["C2"],
+    # one layer of the hidden-4096, 2048-token shape: the many-block attention shapes and GEMMs that are
+    # neither split nor skinny
+    "c3_one_layer_bf16": synth.ChunkCfg(layers=1, hidden=4096, heads=32, ffn=16384, seq=2048, dtype="bf16"),
 }
 
 

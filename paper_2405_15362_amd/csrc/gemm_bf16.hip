@@ -206,10 +206,32 @@ __device__ __forceinline__ u32x4 pack8(const float* f) {
   return v;
 }
 
+// What an epilogue reads besides the bias for eight consecutive output columns: the old fp32 sums
+// (ACCUM), the residual (BIAS_RESID) or the GeLU input (DGELU).  Fetched ahead of use, a whole
+// 32-row slab at a time, so that many loads are in flight per wave.
+template <int EPI>
+struct OctOperand {
+  f32x4 lo, hi;  // ACCUM
+  u32x4 packed;  // BIAS_RESID, DGELU
+  static constexpr bool used = EPI == PMC_EPI_ACCUM_F32 || EPI == PMC_EPI_BIAS_RESID || EPI == PMC_EPI_DGELU;
+  __device__ __forceinline__ void load(const GemmParams& p, int m, int n) {
+    const size_t idx = (size_t)m * p.ldc + n;
+    if (EPI == PMC_EPI_ACCUM_F32) {
+      const float* c = reinterpret_cast<const float*>(p.C) + idx;
+      lo = *reinterpret_cast<const f32x4*>(c);
+      hi = *reinterpret_cast<const f32x4*>(c + 4);
+    } else if (EPI == PMC_EPI_BIAS_RESID) {
+      packed = *reinterpret_cast<const u32x4*>(p.resid + idx);
+    } else if (EPI == PMC_EPI_DGELU) {
+      packed = *reinterpret_cast<const u32x4*>(p.aux + idx);
+    }
+  }
+};
+
 // Applies epilogue EPI to eight consecutive output columns n .. n+7 of row m and stores them
 // (16 bytes per lane for bf16 results, 32 for fp32 ones).  Same arithmetic as store_quad.
 template <int EPI>
-__device__ __forceinline__ void store_oct(const GemmParams& p, float (&v)[8], int m, int n) {
+__device__ __forceinline__ void store_oct(const GemmParams& p, float (&v)[8], int m, int n, const OctOperand<EPI>& x) {
   const size_t idx = (size_t)m * p.ldc + n;
   if (EPI == kEpiPartial || EPI == PMC_EPI_ACCUM_F32) {
     float* c = EPI == kEpiPartial
@@ -217,9 +239,8 @@ __device__ __forceinline__ void store_oct(const GemmParams& p, float (&v)[8], in
                    : reinterpret_cast<float*>(p.C) + idx;
     f32x4 lo = {v[0], v[1], v[2], v[3]}, hi = {v[4], v[5], v[6], v[7]};
     if (EPI == PMC_EPI_ACCUM_F32) {
-      const f32x4 old_lo = *reinterpret_cast<const f32x4*>(c), old_hi = *reinterpret_cast<const f32x4*>(c + 4);
-      lo = old_lo + lo;
-      hi = old_hi + hi;
+      lo = x.lo + lo;
+      hi = x.hi + hi;
     }
     *reinterpret_cast<f32x4*>(c) = lo;
     *reinterpret_cast<f32x4*>(c + 4) = hi;
@@ -233,13 +254,13 @@ __device__ __forceinline__ void store_oct(const GemmParams& p, float (&v)[8], in
   }
   if (EPI == PMC_EPI_BIAS_RESID) {
     float r[8];
-    unpack8(*reinterpret_cast<const u32x4*>(p.resid + idx), r);
+    unpack8(x.packed, r);
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] += r[e];
   }
   if (EPI == PMC_EPI_DGELU) {
     float u[8];
-    unpack8(*reinterpret_cast<const u32x4*>(p.aux + idx), u);
+    unpack8(x.packed, u);
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_fast(u[e]);
   }
@@ -265,9 +286,23 @@ __device__ __forceinline__ void epilogue_staged(const GemmParams& p, f32x16 (&ac
   constexpr int WN = 32 * TN, PITCH = WN + 4;
   constexpr int LPR = WN / 8;     // lanes per row on the way out
   constexpr int RPP = 64 / LPR;   // rows per pass
+  constexpr int NPASS = 32 / RPP;
   const int orow = lane / LPR, ocol = 8 * (lane % LPR);
+  const int n = nw0 + ocol;
+  // operands of slab i + 1 are requested before slab i is staged and stored
+  OctOperand<EPI> ahead[2][NPASS];
+  auto fetch = [&](int i, OctOperand<EPI> (&dst)[NPASS]) {
+    if (!OctOperand<EPI>::used) return;
+#pragma unroll
+    for (int pass = 0; pass < NPASS; ++pass) {
+      const int m = mw0 + 32 * i + pass * RPP + orow;
+      if (m < p.M && n < p.N) dst[pass].load(p, m, n);
+    }
+  };
+  fetch(0, ahead[0]);
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
+    if (i + 1 < TM) fetch(i + 1, ahead[(i + 1) & 1]);
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -276,14 +311,14 @@ __device__ __forceinline__ void epilogue_staged(const GemmParams& p, f32x16 (&ac
         *reinterpret_cast<f32x4*>(slab + (lane & 31) * PITCH + 32 * j + 8 * q + 4 * (lane >> 5)) = t;
       }
 #pragma unroll
-    for (int pass = 0; pass < 32 / RPP; ++pass) {
+    for (int pass = 0; pass < NPASS; ++pass) {
       const int row = pass * RPP + orow;
       const f32x4 lo = *reinterpret_cast<const f32x4*>(slab + row * PITCH + ocol);
       const f32x4 hi = *reinterpret_cast<const f32x4*>(slab + row * PITCH + ocol + 4);
-      const int m = mw0 + 32 * i + row, n = nw0 + ocol;
+      const int m = mw0 + 32 * i + row;
       if (m < p.M && n < p.N) {
         float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-        store_oct<EPI>(p, v, m, n);
+        store_oct<EPI>(p, v, m, n, ahead[i & 1][pass]);
       }
     }
   }

@@ -217,9 +217,10 @@ struct OctOperand {
   __device__ __forceinline__ void load(const GemmParams& p, int m, int n) {
     const size_t idx = (size_t)m * p.ldc + n;
     if (EPI == PMC_EPI_ACCUM_F32) {
+      // streamed once: keep the fp32 sums out of the way of the operand panels in L2
       const float* c = reinterpret_cast<const float*>(p.C) + idx;
-      lo = *reinterpret_cast<const f32x4*>(c);
-      hi = *reinterpret_cast<const f32x4*>(c + 4);
+      lo = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(c));
+      hi = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(c + 4));
     } else if (EPI == PMC_EPI_BIAS_RESID) {
       packed = *reinterpret_cast<const u32x4*>(p.resid + idx);
     } else if (EPI == PMC_EPI_DGELU) {
@@ -241,6 +242,9 @@ __device__ __forceinline__ void store_oct(const GemmParams& p, float (&v)[8], in
     if (EPI == PMC_EPI_ACCUM_F32) {
       lo = x.lo + lo;
       hi = x.hi + hi;
+      __builtin_nontemporal_store(lo, reinterpret_cast<f32x4*>(c));
+      __builtin_nontemporal_store(hi, reinterpret_cast<f32x4*>(c + 4));
+      return;
     }
     *reinterpret_cast<f32x4*>(c) = lo;
     *reinterpret_cast<f32x4*>(c + 4) = hi;
@@ -344,9 +348,8 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmParams p, const 
 
 // Workgroup id -> (tile_m, tile_n).  Ids are dealt round-robin over 8 XCDs; give each XCD a
 // contiguous run of tile indices, then walk tiles in column groups 8 tiles of M tall.
-__device__ __forceinline__ void tile_of_block(const GemmParams& p, int& tile_m, int& tile_n) {
+__device__ __forceinline__ void tile_of_pid(const GemmParams& p, int pid, int& tile_m, int& tile_n) {
   const int ntiles = p.tiles_m * p.tiles_n;
-  int pid = blockIdx.x;
   const int xcd = pid & 7, local = pid >> 3, lo = ntiles >> 3, rem = ntiles & 7;
   pid = xcd * lo + (xcd < rem ? xcd : rem) + local;
   constexpr int GROUP = 8;
@@ -356,6 +359,9 @@ __device__ __forceinline__ void tile_of_block(const GemmParams& p, int& tile_m, 
   const int group_m = min(p.tiles_m - first_m, GROUP);
   tile_m = first_m + (pid % per_group) % group_m;
   tile_n = (pid % per_group) / group_m;
+}
+__device__ __forceinline__ void tile_of_block(const GemmParams& p, int& tile_m, int& tile_n) {
+  tile_of_pid(p, blockIdx.x, tile_m, tile_n);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -433,16 +439,16 @@ __device__ __forceinline__ bf16x8 read_frag_swz(const bf16_t* tile, int r0, int 
   }
 }
 
+// One output tile (tile_m, tile_n) over the K tiles kt0 .. kt0 + nk - 1: ring prologue, K loop,
+// staged epilogue.  All waves of the workgroup call it together; on return the LDS ring holds
+// epilogue slabs that other waves may still be reading (barrier before the ring is filled again).
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KMAJ, bool B_KMAJ, int NSTAGE, int EPI>
-__global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_bf16_dma_kernel(GemmParams p) {
+__device__ __forceinline__ void dma_tile(const GemmParams& p, bf16_t* smem, int tile_m, int tile_n, int kt0, int nk) {
 #if defined(__HIP_DEVICE_COMPILE__)
   constexpr int BK = 64, NW = WAVES_M * WAVES_N, WM = BM / WAVES_M, WN = BN / WAVES_N, TM = WM / 32, TN = WN / 32;
   constexpr int TA = BM * BK, TB = BN * BK, STAGE = TA + TB;
-  extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
-  int tile_m, tile_n;
-  tile_of_block(p, tile_m, tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
 
   auto make_rsrc = [](const void* ptr) {  // raw buffer descriptor: base, no stride, 2 GB window
@@ -466,8 +472,6 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_bf16_dma_kernel(G
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int nk = p.k_tiles_per_split;
-  const int kt0 = blockIdx.y * nk;  // first K tile of this split
   bf16x8 fa[2][TM], fb[2][TN];
   // One 16-wide K step: the MFMAs on fragment set c, interleaved in a fixed order with the LDS
   // reads that fill set c^1 from (src_a, src_b) at K offset ks.
@@ -529,6 +533,53 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_bf16_dma_kernel(G
   static_assert(NW * 32 * (WN + 4) * 4 <= NSTAGE * STAGE * 2, "epilogue slabs must fit in the stage ring");
   float* slab = reinterpret_cast<float*>(smem) + wave * (32 * (WN + 4));
   epilogue_staged<TM, TN, EPI>(p, acc, slab, m0 + wm0, n0 + wn0, lane);
+#endif
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KMAJ, bool B_KMAJ, int NSTAGE, int EPI>
+__global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_bf16_dma_kernel(GemmParams p) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
+  int tile_m, tile_n;
+  tile_of_block(p, tile_m, tile_n);
+  const int nk = p.k_tiles_per_split;
+  dma_tile<BM, BN, WAVES_M, WAVES_N, A_KMAJ, B_KMAJ, NSTAGE, EPI>(p, smem, tile_m, tile_n, (int)blockIdx.y * nk, nk);
+#endif
+}
+
+// Weight-gradient products (fp32 C += A^T B) with several rounds of tiles per compute unit: one
+// persistent workgroup per unit walks its tiles.  The read-modify-write of C runs at HBM speed and
+// the K loop at matrix-core speed, and a workgroup cannot do both at once; if all workgroups start
+// together they stay in step, every K loop finds the memory idle and every epilogue finds it
+// saturated.  So the workgroups are put out of phase, without idling anyone: group g of G (by
+// workgroup id) starts its first tile at K tile g/G of the way through, and comes back for that
+// tile's first K tiles after its last tile.  Both parts are added into C by the same workgroup, in
+// that order, so the result depends on the launch shape alone.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int GROUPS>
+__global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_bf16_wgrad_persistent_kernel(GemmParams p) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
+  const int ntiles = p.tiles_m * p.tiles_n, G = gridDim.x, b = blockIdx.x;
+  const int nk = p.k_tiles_per_split;  // all of K
+  const int group = (b >> 3) % GROUPS;  // neighbours on one XCD fall into different groups
+  const int head = (nk * group) / GROUPS;  // K tiles of the first tile left for the end
+  bool first = true;
+  int tm0 = 0, tn0 = 0;
+  for (int pid = b; pid < ntiles; pid += G) {
+    int tile_m, tile_n;
+    tile_of_pid(p, pid, tile_m, tile_n);
+    if (first) {
+      tm0 = tile_m;
+      tn0 = tile_n;
+      dma_tile<BM, BN, WAVES_M, WAVES_N, false, false, NSTAGE, PMC_EPI_ACCUM_F32>(p, smem, tile_m, tile_n, head, nk - head);
+      first = false;
+    } else {
+      dma_tile<BM, BN, WAVES_M, WAVES_N, false, false, NSTAGE, PMC_EPI_ACCUM_F32>(p, smem, tile_m, tile_n, 0, nk);
+    }
+    __syncthreads();
+  }
+  if (!first && head > 0)
+    dma_tile<BM, BN, WAVES_M, WAVES_N, false, false, NSTAGE, PMC_EPI_ACCUM_F32>(p, smem, tm0, tn0, 0, head);
 #endif
 }
 
@@ -696,6 +747,42 @@ int launch_dma_tile(hipStream_t st, const GemmParams& p) {
   }
 }
 
+// Persistent, phase-shifted weight-gradient kernel: when every compute unit gets at least two
+// 256x256 tiles.  PMC_GEMM_WGRAD=0|1 in the environment forces the choice (tests, tuning).
+bool use_wgrad_persistent(const GemmParams& p) {
+  if (p.K < 4 * 64) return false;
+  if (const char* f = std::getenv("PMC_GEMM_WGRAD")) return f[0] == '1';
+  if (std::getenv("PMC_GEMM_TILE")) return false;
+  return (long)((p.M + 255) / 256) * ((p.N + 255) / 256) >= 2 * 256;
+}
+
+int launch_wgrad_persistent(hipStream_t st, GemmParams p) {
+  constexpr int NSTAGE = 2, GROUPS = 4;
+  constexpr size_t lds = (size_t)NSTAGE * (256 + 256) * 64 * sizeof(bf16_t);
+  auto kern = gemm_bf16_wgrad_persistent_kernel<256, 256, 2, 4, NSTAGE, GROUPS>;
+  static bool configured = false;
+  static int units = 0;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return fail(PMC_ERR_HIP, "gemm_bf16: cannot reserve %zu bytes of LDS: %s", lds, hipGetErrorString(e));
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
+      return fail(PMC_ERR_HIP, "gemm_bf16: cannot query the device");
+    units = prop.multiProcessorCount;
+    configured = true;
+  }
+  p.tiles_m = (p.M + 255) / 256;
+  p.tiles_n = (p.N + 255) / 256;
+  const int ntiles = p.tiles_m * p.tiles_n;
+  int grid = ntiles < units ? ntiles : units;
+  if (grid >= 8) grid &= ~7;  // whole rounds over the 8 XCDs keep a workgroup's tiles on one XCD
+  kern<<<dim3(grid), dim3(512), lds, st>>>(p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(PMC_ERR_HIP, "gemm_bf16 weight-gradient launch failed: %s", hipGetErrorString(e));
+  return PMC_OK;
+}
+
 // Split K: when even 128x128 tiles leave most compute units idle (skinny products such as the
 // [tokens, hidden] outputs at short sequence length), K is cut into `splits` ranges, each range
 // writes an fp32 partial product to the workspace and a second kernel adds them and applies the
@@ -799,6 +886,7 @@ int gemm_bf16(hipStream_t st, const GemmArgs& a) {
       if (rc != PMC_OK) return rc;
       return launch_reduce(st, p, (const float*)a.ws, splits, a.epilogue);
     }
+    if (!a_kmaj && !b_kmaj && a.epilogue == PMC_EPI_ACCUM_F32 && use_wgrad_persistent(p)) return launch_wgrad_persistent(st, p);
     const int rc = launch_fast(st, p, a_kmaj, b_kmaj, a.epilogue);
     if (rc != kNoFastPath) return rc;
   }

@@ -115,6 +115,28 @@ def test_gemm_bf16_split_k(ctx, ta, tb, epis):
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
 
 
+def test_gemm_bf16_weight_gradient_persistent(ctx, monkeypatch):
+    """The persistent W-pass kernel (fp32 C += A^T B; one workgroup per compute unit walks its
+    256x256 tiles, its first tile cut in two along K to put the workgroups out of phase): fewer tiles
+    than workgroups, more tiles than workgroups with ragged edges, short and long K; and the same
+    result from run to run."""
+    monkeypatch.setenv("PMC_GEMM_WGRAD", "1")
+    for M, N, K in ((512, 256, 256), (264, 136, 1024), (4104, 4360, 256), (4096, 4608, 576), (3848, 4872, 1280)):
+        _gemm_case(ctx, "bf16", True, False, M, N, K, P.EPI_ACCUM_F32)
+    a = dev(mat(("wg", "a"), (1024, 4104), "bf16"), "bf16")
+    b = dev(mat(("wg", "b"), (1024, 4360), "bf16", 0.05), "bf16")
+    c0 = dev(mat(("wg", "c"), (4104, 4360), "f32"), "f32")
+    outs = []
+    for flag in ("1", "1", "0"):
+        monkeypatch.setenv("PMC_GEMM_WGRAD", flag)
+        c = c0.clone()
+        P.pmc_gemm(ctx, a, b, c, True, False, P.EPI_ACCUM_F32)
+        outs.append(c)
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0], outs[1])
+    assert rel_l2(host(outs[0]), host(outs[2])) <= 1e-6     # the plain kernel adds K in one piece
+
+
 @pytest.mark.parametrize("ta,tb", [(False, False), (False, True), (True, False)])
 def test_gemm_bf16_large_tiles(ctx, ta, tb):
     # enough 256x256 tiles to take the large-tile path, ragged edge tiles included

@@ -41,6 +41,9 @@ def main() -> int:
     ap.add_argument("--microbatch", type=int, default=0,
                     help="override the workload's microbatch size (sequences per pass): the arithmetic-intensity "
                          "sweep of Appendix D.2; 0 keeps the workload's own (1)")
+    ap.add_argument("--queued", type=int, default=4,
+                    help="also time W for this many queued microbatches in one call (deferred W, contracted "
+                         "together); 0 or 1 skips it")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--replay", action="store_true", help="also replay the d=4, n=16 schedules at the C5 shape")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
@@ -73,7 +76,7 @@ def main() -> int:
 
     params = synth.chunk_params(cfg, name)
     x_h, dy_h = synth.chunk_input(cfg, name), synth.upstream_grad(cfg, name)
-    ctx = R.Context(R.cfg_from_synth(cfg), slabs=1)
+    ctx = R.Context(R.cfg_from_synth(cfg), slabs=max(1, args.queued))
     ch = ctx.add_chunk(params, cfg.dtype)
     x, dy = R.to_device(x_h, cfg.dtype), R.to_device(dy_h, cfg.dtype)
     y, dx = torch.empty_like(x), torch.empty_like(x)
@@ -124,6 +127,17 @@ def main() -> int:
         passes[k] = {"ms": round(ms, 4), "tflops": round(L * fl[k] / (ms * 1e-3) / 1e12, 1),
                      "frac_of_bf16_peak": round(L * fl[k] / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
     passes["B"]["tflops_executed"] = round(L * fl["B_executed"] / (passes["B"]["ms"] * 1e-3) / 1e12, 1)
+    if args.queued > 1:
+        # deferred W: F and B of q microbatches (untimed), then ONE W call for all of them
+        q, qms = args.queued, []
+        for _ in range(5):
+            for j in range(q):
+                P.stage_forward(ch.handle, j, x, y)
+                P.stage_backward_input(ch.handle, j, dy, dx)
+            qms.append(timed(lambda: P.stage_backward_weight(ch.handle, list(range(q))), 1))
+        ms = float(np.median(qms)) / q
+        passes[f"W_queued{q}"] = {"ms_per_microbatch": round(ms, 4), "tflops": round(L * fl["W"] / (ms * 1e-3) / 1e12, 1),
+                                  "frac_of_bf16_peak": round(L * fl["W"] / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
 
     # dominant kernel: the bf16 GEMM.  Its launches are bracketed by HIP events inside traced steps.
     P.pmc_trace_begin(ctx.ctx, 4096)

@@ -146,8 +146,15 @@ int stage_forward_on(pmc_chunk* chunk, int32_t mb, const void* x, void* y, int32
 int stage_backward_input(pmc_chunk* chunk, int32_t mb, const void* dy, void* dx);
 
 /* W (Section 2.1): adds the weight and bias gradients of the `count` listed microbatches (each
- * must have had its B) into the bound fp32 accumulators, in list order, and returns their slabs
- * to the pool.  count > 1 is the deferred, queued case. */
+ * must have had its B) into the bound fp32 accumulators and returns their slabs to the pool.
+ * count > 1 is the deferred, queued case (Section 2.1: W "can be deferred").  In bf16 mode queued
+ * microbatches are contracted together, PMC_MAX_QUEUED_W at a time in list order: each weight
+ * gradient is ONE product dW += [X_1; X_2; ...]^T . [dY_1; dY_2; ...] over the concatenated token
+ * axis, so the fp32 accumulator is read and written once per group instead of once per
+ * microbatch.  The sum is the same up to fp32 summation order (the microbatches are added inside
+ * the matrix-core accumulators before the one addition into dW), so a queued W and `count` single
+ * ones agree to rounding, not bit for bit; fp32 mode runs the microbatches one after the other. */
+#define PMC_MAX_QUEUED_W 8
 int stage_backward_weight(pmc_chunk* chunk, const int32_t* mbs, int32_t count);
 
 /* ---- schedules (host only; no GPU needed) --------------------------------------------------- */
@@ -268,6 +275,14 @@ typedef enum pmc_epilogue {
 int pmc_gemm(pmc_ctx* ctx, int32_t dtype, int32_t trans_a, int32_t trans_b, int32_t M, int32_t N,
              int32_t K, const void* A, int32_t lda, const void* B, int32_t ldb, void* C, int32_t ldc,
              int32_t epilogue, const void* bias, const void* resid, void* aux);
+
+/* C[M,N] (fp32) += sum over i < count of A_i^T . B_i, with A_i stored [K,M] (row pitch lda) and
+ * B_i stored [K,N] (row pitch ldb), bf16, all device; a, b: host arrays of `count` device pointers
+ * (1 <= count <= PMC_MAX_QUEUED_W).  One product over the concatenated K axis: the kernel behind
+ * the queued W pass.  M, N multiples of 8, K (of one piece) a multiple of 64. */
+int pmc_gemm_grouped_wgrad(pmc_ctx* ctx, int32_t M, int32_t N, int32_t K, int32_t count,
+                           const void* const* a, int32_t lda, const void* const* b, int32_t ldb,
+                           float* C, int32_t ldc);
 
 /* y = LayerNorm(x) over rows of length h (a multiple of 4 up to 4096 in fp32, of 8 up to 8192 in
  * bf16); mean and rstd are fp32 [rows]; x_copy (may be NULL) receives a copy of x. */

@@ -99,6 +99,7 @@ _SIGS = {
     "pmc_trace_begin": (C.c_int, [_vp, _i32]),
     "pmc_trace_end": (C.c_int, [_vp, C.POINTER(TraceRec), _i32, C.POINTER(_i32)]),
     "pmc_gemm": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _i32, _vp, _i32, _vp, _i32, _i32, _vp, _vp, _vp]),
+    "pmc_gemm_grouped_wgrad": (C.c_int, [_vp, _i32, _i32, _i32, _i32, C.POINTER(_vp), _i32, C.POINTER(_vp), _i32, _vp, _i32]),
     "pmc_layernorm_forward": (C.c_int, [_vp, _i32, _i32, _i32, _vp, _vp, _vp, C.c_float, _vp, _vp, _vp, _vp]),
     "pmc_layernorm_backward": (C.c_int, [_vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "pmc_attention_forward": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp]),
@@ -373,6 +374,14 @@ def pmc_gemm(ctx, a, b, c, trans_a=False, trans_b=False, epilogue=EPI_NONE, bias
     K = a.shape[0] if trans_a else a.shape[1]
     _check(lib.pmc_gemm(ctx, _dt(a), int(trans_a), int(trans_b), M, N, K, _ptr(a), a.stride(0), _ptr(b), b.stride(0),
                         _ptr(c), c.stride(0), epilogue, _ptr(bias), _ptr(resid), _ptr(aux)))
+
+
+def pmc_gemm_grouped_wgrad(ctx, a_list, b_list, c) -> None:
+    """c[M,N] (fp32) += sum_i a_i^T . b_i with a_i [K,M], b_i [K,N] bf16: one product over the pieces."""
+    M, N = c.shape
+    K = a_list[0].shape[0]
+    _check(lib.pmc_gemm_grouped_wgrad(ctx, M, N, K, len(a_list), _ptr_array(a_list), a_list[0].stride(0),
+                                      _ptr_array(b_list), b_list[0].stride(0), _ptr(c), c.stride(0)))
 
 
 def pmc_layernorm_forward(ctx, x, gain, bias, eps, y, mean, rstd, x_copy=None) -> None:

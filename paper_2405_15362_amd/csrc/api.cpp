@@ -428,6 +428,56 @@ int chunk_backward_weight_one(pmc_chunk* ch, int32_t mb, bool release) {
   return PMC_OK;
 }
 
+// W of 2 .. PMC_MAX_QUEUED_W microbatches of a bf16 chunk at once: per layer, the bias gradients of
+// each microbatch, then every weight gradient as one product over the microbatches' concatenated
+// token axis (one read-modify-write of the fp32 accumulator for the whole group).
+int chunk_backward_weight_group(pmc_chunk* ch, const int32_t* mbs, int count) {
+  const pmc_chunk_cfg& c = ch->cfg;
+  pmc_ctx* ctx = ch->ctx;
+  hipStream_t st = ctx->stream;
+  const int T = ch->tokens, h = c.hidden, f = c.ffn, L = c.layers;
+  char* slab[PMC_MAX_QUEUED_W];
+  for (int i = 0; i < count; ++i) slab[i] = ch->live.find(mbs[i])->second.slab;
+  auto grouped = [&](int M, int N, auto a_of, int lda, auto b_of, int ldb, float* C) {
+    k::GroupedWgradArgs g;
+    g.M = M; g.N = N; g.K = T; g.count = count; g.lda = lda; g.ldb = ldb; g.C = C; g.ldc = N;
+    for (int i = 0; i < count; ++i) {
+      g.A[i] = a_of(slab[i]);
+      g.B[i] = b_of(slab[i]);
+    }
+    const int variant = 1 | (PMC_EPI_ACCUM_F32 << 2);
+    return traced(ctx, PMC_OP_GEMM, PMC_W, M, N, T * count, variant, [&] { return k::gemm_bf16_grouped_wgrad(st, g); });
+  };
+  for (int l = L - 1; l >= 0; --l) {
+    const LayerOffsets& o = ch->off[l];
+    const size_t dxout_off = l == L - 1 ? ch->off[0].x : ch->off[l + 1].x;
+    for (int i = 0; i < count; ++i) {
+      char* s = slab[i];
+      k::ColumnSumJobs jobs = {};
+      jobs.count = 4;
+      const void* src[4] = {s + dxout_off, s + o.u, s + o.xmid, s + o.qkv};
+      const int width[4] = {h, f, h, 3 * h};
+      const int which[4] = {B_2, B_1, B_O, B_QKV};
+      for (int j = 0; j < 4; ++j) {
+        jobs.a[j] = src[j];
+        jobs.out[j] = G(ch, l, which[j]);
+        jobs.n[j] = jobs.lda[j] = width[j];
+      }
+      PMC_TRY(traced(ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sums(st, c.dtype, T, jobs); }));
+    }
+    PMC_TRY(grouped(f, h, [&](char* s) { return s + o.g; }, f, [&](char* s) { return s + dxout_off; }, h, G(ch, l, W_2)));
+    PMC_TRY(grouped(h, f, [&](char* s) { return s + o.c; }, h, [&](char* s) { return s + o.u; }, f, G(ch, l, W_1)));
+    PMC_TRY(grouped(h, h, [&](char* s) { return s + o.o; }, h, [&](char* s) { return s + o.xmid; }, h, G(ch, l, W_O)));
+    PMC_TRY(grouped(h, 3 * h, [&](char* s) { return s + o.a; }, h, [&](char* s) { return s + o.qkv; }, 3 * h, G(ch, l, W_QKV)));
+  }
+  for (int i = 0; i < count; ++i) {
+    auto it = ch->live.find(mbs[i]);
+    ctx->pool.give(it->second.slab, it->second.device, (int64_t)(ch->unit_bytes - ch->stats_bytes));
+    ch->live.erase(it);
+  }
+  return PMC_OK;
+}
+
 // Returns a slab whose W has run with release = false.
 int chunk_release(pmc_chunk* ch, int32_t mb) {
   auto it = ch->live.find(mb);
@@ -593,7 +643,15 @@ int stage_backward_weight(pmc_chunk* ch, const int32_t* mbs, int32_t count) {
     for (int32_t j = 0; j < i; ++j)
       if (mbs[j] == mbs[i]) return fail(PMC_ERR_INVALID, "stage_backward_weight: microbatch %d listed twice", mbs[i]);
   }
-  for (int32_t i = 0; i < count; ++i) PMC_TRY(chunk_backward_weight_one(ch, mbs[i], true));
+  // bf16 chunks whose token count fills whole 64-wide K tiles: groups of queued microbatches go
+  // through one product per weight; everything else one microbatch at a time
+  const bool group = ch->cfg.dtype == PMC_BF16 && ch->tokens % 64 == 0;
+  for (int32_t i = 0; i < count;) {
+    const int32_t n = group ? (count - i < PMC_MAX_QUEUED_W ? count - i : PMC_MAX_QUEUED_W) : 1;
+    if (n > 1) PMC_TRY(chunk_backward_weight_group(ch, mbs + i, n));
+    else PMC_TRY(chunk_backward_weight_one(ch, mbs[i], true));
+    i += n;
+  }
   return PMC_OK;
 }
 
@@ -643,6 +701,19 @@ int pmc_gemm(pmc_ctx* ctx, int32_t dtype, int32_t trans_a, int32_t trans_b, int3
   g.epilogue = epilogue; g.bias = bias; g.resid = resid; g.aux = aux;
   g.ws = ctx->ws; g.ws_bytes = ctx->ws_bytes;
   return k::gemm(ctx->stream, g);
+}
+
+int pmc_gemm_grouped_wgrad(pmc_ctx* ctx, int32_t M, int32_t N, int32_t K, int32_t count, const void* const* a, int32_t lda,
+                           const void* const* b, int32_t ldb, float* C, int32_t ldc) {
+  if (!ctx || !a || !b || !C) return fail(PMC_ERR_INVALID, "pmc_gemm_grouped_wgrad: NULL argument");
+  if (count < 1 || count > PMC_MAX_QUEUED_W) return fail(PMC_ERR_INVALID, "pmc_gemm_grouped_wgrad: count %d (1..%d)", count, PMC_MAX_QUEUED_W);
+  k::GroupedWgradArgs g;
+  g.M = M; g.N = N; g.K = K; g.count = count; g.lda = lda; g.ldb = ldb; g.C = C; g.ldc = ldc;
+  for (int i = 0; i < count; ++i) {
+    g.A[i] = a[i];
+    g.B[i] = b[i];
+  }
+  return k::gemm_bf16_grouped_wgrad(ctx->stream, g);
 }
 
 int pmc_layernorm_forward(pmc_ctx* ctx, int32_t dtype, int32_t rows, int32_t h, const void* x, const void* gain,

@@ -36,6 +36,8 @@ namespace pmc {
 namespace k {
 namespace {
 
+constexpr int kMaxSegments = PMC_MAX_QUEUED_W;
+
 struct GemmParams {
   const bf16_t* A;
   const bf16_t* B;
@@ -46,6 +48,12 @@ struct GemmParams {
   int M, N, K, lda, ldb, ldc;
   int tiles_m, tiles_n;
   int k_tiles_per_split;  // fast path: 64-wide K tiles each blockIdx.y handles (all of K when not split)
+  // Segmented contraction (weight gradients of several queued microbatches in one product): the K
+  // axis is the concatenation of nseg pieces of seg_tiles 64-wide tiles each, piece i living at
+  // (Aseg[i], Bseg[i]) with the pitches lda, ldb.  nseg = 0: one piece at (A, B).
+  const bf16_t* Aseg[kMaxSegments];
+  const bf16_t* Bseg[kMaxSegments];
+  int nseg, seg_tiles;
 };
 
 constexpr int kEpiPartial = 100;  // fast path, split K: store the fp32 partial product of split blockIdx.y
@@ -442,7 +450,7 @@ __device__ __forceinline__ bf16x8 read_frag_swz(const bf16_t* tile, int r0, int 
 // One output tile (tile_m, tile_n) over the K tiles kt0 .. kt0 + nk - 1: ring prologue, K loop,
 // staged epilogue.  All waves of the workgroup call it together; on return the LDS ring holds
 // epilogue slabs that other waves may still be reading (barrier before the ring is filled again).
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KMAJ, bool B_KMAJ, int NSTAGE, int EPI>
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KMAJ, bool B_KMAJ, int NSTAGE, int EPI, bool SEG = false>
 __device__ __forceinline__ void dma_tile(const GemmParams& p, bf16_t* smem, int tile_m, int tile_n, int kt0, int nk) {
 #if defined(__HIP_DEVICE_COMPILE__)
   constexpr int BK = 64, NW = WAVES_M * WAVES_N, WM = BM / WAVES_M, WN = BN / WAVES_N, TM = WM / 32, TN = WN / 32;
@@ -456,7 +464,7 @@ __device__ __forceinline__ void dma_tile(const GemmParams& p, bf16_t* smem, int 
     i32x4 r = {(int)(uint32_t)a, (int)(uint32_t)(a >> 32), 0x7fffffff, 0x00020000};
     return r;
   };
-  const i32x4 ra = make_rsrc(p.A), rb = make_rsrc(p.B);
+  i32x4 ra = make_rsrc(p.A), rb = make_rsrc(p.B);
   DmaLoader<BM, A_KMAJ, NW> la;
   DmaLoader<BN, B_KMAJ, NW> lb;
   la.init(p.lda, m0, p.M, wave, lane);
@@ -497,11 +505,31 @@ __device__ __forceinline__ void dma_tile(const GemmParams& p, bf16_t* smem, int 
   static_assert(INFL < 64, "vmcnt is a 6-bit field");
   constexpr int WAIT_TILE = (INFL & 15) | ((INFL >> 4) << 14) | (7 << 4) | (15 << 8);  // s_waitcnt vmcnt(INFL)
   auto tile_k = [&](int t) { return kt0 + (t < nk ? t : nk - 1); };
-#pragma unroll
-  for (int t = 0; t < NSTAGE - 1; ++t) {
-    la.issue(ra, smem + t * STAGE, tile_k(t) * stepa, wave);
-    lb.issue(rb, smem + t * STAGE + TA, tile_k(t) * stepb, wave);
+  // Requests K tile t of this call into a stage.  Segmented: tile kt0 + t of the concatenated axis
+  // is tile `local` of piece `seg`; the two are stepped along with the requests (which come in
+  // ascending t), so no division sits in the loop.
+  int seg = 0, local = 0;
+  if (SEG) {
+    seg = kt0 / p.seg_tiles;
+    local = kt0 - seg * p.seg_tiles;
+    ra = make_rsrc(p.Aseg[seg]);
+    rb = make_rsrc(p.Bseg[seg]);
   }
+  auto request = [&](int t, int stage) {
+    const int kt = SEG ? local : tile_k(t);
+    la.issue(ra, smem + stage * STAGE, kt * stepa, wave);
+    lb.issue(rb, smem + stage * STAGE + TA, kt * stepb, wave);
+    if (SEG && t + 1 < nk) {  // past the end the last tile is requested again
+      if (++local == p.seg_tiles) {
+        local = 0;
+        ++seg;
+        ra = make_rsrc(p.Aseg[seg]);
+        rb = make_rsrc(p.Bseg[seg]);
+      }
+    }
+  };
+#pragma unroll
+  for (int t = 0; t < NSTAGE - 1; ++t) request(t, t);
   __builtin_amdgcn_s_waitcnt(WAIT_TILE);
   __syncthreads();
 #pragma unroll
@@ -514,8 +542,7 @@ __device__ __forceinline__ void dma_tile(const GemmParams& p, bf16_t* smem, int 
     const bf16_t* cur_b = cur_a + TA;
     const int nxt = cur + 1 == NSTAGE ? 0 : cur + 1;
     const int fill = cur == 0 ? NSTAGE - 1 : cur - 1;  // all its readers passed the last barrier
-    la.issue(ra, smem + fill * STAGE, tile_k(kt + NSTAGE - 1) * stepa, wave);
-    lb.issue(rb, smem + fill * STAGE + TA, tile_k(kt + NSTAGE - 1) * stepb, wave);
+    request(kt + NSTAGE - 1, fill);
     step(0, cur_a, cur_b, 16);
     step(1, cur_a, cur_b, 32);
     step(0, cur_a, cur_b, 48);
@@ -536,14 +563,14 @@ __device__ __forceinline__ void dma_tile(const GemmParams& p, bf16_t* smem, int 
 #endif
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KMAJ, bool B_KMAJ, int NSTAGE, int EPI>
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KMAJ, bool B_KMAJ, int NSTAGE, int EPI, bool SEG = false>
 __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_bf16_dma_kernel(GemmParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)
   extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
   int tile_m, tile_n;
   tile_of_block(p, tile_m, tile_n);
   const int nk = p.k_tiles_per_split;
-  dma_tile<BM, BN, WAVES_M, WAVES_N, A_KMAJ, B_KMAJ, NSTAGE, EPI>(p, smem, tile_m, tile_n, (int)blockIdx.y * nk, nk);
+  dma_tile<BM, BN, WAVES_M, WAVES_N, A_KMAJ, B_KMAJ, NSTAGE, EPI, SEG>(p, smem, tile_m, tile_n, (int)blockIdx.y * nk, nk);
 #endif
 }
 
@@ -555,7 +582,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_bf16_dma_kernel(G
 // workgroup id) starts its first tile at K tile g/G of the way through, and comes back for that
 // tile's first K tiles after its last tile.  Both parts are added into C by the same workgroup, in
 // that order, so the result depends on the launch shape alone.
-template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int GROUPS>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int GROUPS, bool SEG = false>
 __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_bf16_wgrad_persistent_kernel(GemmParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)
   extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
@@ -571,15 +598,15 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_bf16_wgrad_persis
     if (first) {
       tm0 = tile_m;
       tn0 = tile_n;
-      dma_tile<BM, BN, WAVES_M, WAVES_N, false, false, NSTAGE, PMC_EPI_ACCUM_F32>(p, smem, tile_m, tile_n, head, nk - head);
+      dma_tile<BM, BN, WAVES_M, WAVES_N, false, false, NSTAGE, PMC_EPI_ACCUM_F32, SEG>(p, smem, tile_m, tile_n, head, nk - head);
       first = false;
     } else {
-      dma_tile<BM, BN, WAVES_M, WAVES_N, false, false, NSTAGE, PMC_EPI_ACCUM_F32>(p, smem, tile_m, tile_n, 0, nk);
+      dma_tile<BM, BN, WAVES_M, WAVES_N, false, false, NSTAGE, PMC_EPI_ACCUM_F32, SEG>(p, smem, tile_m, tile_n, 0, nk);
     }
     __syncthreads();
   }
   if (!first && head > 0)
-    dma_tile<BM, BN, WAVES_M, WAVES_N, false, false, NSTAGE, PMC_EPI_ACCUM_F32>(p, smem, tm0, tn0, 0, head);
+    dma_tile<BM, BN, WAVES_M, WAVES_N, false, false, NSTAGE, PMC_EPI_ACCUM_F32, SEG>(p, smem, tm0, tn0, 0, head);
 #endif
 }
 
@@ -689,12 +716,12 @@ int launch_tile(hipStream_t st, const GemmParams& p, int epi) {
   return launch_epi<128, 128, 64, 64, 64, A_KMAJ, B_KMAJ>(st, p, epi);
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KMAJ, bool B_KMAJ, int NSTAGE, int EPI>
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KMAJ, bool B_KMAJ, int NSTAGE, int EPI, bool SEG = false>
 int launch_dma(hipStream_t st, GemmParams p) {
   constexpr int NT = WAVES_M * WAVES_N * 64;
   constexpr size_t lds = (size_t)NSTAGE * (BM + BN) * 64 * sizeof(bf16_t);
   static_assert(lds <= 160 * 1024, "stages do not fit the 160 KB LDS");
-  auto kern = gemm_bf16_dma_kernel<BM, BN, WAVES_M, WAVES_N, A_KMAJ, B_KMAJ, NSTAGE, EPI>;
+  auto kern = gemm_bf16_dma_kernel<BM, BN, WAVES_M, WAVES_N, A_KMAJ, B_KMAJ, NSTAGE, EPI, SEG>;
   static bool configured = false;  // per instantiation
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -735,15 +762,15 @@ int pick_tile(int M, int N) {
   return best;
 }
 
-template <bool A_KMAJ, bool B_KMAJ, int EPI>
+template <bool A_KMAJ, bool B_KMAJ, int EPI, bool SEG = false>
 int launch_dma_tile(hipStream_t st, const GemmParams& p) {
   switch (pick_tile(p.M, p.N)) {
-    case 0: return launch_dma<256, 256, 2, 4, A_KMAJ, B_KMAJ, 2, EPI>(st, p);
-    case 1: return launch_dma<256, 128, 4, 2, A_KMAJ, B_KMAJ, 3, EPI>(st, p);
+    case 0: return launch_dma<256, 256, 2, 4, A_KMAJ, B_KMAJ, 2, EPI, SEG>(st, p);
+    case 1: return launch_dma<256, 128, 4, 2, A_KMAJ, B_KMAJ, 3, EPI, SEG>(st, p);
     case 3:  // the [64 k][rows] swizzle needs 128 rows: a 64-row A tile only when A is contraction-contiguous
-      if constexpr (A_KMAJ) return launch_dma<64, 128, 1, 4, A_KMAJ, B_KMAJ, 3, EPI>(st, p);
-      else return launch_dma<128, 128, 2, 2, A_KMAJ, B_KMAJ, 2, EPI>(st, p);
-    default: return launch_dma<128, 128, 2, 2, A_KMAJ, B_KMAJ, 2, EPI>(st, p);
+      if constexpr (A_KMAJ) return launch_dma<64, 128, 1, 4, A_KMAJ, B_KMAJ, 3, EPI, SEG>(st, p);
+      else return launch_dma<128, 128, 2, 2, A_KMAJ, B_KMAJ, 2, EPI, SEG>(st, p);
+    default: return launch_dma<128, 128, 2, 2, A_KMAJ, B_KMAJ, 2, EPI, SEG>(st, p);
   }
 }
 
@@ -756,10 +783,11 @@ bool use_wgrad_persistent(const GemmParams& p) {
   return (long)((p.M + 255) / 256) * ((p.N + 255) / 256) >= 2 * 256;
 }
 
+template <bool SEG>
 int launch_wgrad_persistent(hipStream_t st, GemmParams p) {
   constexpr int NSTAGE = 2, GROUPS = 2;  // measured: 2 phases give the most (1: -6 % W-pass time, 2: -8 %, 4 and 8: -7 %)
   constexpr size_t lds = (size_t)NSTAGE * (256 + 256) * 64 * sizeof(bf16_t);
-  auto kern = gemm_bf16_wgrad_persistent_kernel<256, 256, 2, 4, NSTAGE, GROUPS>;
+  auto kern = gemm_bf16_wgrad_persistent_kernel<256, 256, 2, 4, NSTAGE, GROUPS, SEG>;
   static bool configured = false;
   static int units = 0;
   if (!configured) {
@@ -874,6 +902,8 @@ int gemm_bf16(hipStream_t st, const GemmArgs& a) {
   p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldb = a.ldb; p.ldc = a.ldc;
   p.tiles_m = p.tiles_n = 0;
   p.k_tiles_per_split = 0;
+  p.nseg = p.seg_tiles = 0;
+  for (int i = 0; i < kMaxSegments; ++i) p.Aseg[i] = p.Bseg[i] = nullptr;
   const bool a_kmaj = !a.trans_a, b_kmaj = a.trans_b;
   // Fast path: K in whole 64-wide tiles, operands inside the 2 GB window of a buffer descriptor.
   const size_t a_bytes = (size_t)(a.trans_a ? a.K : a.M) * a.lda * 2, b_bytes = (size_t)(a.trans_b ? a.N : a.K) * a.ldb * 2;
@@ -886,7 +916,7 @@ int gemm_bf16(hipStream_t st, const GemmArgs& a) {
       if (rc != PMC_OK) return rc;
       return launch_reduce(st, p, (const float*)a.ws, splits, a.epilogue);
     }
-    if (!a_kmaj && !b_kmaj && a.epilogue == PMC_EPI_ACCUM_F32 && use_wgrad_persistent(p)) return launch_wgrad_persistent(st, p);
+    if (!a_kmaj && !b_kmaj && a.epilogue == PMC_EPI_ACCUM_F32 && use_wgrad_persistent(p)) return launch_wgrad_persistent<false>(st, p);
     const int rc = launch_fast(st, p, a_kmaj, b_kmaj, a.epilogue);
     if (rc != kNoFastPath) return rc;
   }
@@ -894,6 +924,35 @@ int gemm_bf16(hipStream_t st, const GemmArgs& a) {
   if (a_kmaj && !b_kmaj) return launch_tile<true, false>(st, p, a.epilogue);
   if (!a_kmaj && b_kmaj) return launch_tile<false, true>(st, p, a.epilogue);
   return launch_tile<false, false>(st, p, a.epilogue);
+}
+
+// C[M,N] (fp32) += sum over pieces i of A_i^T . B_i, A_i stored [K,M], B_i stored [K,N]: one product
+// whose contraction runs through the pieces one after the other, one read-modify-write of C.
+int gemm_bf16_grouped_wgrad(hipStream_t st, const GroupedWgradArgs& a) {
+  if (a.count < 1 || a.count > kMaxSegments) return fail(PMC_ERR_INVALID, "grouped weight gradient: %d pieces (1..%d)", a.count, kMaxSegments);
+  if (a.M % 8 || a.N % 8 || a.K % 64) return fail(PMC_ERR_INVALID, "grouped weight gradient: M=%d N=%d must be multiples of 8, K=%d of 64", a.M, a.N, a.K);
+  if (a.lda % 8 || a.ldb % 8 || a.ldc % 4 || a.lda < a.M || a.ldb < a.N || a.ldc < a.N)
+    return fail(PMC_ERR_INVALID, "grouped weight gradient: bad pitches (lda=%d ldb=%d ldc=%d)", a.lda, a.ldb, a.ldc);
+  if ((size_t)a.K * a.lda * 2 >= 0x7fffffffull || (size_t)a.K * a.ldb * 2 >= 0x7fffffffull)
+    return fail(PMC_ERR_INVALID, "grouped weight gradient: a piece exceeds the 2 GB window of a buffer descriptor");
+  if (!aligned(a.C, 16)) return fail(PMC_ERR_INVALID, "grouped weight gradient: C must be 16-byte aligned");
+  GemmParams p;
+  p.A = (const bf16_t*)a.A[0]; p.B = (const bf16_t*)a.B[0]; p.C = a.C;
+  p.bias = p.resid = nullptr; p.aux = nullptr;
+  p.M = a.M; p.N = a.N; p.K = a.K * a.count; p.lda = a.lda; p.ldb = a.ldb; p.ldc = a.ldc;
+  p.tiles_m = p.tiles_n = 0;
+  p.k_tiles_per_split = p.K / 64;
+  p.nseg = a.count;
+  p.seg_tiles = a.K / 64;
+  for (int i = 0; i < kMaxSegments; ++i) {
+    const int j = i < a.count ? i : a.count - 1;
+    if (!a.A[j] || !a.B[j] || !aligned(a.A[j], 16) || !aligned(a.B[j], 16))
+      return fail(PMC_ERR_INVALID, "grouped weight gradient: piece %d is NULL or not 16-byte aligned", j);
+    p.Aseg[i] = (const bf16_t*)a.A[j];
+    p.Bseg[i] = (const bf16_t*)a.B[j];
+  }
+  if (use_wgrad_persistent(p)) return launch_wgrad_persistent<true>(st, p);
+  return launch_dma_tile<false, false, PMC_EPI_ACCUM_F32, true>(st, p);
 }
 
 size_t gemm_scratch_bytes(int dtype, int M, int N, int K) {

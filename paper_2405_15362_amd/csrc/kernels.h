@@ -26,6 +26,19 @@ struct GemmArgs {
   size_t ws_bytes = 0;
 };
 
+// Weight gradients of several queued microbatches as ONE product: C[M,N] (fp32) += sum_i A_i^T . B_i
+// with A_i stored [K,M] (pitch lda) and B_i stored [K,N] (pitch ldb), bf16.  K a multiple of 64.
+struct GroupedWgradArgs {
+  int M = 0, N = 0, K = 0;  // K of ONE piece
+  int count = 0;            // 1 .. PMC_MAX_QUEUED_W pieces
+  const void* A[PMC_MAX_QUEUED_W] = {};
+  const void* B[PMC_MAX_QUEUED_W] = {};
+  int lda = 0, ldb = 0;
+  float* C = nullptr;
+  int ldc = 0;
+};
+int gemm_bf16_grouped_wgrad(hipStream_t stream, const GroupedWgradArgs& a);
+
 // Scratch a product of this shape can use (0: none).
 size_t gemm_scratch_bytes(int dtype, int M, int N, int K);
 

@@ -137,6 +137,56 @@ def test_gemm_bf16_weight_gradient_persistent(ctx, monkeypatch):
     assert rel_l2(host(outs[0]), host(outs[2])) <= 1e-6     # the plain kernel adds K in one piece
 
 
+@pytest.mark.parametrize("wgrad", ["0", "1"])
+def test_gemm_bf16_grouped_weight_gradient(ctx, monkeypatch, wgrad):
+    """Queued weight gradients as one product: C += sum_i A_i^T B_i over pieces that live in separate
+    buffers.  Every tile shape of the plain kernel and the persistent one; one piece, several pieces,
+    the maximum; pieces of a single 64-wide K tile (a piece boundary at every tile) and of many;
+    ragged M and N; and the same bits from run to run.  Against the fp64 sum of the pieces' products;
+    the result must also agree with adding the pieces one product at a time."""
+    monkeypatch.setenv("PMC_GEMM_WGRAD", wgrad)
+    cases = [(512, 256, 64, 3), (264, 136, 192, 2), (1000, 1544, 128, 8), (2048, 2304, 256, 4), (4104, 4360, 64, 5),
+             (128, 128, 1024, 1)]
+    for tile in (None, "0", "1", "2"):
+        if tile is None:
+            monkeypatch.delenv("PMC_GEMM_TILE", raising=False)
+        else:
+            monkeypatch.setenv("PMC_GEMM_TILE", tile)
+        for M, N, K, count in (cases if tile is None else cases[:3]):
+            key = ("grouped", M, N, K, count)
+            print("grouped wgrad case", key, "tile", tile, "persistent", wgrad, flush=True)
+            a = [mat(key + ("a", i), (K, M), "bf16") for i in range(count)]
+            b = [mat(key + ("b", i), (K, N), "bf16", 0.05) for i in range(count)]
+            c0 = mat(key + ("c0",), (M, N), "f32")
+            ref = c0.astype(np.float64)
+            for x, y in zip(a, b):
+                ref = ref + x.T.astype(np.float64) @ y.astype(np.float64)
+            da, db = [dev(x, "bf16") for x in a], [dev(y, "bf16") for y in b]
+            outs = []
+            for _ in range(2):
+                c = dev(c0, "f32")
+                P.pmc_gemm_grouped_wgrad(ctx, da, db, c)
+                outs.append(c)
+            one_by_one = dev(c0, "f32")
+            for x, y in zip(da, db):
+                P.pmc_gemm(ctx, x, y, one_by_one, True, False, P.EPI_ACCUM_F32)
+            torch.cuda.synchronize()
+            assert torch.equal(outs[0], outs[1]), key
+            assert rel_l2(host(outs[0]), ref) <= 1e-5, (key, rel_l2(host(outs[0]), ref))   # fp32 sums of exact bf16 products
+            assert rel_l2(host(outs[0]), host(one_by_one)) <= 1e-5, key
+
+
+def test_gemm_grouped_weight_gradient_rejects_bad_arguments(ctx):
+    a = [torch.zeros(64, 128, device="cuda", dtype=torch.bfloat16)]
+    b = [torch.zeros(64, 128, device="cuda", dtype=torch.bfloat16)]
+    c = torch.zeros(128, 128, device="cuda", dtype=torch.float32)
+    with pytest.raises(P.PmcError):
+        P.pmc_gemm_grouped_wgrad(ctx, a * 9, b * 9, c)                       # more pieces than PMC_MAX_QUEUED_W
+    a32 = [torch.zeros(32, 128, device="cuda", dtype=torch.bfloat16)]
+    with pytest.raises(P.PmcError):
+        P.pmc_gemm_grouped_wgrad(ctx, a32, a32, c)                           # K not in whole 64-wide tiles
+
+
 @pytest.mark.parametrize("ta,tb", [(False, False), (False, True), (True, False)])
 def test_gemm_bf16_large_tiles(ctx, ta, tb):
     # enough 256x256 tiles to take the large-tile path, ragged edge tiles included

@@ -83,11 +83,31 @@ def test_deferred_w_accumulates_over_microbatches(name):
     for l in range(cfg.layers):
         for k in OL.PARAM_NAMES:
             assert rel_l2(grads[l][k], total[l][k]) <= tol(cfg.dtype), (l, k)
-    # immediate W per microbatch gives the same bits as the queued one (same order of additions)
+    # immediate W per microbatch: in fp32 mode the queued pass runs the same products in the same
+    # order (same bits); in bf16 mode it contracts the queued microbatches in one product per weight
+    # (same sum up to fp32 summation order), LayerNorm and bias gradients keep their order
     _, _, _, (_, _, grads2) = _run_fbw(cfg, name + "_defer", n_mb, defer=False)
     for l in range(cfg.layers):
         for k in OL.PARAM_NAMES:
-            assert np.array_equal(grads[l][k], grads2[l][k]), (l, k)
+            if cfg.dtype == "f32" or k not in ("w_qkv", "w_o", "w_1", "w_2"):
+                assert np.array_equal(grads[l][k], grads2[l][k]), (l, k)
+            else:
+                assert rel_l2(grads[l][k], grads2[l][k]) <= 1e-5, (l, k, rel_l2(grads[l][k], grads2[l][k]))
+
+
+def test_queued_w_groups_larger_than_the_maximum():
+    """More queued microbatches than one grouped product takes (8): the list is cut into groups; ragged
+    token count (not a multiple of 64) falls back to one microbatch at a time.  Both against the oracle."""
+    for name, n_mb in (("dh128_bf16", 10), ("dh64_ragged_bf16", 3)):
+        cfg = CASES[name]
+        params, xs, dys, (ys, dxs, grads) = _run_fbw(cfg, name + "_q", n_mb, defer=True)
+        total = OL.zero_grads(OL.cast_params(params))
+        for j in range(n_mb):
+            _, _, ln, wg = oracle_chunk(cfg, params, xs[j], dys[j])
+            OL.accumulate(total, ln, wg)
+        for l in range(cfg.layers):
+            for k in OL.PARAM_NAMES:
+                assert rel_l2(grads[l][k], total[l][k]) <= tol(cfg.dtype), (name, l, k)
 
 
 def test_pass_order_errors():

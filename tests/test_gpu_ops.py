@@ -176,6 +176,62 @@ def test_gemm_bf16_grouped_weight_gradient(ctx, monkeypatch, wgrad):
             assert rel_l2(host(outs[0]), host(one_by_one)) <= 1e-5, key
 
 
+def test_gemm_bf16_largest_workload_shapes_sampled(ctx):
+    """The twelve products of a layer at the largest workload (hidden 5120, FFN 20480, 4096 tokens), at
+    full size and in the launch configuration the passes use (heuristic tile choice, persistent W
+    kernel).  Operands are drawn on the GPU from a seeded generator (2e8 elements per product);
+    a few thousand output elements, rows and columns sampled over all tiles including the last,
+    are checked against fp64 dot products with the epilogue's definition applied."""
+    T, h, f = 4096, 5120, 20480
+    gen = torch.Generator(device="cuda").manual_seed(4)
+    rng = np.random.default_rng(4)
+    bf = torch.bfloat16
+
+    def rnd(shape, scale):
+        return (torch.randn(shape, device="cuda", generator=gen) * scale).to(bf)
+
+    def f64(t):
+        return t.float().cpu().numpy().astype(np.float64)
+
+    cases = [("F qkv", False, False, T, 3 * h, h, P.EPI_BIAS), ("F proj", False, False, T, h, h, P.EPI_BIAS_RESID),
+             ("F fc1", False, False, T, f, h, P.EPI_BIAS_GELU), ("F fc2", False, False, T, h, f, P.EPI_BIAS_RESID),
+             ("B dfc2", False, True, T, f, h, P.EPI_DGELU), ("B dfc1", False, True, T, h, f, P.EPI_NONE),
+             ("B dproj", False, True, T, h, h, P.EPI_NONE), ("B dqkv", False, True, T, h, 3 * h, P.EPI_NONE),
+             ("W fc2", True, False, f, h, T, P.EPI_ACCUM_F32), ("W fc1", True, False, h, f, T, P.EPI_ACCUM_F32),
+             ("W proj", True, False, h, h, T, P.EPI_ACCUM_F32), ("W qkv", True, False, h, 3 * h, T, P.EPI_ACCUM_F32)]
+    for name, ta, tb, M, N, K, epi in cases:
+        print("largest-shape gemm", name, M, N, K, flush=True)
+        a = rnd((K, M) if ta else (M, K), 1.0)
+        b = rnd((N, K) if tb else (K, N), 0.02)
+        bias, extra = rnd((N,), 0.02), rnd((M, N), 1.0)          # extra: residual or GeLU input
+        c = (torch.randn((M, N), device="cuda", generator=gen) if epi == P.EPI_ACCUM_F32
+             else torch.zeros((M, N), device="cuda", dtype=bf))
+        c0 = c.clone() if epi == P.EPI_ACCUM_F32 else None
+        aux = extra.clone() if epi == P.EPI_DGELU else (torch.zeros_like(extra) if epi == P.EPI_BIAS_GELU else None)
+        P.pmc_gemm(ctx, a, b, c, ta, tb, epi, bias if epi in (P.EPI_BIAS, P.EPI_BIAS_RESID, P.EPI_BIAS_GELU) else None,
+                   extra if epi == P.EPI_BIAS_RESID else None, aux)
+        torch.cuda.synchronize()
+        ms = np.unique(np.concatenate([rng.integers(0, M, 46), [0, M - 1]]))
+        ns = np.unique(np.concatenate([rng.integers(0, N, 46), [0, N - 1]]))
+        mi, ni = torch.from_numpy(ms).cuda(), torch.from_numpy(ns).cuda()
+        A = f64(a[:, mi]).T if ta else f64(a[mi])                 # [len(ms), K]
+        B = f64(b[ni]).T if tb else f64(b[:, ni])                 # [K, len(ns)]
+        ref = A @ B
+        sub = lambda t: f64(t[mi][:, ni])
+        if epi in (P.EPI_BIAS, P.EPI_BIAS_RESID, P.EPI_BIAS_GELU):
+            ref = ref + f64(bias[ni])
+        if epi == P.EPI_BIAS_RESID:
+            ref = ref + sub(extra)
+        if epi == P.EPI_DGELU:
+            ref = ref * OL.gelu_grad(sub(extra))
+        if epi == P.EPI_ACCUM_F32:
+            ref = ref + sub(c0)
+        assert rel_l2(sub(c), ref) <= tol("bf16"), (name, rel_l2(sub(c), ref))
+        if epi == P.EPI_BIAS_GELU:
+            assert rel_l2(sub(aux), OL.gelu(ref)) <= tol("bf16"), name
+        del a, b, c, c0, aux, extra
+
+
 def test_gemm_grouped_weight_gradient_rejects_bad_arguments(ctx):
     a = [torch.zeros(64, 128, device="cuda", dtype=torch.bfloat16)]
     b = [torch.zeros(64, 128, device="cuda", dtype=torch.bfloat16)]

@@ -109,7 +109,7 @@ struct LayerOffsets {  // byte offsets inside the slab
 };
 
 struct WorkspaceLayout {
-  size_t t_h, attn, partial, gemm, gemm_bytes, total;
+  size_t t_h, attn, partial, partial_stride, gemm, gemm_bytes, total;
 };
 
 }  // namespace pmc
@@ -175,8 +175,10 @@ WorkspaceLayout workspace_of(const pmc_chunk_cfg& c) {
   w.attn = at;
   at += k::attention_backward_scratch_bytes(c.dtype, c.microbatch, c.seq, c.heads, c.hidden / c.heads);
   w.partial = at;
+  // one region per LayerNorm of the backward pass (their reductions are run together at its end)
   const size_t pf = k::layernorm_backward_scratch_floats(t, c.hidden);
-  at += align256(pf * sizeof(float));
+  w.partial_stride = align256(pf * sizeof(float));
+  at += w.partial_stride * (size_t)std::min(2 * c.layers, (int)k::LnPartialJobs::kMax);
   // split-K partial products of the skinny projections (F and B write [tokens, hidden] outputs)
   size_t g = 0;
   const int h = c.hidden, f = c.ffn;
@@ -319,7 +321,16 @@ int chunk_backward_input(pmc_chunk* ch, int32_t mb, const void* dy, void* dx) {
   char* ws = ch->ctx->ws;
   void* t_h = ws + ch->wsl.t_h;
   void* attn_ws = ws + ch->wsl.attn;
-  float* partial = (float*)(ws + ch->wsl.partial);
+  // LayerNorm gain/bias gradients: each call leaves its partial sums in a region of its own and
+  // one launch adds them all up (when the regions run out, and at the end of the pass)
+  k::LnPartialJobs ln_jobs;
+  auto next_partial = [&]() { return (float*)(ws + ch->wsl.partial + (size_t)ln_jobs.count * ch->wsl.partial_stride); };
+  auto flush_ln = [&](bool force) {
+    if (ln_jobs.count == 0 || (!force && ln_jobs.count < k::LnPartialJobs::kMax)) return (int)PMC_OK;
+    const int rc = traced(ch->ctx, PMC_OP_LN_BWD, PMC_B, ln_jobs.count, 2 * h, 0, 1, [&] { return k::layernorm_backward_reduce(st, h, ln_jobs); });
+    ln_jobs.count = 0;
+    return rc;
+  };
   for (int l = L - 1; l >= 0; --l) {
     const LayerOffsets& o = ch->off[l];
     const void* dyl = l == L - 1 ? dy : (const void*)(s + ch->off[l + 1].x);
@@ -330,7 +341,8 @@ int chunk_backward_input(pmc_chunk* ch, int32_t mb, const void* dy, void* dx) {
     PMC_TRY(t_gemm(ch->ctx, PMC_B, gemm_args(ch, false, true, T, h, f, s + o.u, f, P(ch, l, W_1), f, t_h, h, PMC_EPI_NONE), ch->wsl));
     // dX_mid = dY + LN2 input-gradient(dC), written over X_mid; LN2 gain/bias gradients
     PMC_TRY(traced(ch->ctx, PMC_OP_LN_BWD, PMC_B, T, h, 0, 0, [&] { return k::layernorm_backward(st, c.dtype, T, h, t_h, s + o.xmid, P(ch, l, LN2_G), (const float*)(s + o.mean2),
-                                  (const float*)(s + o.rstd2), dyl, s + o.xmid, G(ch, l, LN2_G), G(ch, l, LN2_B), partial); }));
+                                  (const float*)(s + o.rstd2), dyl, s + o.xmid, G(ch, l, LN2_G), G(ch, l, LN2_B), next_partial(), &ln_jobs); }));
+    PMC_TRY(flush_ln(false));
     // dO = dX_mid . Wo^T
     PMC_TRY(t_gemm(ch->ctx, PMC_B, gemm_args(ch, false, true, T, h, h, s + o.xmid, h, P(ch, l, W_O), h, t_h, h, PMC_EPI_NONE), ch->wsl));
     // dQKV, written over QKV
@@ -342,8 +354,10 @@ int chunk_backward_input(pmc_chunk* ch, int32_t mb, const void* dy, void* dx) {
     // dX = dX_mid + LN1 input-gradient(dA): over X for inner layers, to the caller for layer 0
     void* out = l == 0 ? dx : (void*)(s + o.x);
     PMC_TRY(traced(ch->ctx, PMC_OP_LN_BWD, PMC_B, T, h, 0, 0, [&] { return k::layernorm_backward(st, c.dtype, T, h, t_h, s + o.x, P(ch, l, LN1_G), (const float*)(s + o.mean1),
-                                  (const float*)(s + o.rstd1), s + o.xmid, out, G(ch, l, LN1_G), G(ch, l, LN1_B), partial); }));
+                                  (const float*)(s + o.rstd1), s + o.xmid, out, G(ch, l, LN1_G), G(ch, l, LN1_B), next_partial(), &ln_jobs); }));
+    PMC_TRY(flush_ln(false));
   }
+  PMC_TRY(flush_ln(true));
   // keep the chunk's dY for W of the top layer in the slot of the (now dead) chunk input
   PMC_TRY(traced(ch->ctx, PMC_OP_COPY, PMC_B, T, h, 0, 0, [&] { return k::copy_rows(st, c.dtype, T, h, dy, h, s + ch->off[0].x, h); }));
   m.state = kBackwardDone;

@@ -48,11 +48,24 @@ int gemm_bf16(hipStream_t stream, const GemmArgs& a);
 
 int layernorm_forward(hipStream_t stream, int dtype, int rows, int h, const void* x, const void* gain,
                       const void* bias, float eps, void* y, float* mean, float* rstd, void* x_copy);
-// partial: fp32 scratch of layernorm_backward_scratch_floats(rows, h) floats.
+// partial: fp32 scratch of layernorm_backward_scratch_floats(rows, h) floats.  The kernel leaves one
+// row of gain/bias-gradient partial sums per workgroup there; a second, tiny kernel adds them into
+// dgain/dbias.  With `defer` given that second step is only noted down (the scratch must then stay
+// untouched, one region per call) and layernorm_backward_reduce runs all noted reductions in ONE
+// launch: a backward pass has two LayerNorms per layer and pays for one such launch, not for 2 L.
+struct LnPartialJobs {
+  static constexpr int kMax = 16;
+  const float* partial[kMax];
+  float* dgain[kMax];
+  float* dbias[kMax];
+  int parts[kMax];
+  int count = 0;
+};
 size_t layernorm_backward_scratch_floats(int rows, int h);
 int layernorm_backward(hipStream_t stream, int dtype, int rows, int h, const void* dy, const void* x,
                        const void* gain, const float* mean, const float* rstd, const void* resid, void* dx,
-                       float* dgain, float* dbias, float* partial);
+                       float* dgain, float* dbias, float* partial, LnPartialJobs* defer = nullptr);
+int layernorm_backward_reduce(hipStream_t stream, int h, const LnPartialJobs& jobs);
 
 int attention_forward(hipStream_t stream, int dtype, int batch, int seq, int heads, int head_dim, int causal,
                       const void* qkv, void* o, float* lse);

@@ -193,14 +193,15 @@ __global__ __launch_bounds__(kBwdWaves * 64) void ln_bwd_kernel(int rows, int h,
   }
 }
 
-// out_a[i] += sum_p partial[p*stride + i] (i < split), out_b[i - split] += ... (i >= split).
-// A block handles 64 columns; its four waves each sum a contiguous quarter of the parts (loads
-// are independent, so many are in flight), and the quarters are added in order 0,1,2,3: the
-// summation order is fixed by (parts) alone.
-__global__ __launch_bounds__(256) void sum_partials_kernel(int parts, int width, int split, size_t stride,
-                                                            const float* __restrict__ partial,
-                                                            float* __restrict__ out_a, float* __restrict__ out_b) {
+// For every job j (blockIdx.y): out_a[i] += sum_p partial_j[p*stride + i] (i < split),
+// out_b[i - split] += ... (i >= split).  A block handles 64 columns; its four waves each sum a
+// contiguous quarter of the parts (loads are independent, so many are in flight), and the quarters
+// are added in order 0,1,2,3: the summation order is fixed by (parts) alone.
+__global__ __launch_bounds__(256) void sum_partials_kernel(LnPartialJobs jobs, int width, int split, size_t stride) {
   __shared__ float quarter[4][64];
+  const int job = blockIdx.y;
+  const float* __restrict__ partial = jobs.partial[job];
+  const int parts = jobs.parts[job];
   const int lane = threadIdx.x & 63, g = threadIdx.x >> 6;
   const int i = blockIdx.x * 64 + lane;
   const int per = (parts + 3) / 4, p0 = g * per, p1 = min(parts, p0 + per);
@@ -220,8 +221,8 @@ __global__ __launch_bounds__(256) void sum_partials_kernel(int parts, int width,
   __syncthreads();
   if (g == 0 && i < width) {
     const float total = ((quarter[0][lane] + quarter[1][lane]) + quarter[2][lane]) + quarter[3][lane];
-    if (i < split) out_a[i] += total;
-    else out_b[i - split] += total;
+    if (i < split) jobs.dgain[job][i] += total;
+    else jobs.dbias[job][i - split] += total;
   }
 }
 
@@ -343,7 +344,8 @@ int ln_fwd_t(hipStream_t st, int rows, int h, const void* x, const void* gain, c
 
 template <typename T>
 int ln_bwd_t(hipStream_t st, int rows, int h, const void* dy, const void* x, const void* gain, const float* mean,
-             const float* rstd, const void* resid, void* dx, float* dgain, float* dbias, float* partial) {
+             const float* rstd, const void* resid, void* dx, float* dgain, float* dbias, float* partial,
+             LnPartialJobs* defer) {
   const LnBwdShape sh = ln_bwd_shape(h, Vec<T>::N);
   if (!sh.nc) return fail(PMC_ERR_INVALID, "LayerNorm width %d too large", h);
   const int blocks = ln_bwd_blocks(rows, kBwdWaves / sh.wr);
@@ -365,10 +367,15 @@ int ln_bwd_t(hipStream_t st, int rows, int h, const void* dy, const void* x, con
   }
 #undef LN_BWD_CASE
   PMC_LAUNCH_CHECK("layernorm_backward");
-  sum_partials_kernel<<<dim3((2 * h + 63) / 64), dim3(256), 0, st>>>(blocks, 2 * h, h, (size_t)2 * h, partial, dgain,
-                                                                       dbias);
-  PMC_LAUNCH_CHECK("layernorm_backward reduce");
-  return PMC_OK;
+  LnPartialJobs now;
+  LnPartialJobs& jobs = defer ? *defer : now;
+  if (jobs.count >= LnPartialJobs::kMax) return fail(PMC_ERR_INVALID, "layernorm_backward: too many deferred reductions");
+  jobs.partial[jobs.count] = partial;
+  jobs.dgain[jobs.count] = dgain;
+  jobs.dbias[jobs.count] = dbias;
+  jobs.parts[jobs.count] = blocks;
+  ++jobs.count;
+  return defer ? PMC_OK : layernorm_backward_reduce(st, h, jobs);
 }
 
 }  // namespace
@@ -391,9 +398,16 @@ size_t layernorm_backward_scratch_floats(int rows, int h) {
   return (size_t)ln_bwd_blocks(rows, 1) * 2 * h;
 }
 
+int layernorm_backward_reduce(hipStream_t st, int h, const LnPartialJobs& jobs) {
+  if (jobs.count < 1 || jobs.count > LnPartialJobs::kMax) return fail(PMC_ERR_INVALID, "layernorm_backward_reduce: %d jobs", jobs.count);
+  sum_partials_kernel<<<dim3((2 * h + 63) / 64, jobs.count), dim3(256), 0, st>>>(jobs, 2 * h, h, (size_t)2 * h);
+  PMC_LAUNCH_CHECK("layernorm_backward reduce");
+  return PMC_OK;
+}
+
 int layernorm_backward(hipStream_t st, int dtype, int rows, int h, const void* dy, const void* x, const void* gain,
                        const float* mean, const float* rstd, const void* resid, void* dx, float* dgain, float* dbias,
-                       float* partial) {
+                       float* partial, LnPartialJobs* defer) {
   if (rows <= 0 || h <= 0) return fail(PMC_ERR_INVALID, "layernorm_backward: rows=%d h=%d", rows, h);
   const int vec = dtype == PMC_F32 ? 4 : 8;
   if (h % vec) return fail(PMC_ERR_INVALID, "layernorm_backward: h=%d must be a multiple of %d", h, vec);
@@ -402,8 +416,8 @@ int layernorm_backward(hipStream_t st, int dtype, int rows, int h, const void* d
   if (!aligned16(dy) || !aligned16(x) || !aligned16(gain) || !aligned16(dx) || (resid && !aligned16(resid)))
     return fail(PMC_ERR_INVALID, "layernorm_backward: pointers must be 16-byte aligned");
   if ((size_t)2 * h * sizeof(float) > 64 * 1024) return fail(PMC_ERR_INVALID, "layernorm_backward: h=%d too large", h);
-  if (dtype == PMC_F32) return ln_bwd_t<float>(st, rows, h, dy, x, gain, mean, rstd, resid, dx, dgain, dbias, partial);
-  if (dtype == PMC_BF16) return ln_bwd_t<bf16_t>(st, rows, h, dy, x, gain, mean, rstd, resid, dx, dgain, dbias, partial);
+  if (dtype == PMC_F32) return ln_bwd_t<float>(st, rows, h, dy, x, gain, mean, rstd, resid, dx, dgain, dbias, partial, defer);
+  if (dtype == PMC_BF16) return ln_bwd_t<bf16_t>(st, rows, h, dy, x, gain, mean, rstd, resid, dx, dgain, dbias, partial, defer);
   return fail(PMC_ERR_INVALID, "layernorm_backward: bad dtype %d", dtype);
 }
 

@@ -424,7 +424,8 @@ int chunk_backward_weight_one(pmc_chunk* ch, int32_t mb, bool release) {
       jobs.out[j] = G(ch, l, which[j]);
       jobs.n[j] = jobs.lda[j] = width[j];
     }
-    PMC_TRY(traced(ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sums(st, c.dtype, T, jobs); }));
+    // (memory-bound, no matrix work: on the second stream it runs under the first product)
+    PMC_TRY(traced(ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sums(two ? ctx->side : st, c.dtype, T, jobs); }));
     PMC_TRY(t_gemm(ctx, PMC_W, gemm_args(ch, true, false, f, h, T, s + o.g, f, dxout, h, G(ch, l, W_2), h, PMC_EPI_ACCUM_F32), ch->wsl));
     PMC_TRY(side_gemm(gemm_args(ch, true, false, h, f, T, s + o.c, h, s + o.u, f, G(ch, l, W_1), f, PMC_EPI_ACCUM_F32)));
     PMC_TRY(t_gemm(ctx, PMC_W, gemm_args(ch, true, false, h, h, T, s + o.o, h, s + o.xmid, h, G(ch, l, W_O), h, PMC_EPI_ACCUM_F32), ch->wsl));

@@ -150,6 +150,10 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_fwd_m
   sk.store(smem, tid);
   sv.store(smem + KT, tid);
   __syncthreads();
+  // The query fragments must have arrived before the loop: left pending, the compiler's wait for
+  // them inside the loop would also cover the loads that prefetch the next block.
+#pragma unroll
+  for (int ks = 0; ks < DH / 16; ++ks) asm volatile("" ::"v"(qf[ks]));
   for (int blk = 0; blk < nblk; ++blk) {
     const int k0 = blk * BSW + WK * kg;  // this wave's 32 NKT keys
     const bf16_t* kt_ = smem + (blk & 1) * (KT + VT);
@@ -159,15 +163,28 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_fwd_m
       sv.load(base + 2 * h, ld, (blk + 1) * BSW, seq, tid);
     }
     if (k0 < seq && (!causal || k0 <= qw0 + 31)) {
+      // The K fragments of a 32-key tile are requested together, and those of the next tile each
+      // as soon as its register is free, so that the LDS latency is paid once, not per product; the
+      // first V fragments are requested before the softmax arithmetic for the same reason.
       f32x16 s[NKT];
+      bf16x8 kf[DH / 16];
+#pragma unroll
+      for (int ks = 0; ks < DH / 16; ++ks) kf[ks] = frag_rows(kt_, KP, WK * kg, 16 * ks, lane);
+      __builtin_amdgcn_sched_barrier(0);  // the compiler would sink the reads to their uses again
 #pragma unroll
       for (int kt = 0; kt < NKT; ++kt) {
         zero(s[kt]);
 #pragma unroll
-        for (int ks = 0; ks < DH / 16; ++ks)
-          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(kt_, KP, WK * kg + 32 * kt, 16 * ks, lane), qf[ks],
-                                                          s[kt], 0, 0, 0);
+        for (int ks = 0; ks < DH / 16; ++ks) {
+          s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], s[kt], 0, 0, 0);
+          if (kt + 1 < NKT) kf[ks] = frag_rows(kt_, KP, WK * kg + 32 * (kt + 1), 16 * ks, lane);
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
+      bf16x8 vf[2][DH / 32];
+#pragma unroll
+      for (int dt = 0; dt < DH / 32; ++dt) vf[0][dt] = frag_cols(vt_, VP, 32 * dt, WK * kg, lane);
+      __builtin_amdgcn_sched_barrier(0);
       // only blocks that cross the diagonal of this wave's rows or the end of the sequence need masks
       if ((causal && k0 + WK - 1 > qw0) || (k0 + WK > seq)) {
 #pragma unroll
@@ -207,15 +224,16 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_fwd_m
       }
       lsum += rowsum;
 #pragma unroll
-      for (int kt = 0; kt < NKT; ++kt)
+      for (int g = 0; g < 2 * NKT; ++g) {  // 16 keys at a time: tile g / 2, half g % 2
+        if (g + 1 < 2 * NKT) {
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          const bf16x8 pb = acc_to_frag(s[kt], t);
-#pragma unroll
-          for (int dt = 0; dt < DH / 32; ++dt)
-            oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                frag_cols(vt_, VP, 32 * dt, WK * kg + 32 * kt + 16 * t, lane), pb, oacc[dt], 0, 0, 0);
+          for (int dt = 0; dt < DH / 32; ++dt) vf[(g + 1) & 1][dt] = frag_cols(vt_, VP, 32 * dt, WK * kg + 16 * (g + 1), lane);
         }
+        const bf16x8 pb = acc_to_frag(s[g >> 1], g & 1);
+#pragma unroll
+        for (int dt = 0; dt < DH / 32; ++dt)
+          oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[g & 1][dt], pb, oacc[dt], 0, 0, 0);
+      }
     }
     if (blk + 1 < nblk) {
       bf16_t* nxt = smem + ((blk + 1) & 1) * (KT + VT);

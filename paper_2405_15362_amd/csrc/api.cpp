@@ -83,13 +83,16 @@ struct pmc_ctx {
   char* ws = nullptr;
   size_t ws_bytes = 0;
   int chunks_alive = 0;
-  // second stream for the W pass of small chunks (created on first use, default priority)
-  hipStream_t side = nullptr;
-  hipEvent_t fork = nullptr, join = nullptr;
+  // second stream for the W pass (created on first use, default priority)
+  static constexpr int kSide = 1;
+  hipStream_t side[kSide] = {};
+  hipEvent_t fork = nullptr, join[kSide] = {};
   ~pmc_ctx() {
     if (fork) (void)hipEventDestroy(fork);
-    if (join) (void)hipEventDestroy(join);
-    if (side) (void)hipStreamDestroy(side);
+    for (int i = 0; i < kSide; ++i) {
+      if (join[i]) (void)hipEventDestroy(join[i]);
+      if (side[i]) (void)hipStreamDestroy(side[i]);
+    }
   }
 };
 
@@ -365,25 +368,29 @@ int chunk_backward_input(pmc_chunk* ch, int32_t mb, const void* dy, void* dx) {
   return PMC_OK;
 }
 
-// The weight-gradient products of a pass do not depend on each other.  When they are small (each
-// fills the compute units for two rounds of tiles at most) half of them go to a second stream:
-// workgroups of two different products then share the chip, one product's read-modify-write of dW
-// overlaps the other's matrix work, and the tail of one fills with the head of the next (measured
-// -15 % on the W products of a hidden-2048, 1024-token chunk; larger products gain nothing or
-// lose, so they stay on one stream).  Off while tracing, whose per-operation events assume one stream.
-bool w_pass_two_streams(const pmc_chunk* ch) {
-  if (ch->ctx->tracing || ch->cfg.dtype != PMC_BF16) return false;
-  if (const char* f = std::getenv("PMC_W_STREAMS")) return f[0] == '2';
-  const long tiles = (long)((ch->cfg.hidden + 255) / 256) * ((ch->cfg.ffn + 255) / 256);
-  return tiles <= 512;
+// The weight-gradient products of a pass do not depend on each other.  Every second one goes to a
+// second stream (fork and join with events inside the pass): workgroups of two different products
+// then share the chip, one product's read-modify-write of dW overlaps the other's matrix work, the
+// tail of one fills with the head of the next, and the memory-bound bias-gradient sums run under a
+// product (measured on the W pass: -5 % at hidden 2048 / 1024 tokens, -6 % at 4096 / 2048, -5 % at
+// 5120 / 4096; a third and fourth stream gain nothing more).  PMC_W_STREAMS=1|2 forces the choice.
+// Off while tracing, whose per-operation events assume one stream.
+int w_pass_streams(const pmc_chunk* ch) {
+  if (ch->ctx->tracing || ch->cfg.dtype != PMC_BF16) return 1;
+  if (const char* f = std::getenv("PMC_W_STREAMS"))
+    if ((f[0] == '1' || f[0] == '2') && f[1] == 0) return f[0] - '0';
+  return 2;
 }
 
-int side_stream(pmc_ctx* ctx) {
-  if (ctx->side) return PMC_OK;
-  if (hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) != hipSuccess ||
-      hipEventCreateWithFlags(&ctx->fork, hipEventDisableTiming) != hipSuccess ||
-      hipEventCreateWithFlags(&ctx->join, hipEventDisableTiming) != hipSuccess)
-    return fail(PMC_ERR_HIP, "cannot create the second stream of the W pass");
+int side_streams(pmc_ctx* ctx, int n) {
+  if (!ctx->fork && hipEventCreateWithFlags(&ctx->fork, hipEventDisableTiming) != hipSuccess)
+    return fail(PMC_ERR_HIP, "cannot create the fork event of the W pass");
+  for (int i = 0; i < n; ++i) {
+    if (ctx->side[i]) continue;
+    if (hipStreamCreateWithFlags(&ctx->side[i], hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&ctx->join[i], hipEventDisableTiming) != hipSuccess)
+      return fail(PMC_ERR_HIP, "cannot create a side stream of the W pass");
+  }
   return PMC_OK;
 }
 
@@ -397,18 +404,24 @@ int chunk_backward_weight_one(pmc_chunk* ch, int32_t mb, bool release) {
   hipStream_t st = ctx->stream;
   const int T = ch->tokens, h = c.hidden, f = c.ffn, L = c.layers;
   char* s = m.slab;
-  const bool two = w_pass_two_streams(ch);
+  const int ns = w_pass_streams(ch);
+  const bool two = ns > 1;
   if (two) {
-    PMC_TRY(side_stream(ctx));
-    if (hipEventRecord(ctx->fork, st) != hipSuccess || hipStreamWaitEvent(ctx->side, ctx->fork, 0) != hipSuccess)
-      return fail(PMC_ERR_HIP, "stage_backward_weight: cannot fork the second stream");
+    PMC_TRY(side_streams(ctx, ns - 1));
+    if (hipEventRecord(ctx->fork, st) != hipSuccess) return fail(PMC_ERR_HIP, "stage_backward_weight: cannot fork");
+    for (int i = 0; i < ns - 1; ++i)
+      if (hipStreamWaitEvent(ctx->side[i], ctx->fork, 0) != hipSuccess)
+        return fail(PMC_ERR_HIP, "stage_backward_weight: cannot fork a side stream");
   }
-  // a product on the second stream: no split-K scratch (the first stream's products own it)
+  // product number `slot` of the pass: stream slot % ns (0 = the caller's); side streams get no
+  // split-K scratch (the first stream's products own it)
+  int slot = 0;
   auto side_gemm = [&](k::GemmArgs g) {
-    if (!two) return t_gemm(ctx, PMC_W, g, ch->wsl);
+    const int which = slot++ % ns;
+    if (which == 0) return t_gemm(ctx, PMC_W, g, ch->wsl);
     g.ws = nullptr;
     g.ws_bytes = 0;
-    return k::gemm(ctx->side, g);
+    return k::gemm(ctx->side[which - 1], g);
   };
   for (int l = L - 1; l >= 0; --l) {
     const LayerOffsets& o = ch->off[l];
@@ -425,17 +438,16 @@ int chunk_backward_weight_one(pmc_chunk* ch, int32_t mb, bool release) {
       jobs.n[j] = jobs.lda[j] = width[j];
     }
     // (memory-bound, no matrix work: on the second stream it runs under the first product)
-    PMC_TRY(traced(ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sums(two ? ctx->side : st, c.dtype, T, jobs); }));
-    PMC_TRY(t_gemm(ctx, PMC_W, gemm_args(ch, true, false, f, h, T, s + o.g, f, dxout, h, G(ch, l, W_2), h, PMC_EPI_ACCUM_F32), ch->wsl));
+    PMC_TRY(traced(ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sums(two ? ctx->side[ns - 2] : st, c.dtype, T, jobs); }));
+    PMC_TRY(side_gemm(gemm_args(ch, true, false, f, h, T, s + o.g, f, dxout, h, G(ch, l, W_2), h, PMC_EPI_ACCUM_F32)));
     PMC_TRY(side_gemm(gemm_args(ch, true, false, h, f, T, s + o.c, h, s + o.u, f, G(ch, l, W_1), f, PMC_EPI_ACCUM_F32)));
-    PMC_TRY(t_gemm(ctx, PMC_W, gemm_args(ch, true, false, h, h, T, s + o.o, h, s + o.xmid, h, G(ch, l, W_O), h, PMC_EPI_ACCUM_F32), ch->wsl));
+    PMC_TRY(side_gemm(gemm_args(ch, true, false, h, h, T, s + o.o, h, s + o.xmid, h, G(ch, l, W_O), h, PMC_EPI_ACCUM_F32)));
     PMC_TRY(side_gemm(gemm_args(ch, true, false, h, 3 * h, T, s + o.a, h, s + o.qkv, 3 * h, G(ch, l, W_QKV), 3 * h,
                                 PMC_EPI_ACCUM_F32)));
   }
-  if (two) {
-    if (hipEventRecord(ctx->join, ctx->side) != hipSuccess || hipStreamWaitEvent(st, ctx->join, 0) != hipSuccess)
-      return fail(PMC_ERR_HIP, "stage_backward_weight: cannot join the second stream");
-  }
+  for (int i = 0; i < ns - 1; ++i)
+    if (hipEventRecord(ctx->join[i], ctx->side[i]) != hipSuccess || hipStreamWaitEvent(st, ctx->join[i], 0) != hipSuccess)
+      return fail(PMC_ERR_HIP, "stage_backward_weight: cannot join a side stream");
   if (release) {
     ch->ctx->pool.give(m.slab, m.device, (int64_t)(ch->unit_bytes - ch->stats_bytes));
     ch->live.erase(it);
@@ -453,7 +465,15 @@ int chunk_backward_weight_group(pmc_chunk* ch, const int32_t* mbs, int count) {
   const int T = ch->tokens, h = c.hidden, f = c.ffn, L = c.layers;
   char* slab[PMC_MAX_QUEUED_W];
   for (int i = 0; i < count; ++i) slab[i] = ch->live.find(mbs[i])->second.slab;
+  const int ns = w_pass_streams(ch);  // as in the single-microbatch pass: every second product on a second stream
+  if (ns > 1) {
+    PMC_TRY(side_streams(ctx, 1));
+    if (hipEventRecord(ctx->fork, st) != hipSuccess || hipStreamWaitEvent(ctx->side[0], ctx->fork, 0) != hipSuccess)
+      return fail(PMC_ERR_HIP, "stage_backward_weight: cannot fork the second stream");
+  }
+  int slot = 0;
   auto grouped = [&](int M, int N, auto a_of, int lda, auto b_of, int ldb, float* C) {
+    hipStream_t on = (ns > 1 && (slot++ & 1)) ? ctx->side[0] : st;
     k::GroupedWgradArgs g;
     g.M = M; g.N = N; g.K = T; g.count = count; g.lda = lda; g.ldb = ldb; g.C = C; g.ldc = N;
     for (int i = 0; i < count; ++i) {
@@ -461,7 +481,7 @@ int chunk_backward_weight_group(pmc_chunk* ch, const int32_t* mbs, int count) {
       g.B[i] = b_of(slab[i]);
     }
     const int variant = 1 | (PMC_EPI_ACCUM_F32 << 2);
-    return traced(ctx, PMC_OP_GEMM, PMC_W, M, N, T * count, variant, [&] { return k::gemm_bf16_grouped_wgrad(st, g); });
+    return traced(ctx, PMC_OP_GEMM, PMC_W, M, N, T * count, variant, [&] { return k::gemm_bf16_grouped_wgrad(on, g); });
   };
   for (int l = L - 1; l >= 0; --l) {
     const LayerOffsets& o = ch->off[l];
@@ -478,13 +498,15 @@ int chunk_backward_weight_group(pmc_chunk* ch, const int32_t* mbs, int count) {
         jobs.out[j] = G(ch, l, which[j]);
         jobs.n[j] = jobs.lda[j] = width[j];
       }
-      PMC_TRY(traced(ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sums(st, c.dtype, T, jobs); }));
+      PMC_TRY(traced(ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sums(ns > 1 ? ctx->side[0] : st, c.dtype, T, jobs); }));
     }
     PMC_TRY(grouped(f, h, [&](char* s) { return s + o.g; }, f, [&](char* s) { return s + dxout_off; }, h, G(ch, l, W_2)));
     PMC_TRY(grouped(h, f, [&](char* s) { return s + o.c; }, h, [&](char* s) { return s + o.u; }, f, G(ch, l, W_1)));
     PMC_TRY(grouped(h, h, [&](char* s) { return s + o.o; }, h, [&](char* s) { return s + o.xmid; }, h, G(ch, l, W_O)));
     PMC_TRY(grouped(h, 3 * h, [&](char* s) { return s + o.a; }, h, [&](char* s) { return s + o.qkv; }, 3 * h, G(ch, l, W_QKV)));
   }
+  if (ns > 1 && (hipEventRecord(ctx->join[0], ctx->side[0]) != hipSuccess || hipStreamWaitEvent(st, ctx->join[0], 0) != hipSuccess))
+    return fail(PMC_ERR_HIP, "stage_backward_weight: cannot join the second stream");
   for (int i = 0; i < count; ++i) {
     auto it = ch->live.find(mbs[i]);
     ctx->pool.give(it->second.slab, it->second.device, (int64_t)(ch->unit_bytes - ch->stats_bytes));

@@ -160,6 +160,31 @@ def main() -> int:
                   for k, v in sorted(shapes.items())]
     achieved = gemm_flop / (gemm_ms * 1e-3) / 1e12
 
+    # HBM-bound row kernels: algorithmic bytes (read + written) per launch over its traced time
+    e = 2 if cfg.dtype == "bf16" else 4
+    T = cfg.tokens
+
+    def rate(sel, nbytes):
+        ms = [r["ms"] for r in recs if sel(r)]
+        if not ms:
+            return None
+        t = float(np.median(ms))
+        return {"us_per_launch": round(1e3 * t, 2), "GB_per_s": round(nbytes / (t * 1e-3) / 1e9, 1), "bytes_per_launch": nbytes}
+
+    elementwise = {
+        "ln_fwd": rate(lambda r: r["op"] == "ln_fwd", 2 * T * h * e),                          # x in, y out
+        "ln_bwd": rate(lambda r: r["op"] == "ln_bwd" and not r["trans_a"], 4 * T * h * e),      # dy, x, resid in, dx out
+        "colsum": rate(lambda r: r["op"] == "colsum", T * (5 * h + f) * e),                     # the four dY of a layer
+        "copy": rate(lambda r: r["op"] == "copy", 2 * T * h * e),
+    }
+    att_f = [r["ms"] for r in recs if r["op"] == "attn_fwd"]
+    att_b = [r["ms"] for r in recs if r["op"] == "attn_bwd"]
+    att_unit = cfg.microbatch * s * s * h          # one causal score-sized product over all heads
+    attention = {"fwd_us": round(1e3 * float(np.median(att_f)), 1), "fwd_tflops": round(2 * att_unit / (float(np.median(att_f)) * 1e-3) / 1e12, 1),
+                 "bwd_us": round(1e3 * float(np.median(att_b)), 1),
+                 "bwd_tflops_executed": round(7 * att_unit / (float(np.median(att_b)) * 1e-3) / 1e12, 1),
+                 "flop": "causal: forward 2 s^2 h; backward executes 7 s^2 h (scores and dP recomputed in both kernels)"}
+
     def gemm_bytes(r):
         """Algorithmic HBM bytes of one product: both operands once, the result once (W: fp32
         read-modify-write), plus the tensor its epilogue reads or writes besides (residual, GeLU
@@ -192,6 +217,8 @@ def main() -> int:
         "passes": passes,
         "op_ms_per_step": op_ms_per_step,
         "gemm_shapes": gemm_table,
+        "elementwise_hbm": elementwise,
+        "attention": attention,
         "mfma_util_vs_peak": round(value / PEAK_BF16_TFLOPS, 4),
     }
 

@@ -266,7 +266,9 @@ typedef enum pmc_epilogue {
   PMC_EPI_BIAS_RESID = 2,  /* C = A.B + bias[n] + resid[m,n]                                  */
   PMC_EPI_BIAS_GELU = 3,   /* C = A.B + bias[n]; aux = gelu(C)                                */
   PMC_EPI_DGELU = 4,       /* C = (A.B) * gelu'(aux[m,n])  (C may alias aux)                  */
-  PMC_EPI_ACCUM_F32 = 5    /* C(fp32) += A.B                                                  */
+  PMC_EPI_ACCUM_F32 = 5,   /* C(fp32) += A.B                                                  */
+  PMC_EPI_BIAS_GELU_GRAD = 6, /* u = A.B + bias[n]; C = gelu'(u); aux = gelu(u)  (what F keeps of FC1) */
+  PMC_EPI_MUL = 7          /* C = (A.B) * aux[m,n]  (C may alias aux)                         */
 } pmc_epilogue;
 
 /* C[M,N] = op(A)[M,K] . op(B)[K,N] with the epilogue above.  trans_a = 0: A stored [M,K]

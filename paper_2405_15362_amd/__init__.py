@@ -23,7 +23,7 @@ KINDS = {"1f1b": PMC_1F1B, "vzb": PMC_VZB, "vhalf": PMC_VHALF, "vmin": PMC_VMIN}
 PMC_F, PMC_B, PMC_W = 0, 1, 2
 OPS = "FBW"
 PARAMS_PER_LAYER = 12
-EPI_NONE, EPI_BIAS, EPI_BIAS_RESID, EPI_BIAS_GELU, EPI_DGELU, EPI_ACCUM_F32 = range(6)
+EPI_NONE, EPI_BIAS, EPI_BIAS_RESID, EPI_BIAS_GELU, EPI_DGELU, EPI_ACCUM_F32, EPI_BIAS_GELU_GRAD, EPI_MUL = range(8)
 REPLAY_TIME_PASSES = 1
 PMC_OK, PMC_ERR_INVALID, PMC_ERR_STATE, PMC_ERR_NOMEM, PMC_ERR_HIP, PMC_ERR_ILLEGAL_BLOCK = 0, -1, -2, -3, -4, -5
 

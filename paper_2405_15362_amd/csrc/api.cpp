@@ -298,7 +298,8 @@ int chunk_forward(pmc_chunk* ch, int32_t mb, const void* x, void* y, int device)
                                   PMC_EPI_BIAS_RESID, P(ch, l, B_O), s + o.x), ch->wsl));
     PMC_TRY(traced(ch->ctx, PMC_OP_LN_FWD, PMC_F, T, h, 0, 0, [&] { return k::layernorm_forward(st, c.dtype, T, h, s + o.xmid, P(ch, l, LN2_G), P(ch, l, LN2_B), c.ln_eps, s + o.c,
                                  (float*)(s + o.mean2), (float*)(s + o.rstd2), nullptr); }));
-    PMC_TRY(t_gemm(ch->ctx, PMC_F, gemm_args(ch, false, false, T, f, h, s + o.c, h, P(ch, l, W_1), f, s + o.u, f, PMC_EPI_BIAS_GELU,
+    // FC1: the slab keeps gelu(u) for FC2 and W, and gelu'(u) (in the slot called u) for B
+    PMC_TRY(t_gemm(ch->ctx, PMC_F, gemm_args(ch, false, false, T, f, h, s + o.c, h, P(ch, l, W_1), f, s + o.u, f, PMC_EPI_BIAS_GELU_GRAD,
                                   P(ch, l, B_1), nullptr, s + o.g), ch->wsl));
     void* out = l == L - 1 ? y : (void*)(s + ch->off[l + 1].x);
     PMC_TRY(t_gemm(ch->ctx, PMC_F, gemm_args(ch, false, false, T, h, f, s + o.g, f, P(ch, l, W_2), h, out, h, PMC_EPI_BIAS_RESID,
@@ -337,8 +338,8 @@ int chunk_backward_input(pmc_chunk* ch, int32_t mb, const void* dy, void* dx) {
   for (int l = L - 1; l >= 0; --l) {
     const LayerOffsets& o = ch->off[l];
     const void* dyl = l == L - 1 ? dy : (const void*)(s + ch->off[l + 1].x);
-    // dU = (dY . W2^T) * gelu'(U), written over U
-    PMC_TRY(t_gemm(ch->ctx, PMC_B, gemm_args(ch, false, true, T, f, h, dyl, h, P(ch, l, W_2), h, s + o.u, f, PMC_EPI_DGELU, nullptr,
+    // dU = (dY . W2^T) * gelu'(U), written over the gelu'(U) that F left
+    PMC_TRY(t_gemm(ch->ctx, PMC_B, gemm_args(ch, false, true, T, f, h, dyl, h, P(ch, l, W_2), h, s + o.u, f, PMC_EPI_MUL, nullptr,
                                   nullptr, s + o.u), ch->wsl));
     // dC = dU . W1^T
     PMC_TRY(t_gemm(ch->ctx, PMC_B, gemm_args(ch, false, true, T, h, f, s + o.u, f, P(ch, l, W_1), f, t_h, h, PMC_EPI_NONE), ch->wsl));

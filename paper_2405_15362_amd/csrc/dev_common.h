@@ -104,6 +104,17 @@ __device__ __forceinline__ float gelu_fast(float u) {
   const float k0 = 0.7978845608028654f, k1 = 0.044715f;
   return 0.5f * u * (1.0f + tanh_fast(k0 * (u + k1 * u * u * u)));
 }
+// gelu(u) and gelu'(u) from one exp2 and one reciprocal: with r = 1 / (exp(2z) + 1), tanh z = 1 - 2r,
+// so gelu = u (1 - r) and gelu' = (1 - r) (1 + 2 u r z'),  z = k0 (u + k1 u^3),  z' = k0 (1 + 3 k1 u^2).
+__device__ __forceinline__ void gelu_both_fast(float u, float& g, float& dg) {
+  const float k0 = 0.7978845608028654f, k1 = 0.044715f;
+  const float u2 = u * u;
+  const float z = k0 * u * __builtin_fmaf(k1, u2, 1.0f);
+  const float r = __builtin_amdgcn_rcpf(__builtin_amdgcn_exp2f(z * 2.885390081777927f) + 1.0f);
+  const float s = 1.0f - r;
+  g = u * s;
+  dg = s * __builtin_fmaf(2.0f * k0 * u * r, __builtin_fmaf(3.0f * k1, u2, 1.0f), 1.0f);
+}
 __device__ __forceinline__ float gelu_grad_fast(float u) {
   const float k0 = 0.7978845608028654f, k1 = 0.044715f;
   const float t = tanh_fast(k0 * (u + k1 * u * u * u));

@@ -154,7 +154,7 @@ __device__ __forceinline__ void store_quad(const GemmParams& p, float (&v)[4], i
     return;
   }
   bf16_t* c = reinterpret_cast<bf16_t*>(p.C) + idx;
-  if (EPI == PMC_EPI_BIAS || EPI == PMC_EPI_BIAS_RESID || EPI == PMC_EPI_BIAS_GELU) {
+  if (EPI == PMC_EPI_BIAS || EPI == PMC_EPI_BIAS_RESID || EPI == PMC_EPI_BIAS_GELU || EPI == PMC_EPI_BIAS_GELU_GRAD) {
     float b[4];
     unpack4(*reinterpret_cast<const u32x2*>(p.bias + n), b);
 #pragma unroll
@@ -171,6 +171,20 @@ __device__ __forceinline__ void store_quad(const GemmParams& p, float (&v)[4], i
     unpack4(*reinterpret_cast<const u32x2*>(p.aux + idx), u);
 #pragma unroll
     for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_fast(u[e]);
+  }
+  if (EPI == PMC_EPI_MUL) {
+    float u[4];
+    unpack4(*reinterpret_cast<const u32x2*>(p.aux + idx), u);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] *= u[e];
+  }
+  if (EPI == PMC_EPI_BIAS_GELU_GRAD) {
+    float g[4], dg[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) gelu_both_fast(v[e], g[e], dg[e]);
+    *reinterpret_cast<u32x2*>(c) = pack4(dg);
+    *reinterpret_cast<u32x2*>(p.aux + idx) = pack4(g);
+    return;
   }
   *reinterpret_cast<u32x2*>(c) = pack4(v);
   if (EPI == PMC_EPI_BIAS_GELU) {
@@ -221,7 +235,8 @@ template <int EPI>
 struct OctOperand {
   f32x4 lo, hi;  // ACCUM
   u32x4 packed;  // BIAS_RESID, DGELU
-  static constexpr bool used = EPI == PMC_EPI_ACCUM_F32 || EPI == PMC_EPI_BIAS_RESID || EPI == PMC_EPI_DGELU;
+  static constexpr bool used =
+      EPI == PMC_EPI_ACCUM_F32 || EPI == PMC_EPI_BIAS_RESID || EPI == PMC_EPI_DGELU || EPI == PMC_EPI_MUL;
   __device__ __forceinline__ void load(const GemmParams& p, int m, int n) {
     const size_t idx = (size_t)m * p.ldc + n;
     if (EPI == PMC_EPI_ACCUM_F32) {
@@ -231,7 +246,7 @@ struct OctOperand {
       hi = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(c + 4));
     } else if (EPI == PMC_EPI_BIAS_RESID) {
       packed = *reinterpret_cast<const u32x4*>(p.resid + idx);
-    } else if (EPI == PMC_EPI_DGELU) {
+    } else if (EPI == PMC_EPI_DGELU || EPI == PMC_EPI_MUL) {
       packed = *reinterpret_cast<const u32x4*>(p.aux + idx);
     }
   }
@@ -258,7 +273,7 @@ __device__ __forceinline__ void store_oct(const GemmParams& p, float (&v)[8], in
     *reinterpret_cast<f32x4*>(c + 4) = hi;
     return;
   }
-  if (EPI == PMC_EPI_BIAS || EPI == PMC_EPI_BIAS_RESID || EPI == PMC_EPI_BIAS_GELU) {
+  if (EPI == PMC_EPI_BIAS || EPI == PMC_EPI_BIAS_RESID || EPI == PMC_EPI_BIAS_GELU || EPI == PMC_EPI_BIAS_GELU_GRAD) {
     float b[8];
     unpack8(*reinterpret_cast<const u32x4*>(p.bias + n), b);
 #pragma unroll
@@ -275,6 +290,20 @@ __device__ __forceinline__ void store_oct(const GemmParams& p, float (&v)[8], in
     unpack8(x.packed, u);
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_fast(u[e]);
+  }
+  if (EPI == PMC_EPI_MUL) {
+    float u[8];
+    unpack8(x.packed, u);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] *= u[e];
+  }
+  if (EPI == PMC_EPI_BIAS_GELU_GRAD) {
+    float g[8], dg[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) gelu_both_fast(v[e], g[e], dg[e]);
+    *reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(p.C) + idx) = pack8(dg);
+    *reinterpret_cast<u32x4*>(p.aux + idx) = pack8(g);
+    return;
   }
   *reinterpret_cast<u32x4*>(reinterpret_cast<bf16_t*>(p.C) + idx) = pack8(v);
   if (EPI == PMC_EPI_BIAS_GELU) {
@@ -707,6 +736,8 @@ int launch_epi(hipStream_t st, const GemmParams& p, int epi) {
     case PMC_EPI_BIAS_GELU: return launch<BM, BN, BK, WM, WN, A_KMAJ, B_KMAJ, PMC_EPI_BIAS_GELU>(st, p);
     case PMC_EPI_DGELU: return launch<BM, BN, BK, WM, WN, A_KMAJ, B_KMAJ, PMC_EPI_DGELU>(st, p);
     case PMC_EPI_ACCUM_F32: return launch<BM, BN, BK, WM, WN, A_KMAJ, B_KMAJ, PMC_EPI_ACCUM_F32>(st, p);
+    case PMC_EPI_BIAS_GELU_GRAD: return launch<BM, BN, BK, WM, WN, A_KMAJ, B_KMAJ, PMC_EPI_BIAS_GELU_GRAD>(st, p);
+    case PMC_EPI_MUL: return launch<BM, BN, BK, WM, WN, A_KMAJ, B_KMAJ, PMC_EPI_MUL>(st, p);
   }
   return fail(PMC_ERR_INVALID, "gemm_bf16: unknown epilogue %d", epi);
 }
@@ -857,6 +888,8 @@ int launch_reduce(hipStream_t st, const GemmParams& p, const float* ws, int spli
     case PMC_EPI_BIAS_GELU: return launch_reduce_epi<PMC_EPI_BIAS_GELU>(st, p, ws, splits);
     case PMC_EPI_DGELU: return launch_reduce_epi<PMC_EPI_DGELU>(st, p, ws, splits);
     case PMC_EPI_ACCUM_F32: return launch_reduce_epi<PMC_EPI_ACCUM_F32>(st, p, ws, splits);
+    case PMC_EPI_BIAS_GELU_GRAD: return launch_reduce_epi<PMC_EPI_BIAS_GELU_GRAD>(st, p, ws, splits);
+    case PMC_EPI_MUL: return launch_reduce_epi<PMC_EPI_MUL>(st, p, ws, splits);
   }
   return fail(PMC_ERR_INVALID, "gemm_bf16: unknown epilogue %d", epi);
 }
@@ -871,11 +904,13 @@ int launch_fast(hipStream_t st, const GemmParams& p, bool a_kmaj, bool b_kmaj, i
       case PMC_EPI_BIAS: return launch_dma_tile<true, false, PMC_EPI_BIAS>(st, p);
       case PMC_EPI_BIAS_RESID: return launch_dma_tile<true, false, PMC_EPI_BIAS_RESID>(st, p);
       case PMC_EPI_BIAS_GELU: return launch_dma_tile<true, false, PMC_EPI_BIAS_GELU>(st, p);
+      case PMC_EPI_BIAS_GELU_GRAD: return launch_dma_tile<true, false, PMC_EPI_BIAS_GELU_GRAD>(st, p);
     }
   } else if (a_kmaj && b_kmaj) {  // B: dX = dY . W^T
     switch (epi) {
       case PMC_EPI_NONE: return launch_dma_tile<true, true, PMC_EPI_NONE>(st, p);
       case PMC_EPI_DGELU: return launch_dma_tile<true, true, PMC_EPI_DGELU>(st, p);
+      case PMC_EPI_MUL: return launch_dma_tile<true, true, PMC_EPI_MUL>(st, p);
     }
   } else if (!a_kmaj && !b_kmaj) {  // W: dW += X^T . dY
     switch (epi) {

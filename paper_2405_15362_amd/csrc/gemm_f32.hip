@@ -70,6 +70,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(int M, int N, int K, cons
         case PMC_EPI_BIAS_GELU: v += bias[gn]; C[idx] = v; aux[idx] = gelu_f(v); break;
         case PMC_EPI_DGELU: C[idx] = v * gelu_grad_f(aux[idx]); break;
         case PMC_EPI_ACCUM_F32: C[idx] += v; break;
+        case PMC_EPI_BIAS_GELU_GRAD: v += bias[gn]; C[idx] = gelu_grad_f(v); aux[idx] = gelu_f(v); break;
+        case PMC_EPI_MUL: C[idx] = v * aux[idx]; break;
       }
     }
   }
@@ -115,10 +117,12 @@ int gemm(hipStream_t st, const GemmArgs& a) {
       if (!a.bias || !a.resid) return fail(PMC_ERR_INVALID, "gemm: bias+residual epilogue needs both");
       break;
     case PMC_EPI_BIAS_GELU:
+    case PMC_EPI_BIAS_GELU_GRAD:
       if (!a.bias || !a.aux) return fail(PMC_ERR_INVALID, "gemm: bias+gelu epilogue needs bias and aux");
       break;
     case PMC_EPI_DGELU:
-      if (!a.aux) return fail(PMC_ERR_INVALID, "gemm: gelu-gradient epilogue needs aux");
+    case PMC_EPI_MUL:
+      if (!a.aux) return fail(PMC_ERR_INVALID, "gemm: this epilogue needs aux");
       break;
     default:
       return fail(PMC_ERR_INVALID, "gemm: unknown epilogue %d", a.epilogue);

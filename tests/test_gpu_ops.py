@@ -35,7 +35,7 @@ def _gemm_case(ctx, dtype, ta, tb, M, N, K, epi):
     out_dtype = "f32" if epi == P.EPI_ACCUM_F32 else dtype
     c0 = mat(key + ("c0",), (M, N), "f32")
     c = dev(c0, out_dtype)
-    aux = dev(aux_in, dtype) if epi in (P.EPI_BIAS_GELU, P.EPI_DGELU) else None
+    aux = dev(aux_in, dtype) if epi in (P.EPI_BIAS_GELU, P.EPI_DGELU, P.EPI_BIAS_GELU_GRAD, P.EPI_MUL) else None
     want_aux = None
     if epi == P.EPI_BIAS:
         ref = ref + bias
@@ -48,8 +48,13 @@ def _gemm_case(ctx, dtype, ta, tb, M, N, K, epi):
         ref = ref * OL.gelu_grad(aux_in.astype(np.float64))
     elif epi == P.EPI_ACCUM_F32:
         ref = ref + c0
+    elif epi == P.EPI_BIAS_GELU_GRAD:
+        want_aux = OL.gelu(ref + bias)
+        ref = OL.gelu_grad(ref + bias)
+    elif epi == P.EPI_MUL:
+        ref = ref * aux_in.astype(np.float64)
     P.pmc_gemm(ctx, dev(a, dtype), dev(b, dtype), c, ta, tb, epi,
-               dev(bias, dtype) if epi in (P.EPI_BIAS, P.EPI_BIAS_RESID, P.EPI_BIAS_GELU) else None,
+               dev(bias, dtype) if epi in (P.EPI_BIAS, P.EPI_BIAS_RESID, P.EPI_BIAS_GELU, P.EPI_BIAS_GELU_GRAD) else None,
                dev(resid, dtype) if epi == P.EPI_BIAS_RESID else None, aux)
     torch.cuda.synchronize()
     assert rel_l2(host(c), ref) <= tol(dtype), key
@@ -60,7 +65,7 @@ def _gemm_case(ctx, dtype, ta, tb, M, N, K, epi):
 @pytest.mark.parametrize("ta", [False, True])
 @pytest.mark.parametrize("tb", [False, True])
 def test_gemm_f32_layouts_and_epilogues(ctx, ta, tb):
-    for epi in range(6):
+    for epi in range(8):
         _gemm_case(ctx, "f32", ta, tb, 77, 130, 45, epi)
     _gemm_case(ctx, "f32", ta, tb, 128, 256, 1024, P.EPI_NONE)
 
@@ -69,14 +74,14 @@ def test_gemm_f32_layouts_and_epilogues(ctx, ta, tb):
 @pytest.mark.parametrize("tb", [False, True])
 def test_gemm_bf16_small_tiles_ragged(ctx, ta, tb):
     # several 128x128 tiles with ragged tails in M, N and K
-    for epi in range(6):
+    for epi in range(8):
         _gemm_case(ctx, "bf16", ta, tb, 200, 328, 136, epi)
     _gemm_case(ctx, "bf16", ta, tb, 8, 8, 8, P.EPI_NONE)
     _gemm_case(ctx, "bf16", ta, tb, 512, 768, 1024, P.EPI_NONE)
 
 
-@pytest.mark.parametrize("ta,tb,epis", [(False, False, (P.EPI_NONE, P.EPI_BIAS, P.EPI_BIAS_RESID, P.EPI_BIAS_GELU)),
-                                        (False, True, (P.EPI_NONE, P.EPI_DGELU)),
+@pytest.mark.parametrize("ta,tb,epis", [(False, False, (P.EPI_NONE, P.EPI_BIAS, P.EPI_BIAS_RESID, P.EPI_BIAS_GELU, P.EPI_BIAS_GELU_GRAD)),
+                                        (False, True, (P.EPI_NONE, P.EPI_DGELU, P.EPI_MUL)),
                                         (True, False, (P.EPI_NONE, P.EPI_ACCUM_F32))])
 def test_gemm_bf16_direct_to_lds_path(ctx, ta, tb, epis):
     """K in whole 64-wide tiles takes the direct-to-LDS kernel: each of its three tile shapes, with
@@ -95,8 +100,8 @@ def test_gemm_bf16_direct_to_lds_path(ctx, ta, tb, epis):
     _gemm_case(ctx, "bf16", ta, tb, 3848, 4104, 320, epis[-1])   # heuristic choice, many tiles
 
 
-@pytest.mark.parametrize("ta,tb,epis", [(False, False, (P.EPI_BIAS, P.EPI_BIAS_RESID, P.EPI_BIAS_GELU)),
-                                        (False, True, (P.EPI_NONE, P.EPI_DGELU)),
+@pytest.mark.parametrize("ta,tb,epis", [(False, False, (P.EPI_BIAS, P.EPI_BIAS_RESID, P.EPI_BIAS_GELU, P.EPI_BIAS_GELU_GRAD)),
+                                        (False, True, (P.EPI_NONE, P.EPI_DGELU, P.EPI_MUL)),
                                         (True, False, (P.EPI_ACCUM_F32,))])
 def test_gemm_bf16_split_k(ctx, ta, tb, epis):
     """Skinny products are cut along K into fp32 partials that a second kernel adds in a fixed
@@ -194,8 +199,8 @@ def test_gemm_bf16_largest_workload_shapes_sampled(ctx):
         return t.float().cpu().numpy().astype(np.float64)
 
     cases = [("F qkv", False, False, T, 3 * h, h, P.EPI_BIAS), ("F proj", False, False, T, h, h, P.EPI_BIAS_RESID),
-             ("F fc1", False, False, T, f, h, P.EPI_BIAS_GELU), ("F fc2", False, False, T, h, f, P.EPI_BIAS_RESID),
-             ("B dfc2", False, True, T, f, h, P.EPI_DGELU), ("B dfc1", False, True, T, h, f, P.EPI_NONE),
+             ("F fc1", False, False, T, f, h, P.EPI_BIAS_GELU_GRAD), ("F fc2", False, False, T, h, f, P.EPI_BIAS_RESID),
+             ("B dfc2", False, True, T, f, h, P.EPI_MUL), ("B dfc1", False, True, T, h, f, P.EPI_NONE),
              ("B dproj", False, True, T, h, h, P.EPI_NONE), ("B dqkv", False, True, T, h, 3 * h, P.EPI_NONE),
              ("W fc2", True, False, f, h, T, P.EPI_ACCUM_F32), ("W fc1", True, False, h, f, T, P.EPI_ACCUM_F32),
              ("W proj", True, False, h, h, T, P.EPI_ACCUM_F32), ("W qkv", True, False, h, 3 * h, T, P.EPI_ACCUM_F32)]
@@ -207,8 +212,8 @@ def test_gemm_bf16_largest_workload_shapes_sampled(ctx):
         c = (torch.randn((M, N), device="cuda", generator=gen) if epi == P.EPI_ACCUM_F32
              else torch.zeros((M, N), device="cuda", dtype=bf))
         c0 = c.clone() if epi == P.EPI_ACCUM_F32 else None
-        aux = extra.clone() if epi == P.EPI_DGELU else (torch.zeros_like(extra) if epi == P.EPI_BIAS_GELU else None)
-        P.pmc_gemm(ctx, a, b, c, ta, tb, epi, bias if epi in (P.EPI_BIAS, P.EPI_BIAS_RESID, P.EPI_BIAS_GELU) else None,
+        aux = extra.clone() if epi == P.EPI_MUL else (torch.zeros_like(extra) if epi == P.EPI_BIAS_GELU_GRAD else None)
+        P.pmc_gemm(ctx, a, b, c, ta, tb, epi, bias if epi in (P.EPI_BIAS, P.EPI_BIAS_RESID, P.EPI_BIAS_GELU_GRAD) else None,
                    extra if epi == P.EPI_BIAS_RESID else None, aux)
         torch.cuda.synchronize()
         ms = np.unique(np.concatenate([rng.integers(0, M, 46), [0, M - 1]]))
@@ -218,17 +223,18 @@ def test_gemm_bf16_largest_workload_shapes_sampled(ctx):
         B = f64(b[ni]).T if tb else f64(b[:, ni])                 # [K, len(ns)]
         ref = A @ B
         sub = lambda t: f64(t[mi][:, ni])
-        if epi in (P.EPI_BIAS, P.EPI_BIAS_RESID, P.EPI_BIAS_GELU):
+        if epi in (P.EPI_BIAS, P.EPI_BIAS_RESID, P.EPI_BIAS_GELU_GRAD):
             ref = ref + f64(bias[ni])
         if epi == P.EPI_BIAS_RESID:
             ref = ref + sub(extra)
-        if epi == P.EPI_DGELU:
-            ref = ref * OL.gelu_grad(sub(extra))
+        if epi == P.EPI_MUL:
+            ref = ref * sub(extra)
         if epi == P.EPI_ACCUM_F32:
             ref = ref + sub(c0)
-        assert rel_l2(sub(c), ref) <= tol("bf16"), (name, rel_l2(sub(c), ref))
-        if epi == P.EPI_BIAS_GELU:
+        if epi == P.EPI_BIAS_GELU_GRAD:
             assert rel_l2(sub(aux), OL.gelu(ref)) <= tol("bf16"), name
+            ref = OL.gelu_grad(ref)
+        assert rel_l2(sub(c), ref) <= tol("bf16"), (name, rel_l2(sub(c), ref))
         del a, b, c, c0, aux, extra
 
 

@@ -47,6 +47,7 @@ struct GemmParams {
   bf16_t* aux;
   int M, N, K, lda, ldb, ldc;
   int tiles_m, tiles_n;
+  int group_m;            // height, in tiles, of the column groups the tiles are walked in (see tile_of_pid)
   int k_tiles_per_split;  // fast path: 64-wide K tiles each blockIdx.y handles (all of K when not split)
   // Segmented contraction (weight gradients of several queued microbatches in one product): the K
   // axis is the concatenation of nseg pieces of seg_tiles 64-wide tiles each, piece i living at
@@ -384,12 +385,16 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmParams p, const 
 }
 
 // Workgroup id -> (tile_m, tile_n).  Ids are dealt round-robin over 8 XCDs; give each XCD a
-// contiguous run of tile indices, then walk tiles in column groups 8 tiles of M tall.
+// contiguous run of tile indices, then walk tiles in column groups group_m tiles of M tall.  The 32
+// tiles an XCD works on at a time are then a block of group_m x 32/group_m tiles, whose operand
+// panels (group_m BM rows of A, 32/group_m BN rows of B per K step) are what that XCD's L2 has to
+// fetch.  Measured on whole steps: 4 for the 256-row tiles (+1 % at hidden 4096 over 8, nothing at
+// 5120), 8 for the smaller ones (4 costs the 64 x 128 products 2 %).  PMC_GEMM_GROUP forces a height.
 __device__ __forceinline__ void tile_of_pid(const GemmParams& p, int pid, int& tile_m, int& tile_n) {
   const int ntiles = p.tiles_m * p.tiles_n;
   const int xcd = pid & 7, local = pid >> 3, lo = ntiles >> 3, rem = ntiles & 7;
   pid = xcd * lo + (xcd < rem ? xcd : rem) + local;
-  constexpr int GROUP = 8;
+  const int GROUP = p.group_m;
   const int per_group = GROUP * p.tiles_n;
   const int group = pid / per_group;
   const int first_m = group * GROUP;
@@ -721,6 +726,7 @@ int launch(hipStream_t st, GemmParams p) {
   }
   p.tiles_m = (p.M + BM - 1) / BM;
   p.tiles_n = (p.N + BN - 1) / BN;
+  p.group_m = 8;
   kern<<<dim3(p.tiles_m * p.tiles_n), dim3(NT), lds, st>>>(p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(PMC_ERR_HIP, "gemm_bf16 launch failed: %s", hipGetErrorString(e));
@@ -761,6 +767,10 @@ int launch_dma(hipStream_t st, GemmParams p) {
   }
   p.tiles_m = (p.M + BM - 1) / BM;
   p.tiles_n = (p.N + BN - 1) / BN;
+  {
+    static const int forced = [] { const char* f = std::getenv("PMC_GEMM_GROUP"); return f ? std::atoi(f) : 0; }();
+    p.group_m = forced > 0 ? forced : (BM >= 256 ? 4 : 8);
+  }
   const int splits = (p.K / 64) / p.k_tiles_per_split;
   kern<<<dim3(p.tiles_m * p.tiles_n, splits), dim3(NT), lds, st>>>(p);
   hipError_t e = hipGetLastError();
@@ -833,6 +843,7 @@ int launch_wgrad_persistent(hipStream_t st, GemmParams p) {
   }
   p.tiles_m = (p.M + 255) / 256;
   p.tiles_n = (p.N + 255) / 256;
+  p.group_m = 8;
   const int ntiles = p.tiles_m * p.tiles_n;
   int grid = ntiles < units ? ntiles : units;
   if (grid >= 8) grid &= ~7;  // whole rounds over the 8 XCDs keep a workgroup's tiles on one XCD
@@ -936,6 +947,7 @@ int gemm_bf16(hipStream_t st, const GemmArgs& a) {
   p.bias = (const bf16_t*)a.bias; p.resid = (const bf16_t*)a.resid; p.aux = (bf16_t*)a.aux;
   p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldb = a.ldb; p.ldc = a.ldc;
   p.tiles_m = p.tiles_n = 0;
+  p.group_m = 8;
   p.k_tiles_per_split = 0;
   p.nseg = p.seg_tiles = 0;
   for (int i = 0; i < kMaxSegments; ++i) p.Aseg[i] = p.Bseg[i] = nullptr;
@@ -976,6 +988,7 @@ int gemm_bf16_grouped_wgrad(hipStream_t st, const GroupedWgradArgs& a) {
   p.bias = p.resid = nullptr; p.aux = nullptr;
   p.M = a.M; p.N = a.N; p.K = a.K * a.count; p.lda = a.lda; p.ldb = a.ldb; p.ldc = a.ldc;
   p.tiles_m = p.tiles_n = 0;
+  p.group_m = 8;
   p.k_tiles_per_split = p.K / 64;
   p.nseg = a.count;
   p.seg_tiles = a.K / 64;

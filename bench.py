@@ -196,8 +196,8 @@ def main() -> int:
         return 2 * (m * k + k * n) + 2 * m * n + extra
 
     roofline = {"bound": "mfma",
-                "kernel": "gemm_bf16_dma_kernel, with splitk_reduce_kernel where K is split "
-                          "(every product of a step: 4 projections x F,B,W x layers)",
+                "kernel": "gemm_bf16_dma_kernel / gemm_bf16_wgrad_persistent_kernel, with splitk_reduce_kernel "
+                          "where K is split (every product of a step: 4 projections x F,B,W x layers)",
                 "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": stored_traffic(name),
                 "avg_launch_us": round(1e3 * gemm_ms / len(gemms), 2), "flop_per_launch": gemm_flop / len(gemms),

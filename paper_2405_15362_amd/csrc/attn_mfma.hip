@@ -32,21 +32,39 @@ constexpr float kLn2 = 0.6931471805599453f;
 typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
+// LDS tiles are [rows][DH] bf16 without padding, filled by direct-to-LDS loads (one wave instruction
+// writes 1 KB, lane l the bytes 16 l .. 16 l + 15 of it) and XOR-swizzled in 16-byte chunks: chunk c
+// of row r sits at position c ^ swz(r).  swz is chosen so that both read patterns are free of bank
+// conflicts: 16 consecutive rows at one chunk fall into 16 different 16-byte bank groups (operand
+// fragments along the rows), and the four rows a transposing read touches fall into the four 64-byte
+// quarters of the banks.
+template <int DH>
+__device__ __forceinline__ int swz(int row) {
+  return DH == 128 ? (((row & 3) << 2) | ((row >> 2) & 3))           // 16 chunks per 256-byte row
+                   : ((((row >> 1) & 1) << 2) | ((row >> 2) & 3));   // 8 chunks per 128-byte row, two rows per bank pass
+}
+
 // Fragment with the contraction index contiguous in the LDS row: lane l gets row row0 + l%32,
 // contraction indices k0 + 8*(l/32) .. +7.
-__device__ __forceinline__ bf16x8 frag_rows(const bf16_t* tile, int pitch, int row0, int k0, int lane) {
-  return *reinterpret_cast<const bf16x8*>(tile + (row0 + (lane & 31)) * pitch + k0 + 8 * (lane >> 5));
+template <int DH>
+__device__ __forceinline__ bf16x8 frag_rows(const bf16_t* tile, int row0, int k0, int lane) {
+  const int row = row0 + (lane & 31), c = (k0 >> 3) + (lane >> 5);
+  return *reinterpret_cast<const bf16x8*>(tile + row * DH + ((c ^ swz<DH>(row)) << 3));
 }
 
 // Fragment of the TRANSPOSE of an LDS tile: lane l gets tile column col0 + l%32 and, as its 8
 // contraction entries, tile rows  krow0 + 4*(l/32) + {0,1,2,3}  and  krow0 + 8 + 4*(l/32) + {0,1,2,3}.
 // That row order is exactly the one in which a lane holds a 32x32 accumulator tile's registers
 // 8t .. 8t+7 (rows 8*(r/4) + 4*(l/32) + r%4), so accumulators can be fed back as the other operand.
-__device__ __forceinline__ bf16x8 frag_cols(const bf16_t* tile, int pitch, int col0, int krow0, int lane) {
+template <int DH>
+__device__ __forceinline__ bf16x8 frag_cols(const bf16_t* tile, int col0, int krow0, int lane) {
   const int g = lane >> 4, j = lane & 15;
-  const bf16_t* p = tile + (krow0 + 4 * (g >> 1) + (j >> 2)) * pitch + col0 + 16 * (g & 1) + 4 * (j & 3);
+  const int row = krow0 + 4 * (g >> 1) + (j >> 2), col = col0 + 16 * (g & 1) + 4 * (j & 3);
+  const int c = col >> 3, within = col & 7;
+  const bf16_t* p = tile + row * DH + ((c ^ swz<DH>(row)) << 3) + within;
+  const bf16_t* q = tile + (row + 8) * DH + ((c ^ swz<DH>(row + 8)) << 3) + within;
   const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 8 * pitch));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(q));
   const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
   return __builtin_bit_cast(bf16x8, v);
 }
@@ -59,33 +77,54 @@ __device__ __forceinline__ bf16x8 acc_to_frag(const f32x16& a, int t) {
   return v;
 }
 
-// Cooperative copy of a [ROWS][DH] block of rows row0.. (pitch ld in global memory) into registers
-// and from there into an LDS tile of pitch P.  Rows >= row_limit are clamped to the last valid
-// row (no branches around the loads); whatever they contribute is masked by the caller.
-template <int ROWS, int DH, int P, int NT>
-struct BlockStager {
-  static constexpr int CHUNKS = ROWS * DH / 8;          // 16-byte chunks in the block
-  static constexpr int CH = (CHUNKS + NT - 1) / NT;     // per thread (threads past the end idle)
-  static_assert(CHUNKS % NT == 0 || CHUNKS < NT, "block must split evenly over the threads");
-  u32x4 r[CH];
-  __device__ __forceinline__ void load(const bf16_t* __restrict__ base, size_t ld, int row0, int row_limit, int tid) {
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+
+// Raw buffer descriptor with a 2 GB window at ptr (every offset used stays below that: checked on the host).
+__device__ __forceinline__ i32x4 make_rsrc(const void* ptr) {
+  const uint64_t a = (uint64_t)ptr;
+  i32x4 r = {(int)(uint32_t)a, (int)(uint32_t)(a >> 32), 0x7fffffff, 0x00020000};
+  return r;
+}
+
+// Cooperative direct-to-LDS copy of a [ROWS][DH] block of rows (row pitch ld elements in global
+// memory) by the NT threads of the workgroup: the data never passes through registers.  Rows past
+// the last one are clamped to it, so every access stays inside the tensor; what those rows
+// contribute is masked by the caller.  The loads are inline assembly: the caller waits for them
+// with s_waitcnt vmcnt(0) before the barrier that publishes the tile.
+template <int ROWS, int DH, int NT>
+struct BlockDma {
+  static constexpr int CPR = DH / 8;                 // chunks per row
+  static constexpr int RPI = 64 / CPR;               // rows per wave instruction
+  static constexpr int NI = ROWS / RPI;              // wave instructions per block
+  static constexpr int NW = NT / 64;
+  static constexpr int PER = (NI + NW - 1) / NW;     // per wave (the last waves idle if NI % NW)
+  static_assert(ROWS % RPI == 0, "block must be whole wave instructions");
+  int row_in_block[PER];
+  uint32_t col_bytes[PER];
+  __device__ __forceinline__ void init(int wave, int lane) {
 #pragma unroll
-    for (int i = 0; i < CH; ++i) {
-      const int c = tid + i * NT, row = c / (DH / 8), cc = (c % (DH / 8)) * 8;
-      if (CHUNKS < NT && c >= CHUNKS) continue;
-      const int gr = min(row0 + row, row_limit - 1);
-      r[i] = *reinterpret_cast<const u32x4*>(base + (size_t)gr * ld + cc);
+    for (int i = 0; i < PER; ++i) {
+      const int q = wave + i * NW, row = q * RPI + lane / CPR, pos = lane % CPR;
+      row_in_block[i] = row;
+      col_bytes[i] = (uint32_t)((pos ^ swz<DH>(row)) << 4);
     }
   }
-  __device__ __forceinline__ void store(bf16_t* tile, int tid) const {
+  // row0: first row of the block; last_row: the last valid row; ld_bytes: row pitch in bytes
+  __device__ __forceinline__ void issue(i32x4 rsrc, bf16_t* tile, uint32_t ld_bytes, int row0, int last_row, int wave) const {
 #pragma unroll
-    for (int i = 0; i < CH; ++i) {
-      const int c = tid + i * NT, row = c / (DH / 8), cc = (c % (DH / 8)) * 8;
-      if (CHUNKS < NT && c >= CHUNKS) continue;
-      *reinterpret_cast<u32x4*>(tile + row * P + cc) = r[i];
+    for (int i = 0; i < PER; ++i) {
+      const int q = wave + i * NW;
+      if (NI % NW != 0 && q >= NI) break;
+      const uint32_t voff = (uint32_t)min(row0 + row_in_block[i], last_row) * ld_bytes + col_bytes[i];
+      const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)((lds_void_ptr)(tile + q * 512)));
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                   :: "s"(lds_addr), "v"(voff), "s"(rsrc) : "memory");
     }
   }
 };
+
+constexpr int kWaitAllLoads = 0x0F70;  // s_waitcnt vmcnt(0)
 
 __device__ __forceinline__ void zero(f32x16& a) {
 #pragma unroll
@@ -102,10 +141,6 @@ __device__ __forceinline__ void store_tile_t(bf16_t* row_ptr, const f32x16& a, f
   }
 }
 
-constexpr int PAD_ROWS = 8;    // tile read only with frag_rows: pitch DH + 8
-constexpr int PAD_COLS = 32;   // tile read only with frag_cols: pitch DH + 32
-constexpr int PAD_BOTH = 40;   // tile read both ways: pitch DH + 40
-
 // Forward.  The workgroup is a QW x KW grid of waves: wave (qg, kg) owns queries 32 qg .. 32 qg + 31
 // of the workgroup's 32 QW queries and, of every streamed block of 32 NKT KW keys, the 32 NKT keys
 // starting at 32 NKT kg.
@@ -118,10 +153,9 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_fwd_m
                                                                bf16_t* __restrict__ o, float* __restrict__ lse,
                                                                float scale_log2) {
   constexpr int NT = QW * KW * 64, BQW = 32 * QW, WK = 32 * NKT, BSW = WK * KW;
-  constexpr int KP = DH + PAD_ROWS, VP = DH + PAD_COLS;
-  constexpr int KT = BSW * KP, VT = BSW * VP;
-  extern __shared__ __attribute__((aligned(16))) bf16_t smem[];  // [2][K tile | V tile]
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hl = lane >> 5;
+  constexpr int KT = BSW * DH, VT = BSW * DH;
+  extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];  // [2][K tile | V tile]
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hl = lane >> 5;
   const int qg = wave % QW, kg = wave / QW;
   // grid = (heads * batch, query blocks); under a causal mask late query blocks see the most keys,
   // so they are dealt out first and the short ones fill the tail
@@ -143,12 +177,13 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_fwd_m
 
   const int kend = causal ? min(seq, q0 + BQW) : seq;
   const int nblk = (kend + BSW - 1) / BSW;
-  BlockStager<BSW, DH, KP, NT> sk;
-  BlockStager<BSW, DH, VP, NT> sv;
-  sk.load(base + h, ld, 0, seq, tid);
-  sv.load(base + 2 * h, ld, 0, seq, tid);
-  sk.store(smem, tid);
-  sv.store(smem + KT, tid);
+  const i32x4 rk = make_rsrc(base + h), rv = make_rsrc(base + 2 * h);
+  const uint32_t ldb = (uint32_t)ld * 2;
+  BlockDma<BSW, DH, NT> dma;
+  dma.init(wave, lane);
+  dma.issue(rk, smem, ldb, 0, seq - 1, wave);
+  dma.issue(rv, smem + KT, ldb, 0, seq - 1, wave);
+  __builtin_amdgcn_s_waitcnt(kWaitAllLoads);
   __syncthreads();
   // The query fragments must have arrived before the loop: left pending, the compiler's wait for
   // them inside the loop would also cover the loads that prefetch the next block.
@@ -158,9 +193,10 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_fwd_m
     const int k0 = blk * BSW + WK * kg;  // this wave's 32 NKT keys
     const bf16_t* kt_ = smem + (blk & 1) * (KT + VT);
     const bf16_t* vt_ = kt_ + KT;
-    if (blk + 1 < nblk) {
-      sk.load(base + h, ld, (blk + 1) * BSW, seq, tid);
-      sv.load(base + 2 * h, ld, (blk + 1) * BSW, seq, tid);
+    if (blk + 1 < nblk) {  // the other stage: every wave left it at the last barrier
+      bf16_t* nxt = smem + ((blk + 1) & 1) * (KT + VT);
+      dma.issue(rk, nxt, ldb, (blk + 1) * BSW, seq - 1, wave);
+      dma.issue(rv, nxt + KT, ldb, (blk + 1) * BSW, seq - 1, wave);
     }
     if (k0 < seq && (!causal || k0 <= qw0 + 31)) {
       // The K fragments of a 32-key tile are requested together, and those of the next tile each
@@ -169,7 +205,7 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_fwd_m
       f32x16 s[NKT];
       bf16x8 kf[DH / 16];
 #pragma unroll
-      for (int ks = 0; ks < DH / 16; ++ks) kf[ks] = frag_rows(kt_, KP, WK * kg, 16 * ks, lane);
+      for (int ks = 0; ks < DH / 16; ++ks) kf[ks] = frag_rows<DH>(kt_, WK * kg, 16 * ks, lane);
       __builtin_amdgcn_sched_barrier(0);  // the compiler would sink the reads to their uses again
 #pragma unroll
       for (int kt = 0; kt < NKT; ++kt) {
@@ -177,13 +213,13 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_fwd_m
 #pragma unroll
         for (int ks = 0; ks < DH / 16; ++ks) {
           s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], s[kt], 0, 0, 0);
-          if (kt + 1 < NKT) kf[ks] = frag_rows(kt_, KP, WK * kg + 32 * (kt + 1), 16 * ks, lane);
+          if (kt + 1 < NKT) kf[ks] = frag_rows<DH>(kt_, WK * kg + 32 * (kt + 1), 16 * ks, lane);
           __builtin_amdgcn_sched_barrier(0);
         }
       }
       bf16x8 vf[2][DH / 32];
 #pragma unroll
-      for (int dt = 0; dt < DH / 32; ++dt) vf[0][dt] = frag_cols(vt_, VP, 32 * dt, WK * kg, lane);
+      for (int dt = 0; dt < DH / 32; ++dt) vf[0][dt] = frag_cols<DH>(vt_, 32 * dt, WK * kg, lane);
       __builtin_amdgcn_sched_barrier(0);
       // only blocks that cross the diagonal of this wave's rows or the end of the sequence need masks
       if ((causal && k0 + WK - 1 > qw0) || (k0 + WK > seq)) {
@@ -227,7 +263,7 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_fwd_m
       for (int g = 0; g < 2 * NKT; ++g) {  // 16 keys at a time: tile g / 2, half g % 2
         if (g + 1 < 2 * NKT) {
 #pragma unroll
-          for (int dt = 0; dt < DH / 32; ++dt) vf[(g + 1) & 1][dt] = frag_cols(vt_, VP, 32 * dt, WK * kg + 16 * (g + 1), lane);
+          for (int dt = 0; dt < DH / 32; ++dt) vf[(g + 1) & 1][dt] = frag_cols<DH>(vt_, 32 * dt, WK * kg + 16 * (g + 1), lane);
         }
         const bf16x8 pb = acc_to_frag(s[g >> 1], g & 1);
 #pragma unroll
@@ -235,11 +271,7 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_fwd_m
           oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[g & 1][dt], pb, oacc[dt], 0, 0, 0);
       }
     }
-    if (blk + 1 < nblk) {
-      bf16_t* nxt = smem + ((blk + 1) & 1) * (KT + VT);
-      sk.store(nxt, tid);
-      sv.store(nxt + KT, tid);
-    }
+    __builtin_amdgcn_s_waitcnt(kWaitAllLoads);  // this wave's part of the next block has landed
     __syncthreads();
   }
   if (KW > 1) {
@@ -293,10 +325,9 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_bwd_d
     const float* __restrict__ lse, const bf16_t* __restrict__ d_o, bf16_t* __restrict__ dq, float* __restrict__ delta,
     float scale, float scale_log2) {
   constexpr int NT = QW * KW * 64, BQW = 32 * QW, WK = 32 * NKT, BSW = WK * KW;
-  constexpr int KP = DH + PAD_BOTH, VP = DH + PAD_ROWS;
-  constexpr int KT = BSW * KP, VT = BSW * VP;
-  extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hl = lane >> 5;
+  constexpr int KT = BSW * DH, VT = BSW * DH;
+  extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hl = lane >> 5;
   const int qg = wave % QW, kg = wave / QW;
   // grid = (heads * batch, query blocks); under a causal mask late query blocks see the most keys,
   // so they are dealt out first and the short ones fill the tail
@@ -330,19 +361,21 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_bwd_d
 
   const int kend = causal ? min(seq, q0 + BQW) : seq;
   const int nblk = (kend + BSW - 1) / BSW;
-  BlockStager<BSW, DH, KP, NT> sk;
-  BlockStager<BSW, DH, VP, NT> sv;
-  sk.load(base + h, ld, 0, seq, tid);
-  sv.load(base + 2 * h, ld, 0, seq, tid);
-  sk.store(smem, tid);
-  sv.store(smem + KT, tid);
+  const i32x4 rk = make_rsrc(base + h), rv = make_rsrc(base + 2 * h);
+  const uint32_t ldb = (uint32_t)ld * 2;
+  BlockDma<BSW, DH, NT> dma;
+  dma.init(wave, lane);
+  dma.issue(rk, smem, ldb, 0, seq - 1, wave);
+  dma.issue(rv, smem + KT, ldb, 0, seq - 1, wave);
+  __builtin_amdgcn_s_waitcnt(kWaitAllLoads);
   __syncthreads();
   for (int blk = 0; blk < nblk; ++blk) {
     const bf16_t* kt_ = smem + (blk & 1) * (KT + VT);
     const bf16_t* vt_ = kt_ + KT;
     if (blk + 1 < nblk) {
-      sk.load(base + h, ld, (blk + 1) * BSW, seq, tid);
-      sv.load(base + 2 * h, ld, (blk + 1) * BSW, seq, tid);
+      bf16_t* nxt = smem + ((blk + 1) & 1) * (KT + VT);
+      dma.issue(rk, nxt, ldb, (blk + 1) * BSW, seq - 1, wave);
+      dma.issue(rv, nxt + KT, ldb, (blk + 1) * BSW, seq - 1, wave);
     }
 #pragma unroll
     for (int kt = 0; kt < NKT; ++kt) {
@@ -354,8 +387,8 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_bwd_d
       zero(dp);
 #pragma unroll
       for (int ks = 0; ks < DH / 16; ++ks) {
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(kt_, KP, trow, 16 * ks, lane), qf[ks], s, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(vt_, VP, trow, 16 * ks, lane), dof[ks], dp, 0, 0, 0);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(kt_, trow, 16 * ks, lane), qf[ks], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(vt_, trow, 16 * ks, lane), dof[ks], dp, 0, 0, 0);
       }
       if ((causal && k0 + 31 > qw0) || (k0 + 32 > seq)) {
 #pragma unroll
@@ -374,15 +407,11 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_bwd_d
         const bf16x8 dsb = acc_to_frag(s, t);
 #pragma unroll
         for (int dt = 0; dt < DH / 32; ++dt)
-          acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(kt_, KP, 32 * dt, trow + 16 * t, lane), dsb, acc[dt],
+          acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<DH>(kt_, 32 * dt, trow + 16 * t, lane), dsb, acc[dt],
                                                             0, 0, 0);
       }
     }
-    if (blk + 1 < nblk) {
-      bf16_t* nxt = smem + ((blk + 1) & 1) * (KT + VT);
-      sk.store(nxt, tid);
-      sv.store(nxt + KT, tid);
-    }
+    __builtin_amdgcn_s_waitcnt(kWaitAllLoads);
     __syncthreads();
   }
   if (KW > 1) {
@@ -428,12 +457,11 @@ __global__ __launch_bounds__(KG * QG * 128, KG * QG == 2 ? 3 : 1) void attn_bwd_
     int seq, int heads, int causal, const bf16_t* qkv, const float* __restrict__ lse, const float* __restrict__ delta,
     const bf16_t* __restrict__ d_o, bf16_t* dqkv, float scale, float scale_log2) {
   constexpr int NP = KG * QG, NT = NP * 128, BK = 32 * KG, BSQ = 32 * QG;
-  constexpr int QP = DH + PAD_BOTH;
-  constexpr int QT = BSQ * QP;
-  extern __shared__ __attribute__((aligned(16))) bf16_t smem[];  // [2][Q tile | dO tile], stats, P exchange
+  constexpr int QT = BSQ * DH;
+  extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];  // [2][Q tile | dO tile], stats, P exchange
   float* stats = reinterpret_cast<float*>(smem + 4 * QT);       // [2][lse2[BSQ] | delta[BSQ]]
   float* xch = stats + 4 * BSQ;                                  // [NP][16 registers][64 lanes]
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hl = lane >> 5;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hl = lane >> 5;
   const int role = wave / NP, pair = wave % NP, kg = pair % KG, qg = pair / KG;
   // grid = (heads * batch, key blocks): early key blocks see the most queries and go first
   const int h = heads * DH, head = blockIdx.x % heads, b = blockIdx.x / heads;
@@ -455,7 +483,10 @@ __global__ __launch_bounds__(KG * QG * 128, KG * QG == 2 ? 3 : 1) void attn_bwd_
   for (int dt = 0; dt < DH / 32; ++dt) zero(acc[dt]);
   const int qstart = causal ? (k0 / BSQ) * BSQ : 0;
   const int nblk = (seq - qstart + BSQ - 1) / BSQ;
-  BlockStager<BSQ, DH, QP, NT> sq, sdo;
+  const i32x4 rq = make_rsrc(base), rdo = make_rsrc(dob);
+  const uint32_t ldb = (uint32_t)ld * 2, hb = (uint32_t)h * 2;
+  BlockDma<BSQ, DH, NT> dma;
+  dma.init(wave, lane);
   float st_reg = 0.f;  // threads 0..BSQ-1: lse2 of query tid; BSQ..2 BSQ-1: delta of query tid-BSQ
   auto load_stats = [&](int q0) {
     if (tid < 2 * BSQ) {
@@ -463,12 +494,11 @@ __global__ __launch_bounds__(KG * QG * 128, KG * QG == 2 ? 3 : 1) void attn_bwd_
       st_reg = qi < seq ? (tid < BSQ ? lse_b[qi] * kLog2e : delta_b[qi]) : 0.f;
     }
   };
-  sq.load(base, ld, qstart, seq, tid);
-  sdo.load(dob, (size_t)h, qstart, seq, tid);
+  dma.issue(rq, smem, ldb, qstart, seq - 1, wave);
+  dma.issue(rdo, smem + QT, hb, qstart, seq - 1, wave);
   load_stats(qstart);
-  sq.store(smem, tid);
-  sdo.store(smem + QT, tid);
   if (tid < 2 * BSQ) stats[tid] = st_reg;
+  __builtin_amdgcn_s_waitcnt(kWaitAllLoads);
   __syncthreads();
   float* my_xch = xch + pair * (16 * 64) + lane;
   for (int blk = 0; blk < nblk; ++blk) {
@@ -479,9 +509,10 @@ __global__ __launch_bounds__(KG * QG * 128, KG * QG == 2 ? 3 : 1) void attn_bwd_
     const bf16_t* first = role ? dot_ : qt_;    // role 0: S = Q K^T        role 1: dP = dO V^T
     const bf16_t* second = role ? qt_ : dot_;   // role 0: dV^T += dO^T P   role 1: dK^T += Q^T dS
     const float* st_ = stats + (blk & 1) * 2 * BSQ + (role ? BSQ : 0) + trow;  // lse2 (role 0) or delta (role 1)
-    if (blk + 1 < nblk) {
-      sq.load(base, ld, qstart + (blk + 1) * BSQ, seq, tid);
-      sdo.load(dob, (size_t)h, qstart + (blk + 1) * BSQ, seq, tid);
+    if (blk + 1 < nblk) {  // the other stage: every wave left it at the last barrier
+      bf16_t* nxt = smem + ((blk + 1) & 1) * 2 * QT;
+      dma.issue(rq, nxt, ldb, qstart + (blk + 1) * BSQ, seq - 1, wave);
+      dma.issue(rdo, nxt + QT, hb, qstart + (blk + 1) * BSQ, seq - 1, wave);
       load_stats(qstart + (blk + 1) * BSQ);
     }
     const bool active = q0 < seq && (!causal || q0 + 31 >= kw0);  // the same for both waves of a pair
@@ -490,7 +521,7 @@ __global__ __launch_bounds__(KG * QG * 128, KG * QG == 2 ? 3 : 1) void attn_bwd_
       zero(t);
 #pragma unroll
       for (int ks = 0; ks < DH / 16; ++ks)
-        t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(first, QP, trow, 16 * ks, lane), kvf[ks], t, 0, 0, 0);
+        t = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows<DH>(first, trow, 16 * ks, lane), kvf[ks], t, 0, 0, 0);
       if (role == 0) {
         if ((causal && q0 < kw0 + 31) || (q0 + 32 > seq) || (kw0 + 32 > seq)) {
 #pragma unroll
@@ -525,16 +556,12 @@ __global__ __launch_bounds__(KG * QG * 128, KG * QG == 2 ? 3 : 1) void attn_bwd_
         const bf16x8 fb = acc_to_frag(t, tt);
 #pragma unroll
         for (int dt = 0; dt < DH / 32; ++dt)
-          acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(second, QP, 32 * dt, trow + 16 * tt, lane), fb,
+          acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols<DH>(second, 32 * dt, trow + 16 * tt, lane), fb,
                                                             acc[dt], 0, 0, 0);
       }
     }
-    if (blk + 1 < nblk) {
-      bf16_t* nxt = smem + ((blk + 1) & 1) * 2 * QT;
-      sq.store(nxt, tid);
-      sdo.store(nxt + QT, tid);
-      if (tid < 2 * BSQ) stats[((blk + 1) & 1) * 2 * BSQ + tid] = st_reg;
-    }
+    if (blk + 1 < nblk && tid < 2 * BSQ) stats[((blk + 1) & 1) * 2 * BSQ + tid] = st_reg;
+    __builtin_amdgcn_s_waitcnt(kWaitAllLoads);
     __syncthreads();  // next tiles staged; the exchange slots may be rewritten
   }
   // Merge the query groups, one after the other so that one set of slots is enough:
@@ -579,7 +606,7 @@ int reserve_lds(K kern, size_t bytes, bool& done, const char* what) {
 
 template <int DH, int QW, int KW, int NKT>
 int fwd_launch(hipStream_t st, int batch, int seq, int heads, int causal, const void* qkv, void* o, float* lse) {
-  constexpr size_t lds = 2 * sizeof(bf16_t) * 32 * NKT * KW * ((DH + PAD_ROWS) + (DH + PAD_COLS));
+  constexpr size_t lds = 2 * sizeof(bf16_t) * 32 * NKT * KW * 2 * DH;
   static bool done = false;
   if (int rc = reserve_lds(attn_fwd_mfma<DH, QW, KW, NKT>, lds, done, "attention_forward")) return rc;
   const float scale_log2 = kLog2e / sqrtf((float)DH);
@@ -610,9 +637,9 @@ int fwd_t(hipStream_t st, int batch, int seq, int heads, int causal, const void*
 template <int DH, int QW, int KW, int NKT, int KG, int QG>
 int bwd_launch(hipStream_t st, int batch, int seq, int heads, int causal, const void* qkv, const void* o, const float* lse,
                const void* d_o, void* dqkv, void* dq_stage, float* delta) {
-  constexpr size_t lds_dq = 2 * sizeof(bf16_t) * 32 * NKT * KW * ((DH + PAD_BOTH) + (DH + PAD_ROWS));
+  constexpr size_t lds_dq = 2 * sizeof(bf16_t) * 32 * NKT * KW * 2 * DH;
   constexpr size_t tiles_dkv =
-      4 * sizeof(bf16_t) * 32 * QG * (DH + PAD_BOTH) + (4 * 32 * QG + (size_t)KG * QG * 16 * 64) * sizeof(float);
+      4 * sizeof(bf16_t) * 32 * QG * DH + (4 * 32 * QG + (size_t)KG * QG * 16 * 64) * sizeof(float);
   constexpr size_t merge_dkv = QG > 1 ? (size_t)2 * KG * (DH / 2) * 64 * sizeof(float) : 0;
   constexpr size_t lds_dkv = tiles_dkv > merge_dkv ? tiles_dkv : merge_dkv;
   static_assert(lds_dq <= 160 * 1024 && lds_dkv <= 160 * 1024, "tiles exceed the LDS of a compute unit");
@@ -644,6 +671,9 @@ int check(const char* what, int batch, int seq, int heads, int dh, const void* q
   if (dh != 64 && dh != 128) return fail(PMC_ERR_INVALID, "%s: matrix-core path needs head size 64 or 128, got %d", what, dh);
   if (seq > 65535 * 32 || (long)heads * batch > 0x7fffffffL) return fail(PMC_ERR_INVALID, "%s: seq or heads*batch exceed the grid limit", what);
   if (reinterpret_cast<uintptr_t>(qkv) & 15) return fail(PMC_ERR_INVALID, "%s: qkv must be 16-byte aligned", what);
+  // the tile loads address one sequence's rows with 32-bit byte offsets inside a 2 GB window
+  if ((size_t)seq * 3 * heads * dh * 2 > 0x7fffffffull)
+    return fail(PMC_ERR_INVALID, "%s: one sequence's q|k|v rows (%d x %d) exceed 2 GB", what, seq, 3 * heads * dh);
   return PMC_OK;
 }
 

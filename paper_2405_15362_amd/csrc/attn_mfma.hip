@@ -28,6 +28,7 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kSlack = 8.0f;  // forward: how far (in log2 units) a score may exceed the softmax reference
 
 typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
 typedef short s16x8 __attribute__((ext_vector_type(8)));
@@ -173,7 +174,7 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_fwd_m
   f32x16 oacc[DH / 32];
 #pragma unroll
   for (int dt = 0; dt < DH / 32; ++dt) zero(oacc[dt]);
-  float m2 = -INFINITY, lsum = 0.f;  // running maximum (in log2 units, scale applied) and sum
+  float m2 = -INFINITY, lsum = 0.f;  // softmax reference (log2 units, scale applied; see below) and sum
 
   const int kend = causal ? min(seq, q0 + BQW) : seq;
   const int nblk = (kend + BSW - 1) / BSW;
@@ -237,8 +238,21 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_fwd_m
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      // m2 is the reference the exponentials are taken against, not necessarily the exact running
+      // maximum: it moves (and what is summed so far is rescaled) only when some query's maximum
+      // has risen by more than kSlack above it, so probabilities stay below 2^kSlack and the
+      // quotient o / lsum and lse = m2 + log2(lsum) are the same as with the exact maximum.
       const float m_new = fmaxf(m2, mx * scale_log2);
-      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+      if (__any(m_new > m2 + kSlack)) {
+        const float alpha = __builtin_amdgcn_exp2f(m2 - ((m_new == -INFINITY) ? 0.f : m_new));
+        lsum *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < DH / 32; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+        m2 = m_new;
+      }
+      const float m_use = (m2 == -INFINITY) ? 0.f : m2;
       float rowsum = 0.f;
 #pragma unroll
       for (int kt = 0; kt < NKT; ++kt)
@@ -249,15 +263,6 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_fwd_m
           rowsum += p;
         }
       rowsum += __shfl_xor(rowsum, 32, 64);
-      if (__any(m_new != m2)) {  // the running maximum moved for some query: rescale what is summed so far
-        const float alpha = __builtin_amdgcn_exp2f(m2 - m_use);
-        lsum *= alpha;
-#pragma unroll
-        for (int dt = 0; dt < DH / 32; ++dt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
-        m2 = m_new;
-      }
       lsum += rowsum;
 #pragma unroll
       for (int g = 0; g < 2 * NKT; ++g) {  // 16 keys at a time: tile g / 2, half g % 2

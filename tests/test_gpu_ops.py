@@ -403,6 +403,82 @@ def test_attention_long_sequence(ctx, monkeypatch, family):
         assert rel_l2(host(dq)[:, cols], dqkv_ref[:, cols]) <= tol("bf16"), name
 
 
+@pytest.mark.parametrize("family", ["0", "1", "2"])
+@pytest.mark.parametrize("dh", [64, 128])
+def test_attention_short_sequences(ctx, monkeypatch, family, dh):
+    """Sequences shorter than one streamed block (a single query, a few, one 32-row tile plus
+    one): every tile row past the end is a clamped copy of the last row and must be masked out."""
+    monkeypatch.setenv("PMC_ATTN_SHAPE", family)
+    batch, heads = 2, 2
+    h = heads * dh
+    for seq in (1, 7, 33):
+        key = ("attn-short", dh, seq)
+        print("attention short case", key, family, flush=True)
+        qkv = mat(key + ("qkv",), (batch * seq, 3 * h), "bf16")
+        d_o = mat(key + ("do",), (batch * seq, h), "bf16")
+        q64 = qkv.astype(np.float64)
+        o_ref, probs, lse_ref = OL.attention(q64, heads, True, batch)
+        dqkv_ref = OL.attention_input_grad(d_o.astype(np.float64), q64, probs, heads, batch)
+        qd = dev(qkv, "bf16")
+        o = dev(np.zeros((batch * seq, h)), "bf16")
+        lse = torch.zeros(batch * heads * seq, device="cuda")
+        P.pmc_attention_forward(ctx, qd, o, lse, batch, seq, heads, dh, True)
+        torch.cuda.synchronize()
+        assert rel_l2(host(o), o_ref) <= tol("bf16"), seq
+        assert np.abs(host(lse) - lse_ref.reshape(-1)).max() <= 2e-2, seq
+        dq = dev(np.zeros_like(qkv), "bf16")
+        P.pmc_attention_backward(ctx, qd, o, lse, dev(d_o, "bf16"), dq, batch, seq, heads, dh, True)
+        torch.cuda.synchronize()
+        for name, cols in (("dq", slice(0, h)), ("dk", slice(h, 2 * h)), ("dv", slice(2 * h, 3 * h))):
+            assert rel_l2(host(dq)[:, cols], dqkv_ref[:, cols]) <= tol("bf16"), (seq, name)
+
+
+@pytest.mark.parametrize("family", ["0", "1"])
+@pytest.mark.parametrize("causal", [True, False])
+def test_attention_sharp_softmax(ctx, monkeypatch, family, causal):
+    """Queries and keys three times larger (scores with a standard deviation of 9, 13 in log2
+    units): row maxima keep rising from block to block by more and by less than the slack the
+    forward kernel allows before it moves its softmax reference, so both branches of the online
+    softmax and their mix inside one wave are exercised."""
+    monkeypatch.setenv("PMC_ATTN_SHAPE", family)
+    batch, seq, heads, dh = 1, 700, 2, 128
+    h = heads * dh
+    key = ("attn-sharp", causal)
+    print("attention sharp case", key, family, flush=True)
+    qkv = mat(key + ("qkv",), (batch * seq, 3 * h), "bf16").copy()
+    qkv[:, :2 * h] *= 3.0
+    d_o = mat(key + ("do",), (batch * seq, h), "bf16")
+    qkv = host(dev(qkv, "bf16"))                             # exactly what the device holds after rounding
+    q64 = qkv.astype(np.float64)
+    o_ref, probs, lse_ref = OL.attention(q64, heads, causal, batch)
+    dqkv_ref = OL.attention_input_grad(d_o.astype(np.float64), q64, probs, heads, batch)
+    qd = dev(qkv, "bf16")
+    o = dev(np.zeros((batch * seq, h)), "bf16")
+    lse = torch.zeros(batch * heads * seq, device="cuda")
+    P.pmc_attention_forward(ctx, qd, o, lse, batch, seq, heads, dh, causal)
+    torch.cuda.synchronize()
+    assert rel_l2(host(o), o_ref) <= tol("bf16")
+    assert np.abs(host(lse) - lse_ref.reshape(-1)).max() <= 2e-2
+    dq = dev(np.zeros_like(qkv), "bf16")
+    P.pmc_attention_backward(ctx, qd, o, lse, dev(d_o, "bf16"), dq, batch, seq, heads, dh, causal)
+    torch.cuda.synchronize()
+    for name, cols in (("dq", slice(0, h)), ("dk", slice(h, 2 * h)), ("dv", slice(2 * h, 3 * h))):
+        assert rel_l2(host(dq)[:, cols], dqkv_ref[:, cols]) <= tol("bf16"), name
+
+
+def test_attention_rejects_rows_beyond_the_load_window(ctx):
+    """The matrix-core kernels address one sequence's q|k|v rows with 32-bit offsets in a 2 GB
+    window: a sequence whose rows exceed it is refused before anything is launched."""
+    seq, heads, dh = 32768, 128, 128                    # 32768 rows of 96 KiB = 3 GiB
+    small = torch.zeros(1024, device="cuda", dtype=torch.bfloat16)
+    lse = torch.zeros(16, device="cuda")
+    with pytest.raises(P.PmcError) as e:
+        P.pmc_attention_forward(ctx, small, small, lse, 1, seq, heads, dh, True)
+    assert "2 GB" in str(e.value)
+    with pytest.raises(P.PmcError):
+        P.pmc_attention_backward(ctx, small, small, lse, small, small, 1, seq, heads, dh, True)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_column_sum(ctx, dtype):
     for rows, n in ((1, 8), (50, 264), (1000, 2048), (300, 6144)):

@@ -296,7 +296,9 @@ int pmc_layernorm_forward(pmc_ctx* ctx, int32_t dtype, int32_t rows, int32_t h, 
 int pmc_layernorm_backward(pmc_ctx* ctx, int32_t dtype, int32_t rows, int32_t h, const void* dy,
                            const void* x, const void* gain, const float* mean, const float* rstd,
                            const void* resid, void* dx, float* dgain, float* dbias);
-/* Fused attention on packed qkv [batch*seq, 3h]: o [batch*seq, h], lse fp32 [batch, heads, seq]. */
+/* Fused attention on packed qkv [batch*seq, 3h]: o [batch*seq, h], lse fp32 [batch, heads, seq].
+ * In bf16 with head size 64 or 128 (the matrix-core kernels) one sequence's rows, seq * 3h * 2
+ * bytes, must stay below 2 GB; larger shapes return PMC_ERR_INVALID (also from pmc_chunk_create). */
 int pmc_attention_forward(pmc_ctx* ctx, int32_t dtype, int32_t batch, int32_t seq, int32_t heads,
                           int32_t head_dim, int32_t causal, const void* qkv, void* o, float* lse);
 /* dqkv (same layout as qkv; may alias qkv) from d_o; uses the workspace. */

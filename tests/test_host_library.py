@@ -115,6 +115,10 @@ def test_bad_cfg_is_rejected():
     assert P.pmc_activation_bytes(P.make_cfg(1, 100, 3, 400, 64)) == 0       # hidden % heads
     assert P.pmc_activation_bytes(P.make_cfg(1, 2048, 4, 8192, 64)) == 0     # head size 512
     assert P.pmc_activation_bytes(P.make_cfg(0, 256, 4, 1024, 64)) == 0
+    # bf16, head size 128: a sequence's q|k|v rows (seq x 3 x hidden x 2 bytes) must stay below 2 GB
+    assert P.pmc_activation_bytes(P.make_cfg(1, 8192, 64, 8192, 43688)) > 0
+    assert P.pmc_activation_bytes(P.make_cfg(1, 8192, 64, 8192, 43696)) == 0
+    assert "2 GB" in P.pmc_last_error()
 
 
 @pytest.mark.parametrize("kind", S.KINDS)

@@ -322,10 +322,14 @@ __device__ __forceinline__ void store_oct(const GemmParams& p, float (&v)[8], in
 // 32 TN + 4 words spreads both the column-quad writes and the row-major reads over all banks.
 // Only the wave itself touches its slab: LDS operations of one wave complete in order, so no
 // barrier is needed between the passes.
-template <int TM, int TN, int EPI>
+// J0, JN: the column tiles J0 .. J0 + JN - 1 of the wave's TN are staged (JN a power of two, so that
+// whole rows divide a wave's 64 lanes); a tile that is 5 wide goes out as 4 + 1.
+template <int TM, int TN, int EPI, int J0 = 0, int JN = TN>
 __device__ __forceinline__ void epilogue_staged(const GemmParams& p, f32x16 (&acc)[TM][TN], float* slab, int mw0,
-                                                int nw0, int lane) {
-  constexpr int WN = 32 * TN, PITCH = WN + 4;
+                                                int nw0_wave, int lane) {
+  static_assert((JN & (JN - 1)) == 0 && JN <= 8 && J0 + JN <= TN, "column group");
+  constexpr int WN = 32 * JN, PITCH = WN + 4;
+  const int nw0 = nw0_wave + 32 * J0;
   constexpr int LPR = WN / 8;     // lanes per row on the way out
   constexpr int RPP = 64 / LPR;   // rows per pass
   constexpr int NPASS = 32 / RPP;
@@ -346,10 +350,10 @@ __device__ __forceinline__ void epilogue_staged(const GemmParams& p, f32x16 (&ac
   for (int i = 0; i < TM; ++i) {
     if (i + 1 < TM) fetch(i + 1, ahead[(i + 1) & 1]);
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
+    for (int j = 0; j < JN; ++j)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        f32x4 t = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+        f32x4 t = {acc[i][J0 + j][4 * q], acc[i][J0 + j][4 * q + 1], acc[i][J0 + j][4 * q + 2], acc[i][J0 + j][4 * q + 3]};
         *reinterpret_cast<f32x4*>(slab + (lane & 31) * PITCH + 32 * j + 8 * q + 4 * (lane >> 5)) = t;
       }
 #pragma unroll
@@ -413,7 +417,7 @@ __device__ __forceinline__ void tile_of_block(const GemmParams& p, int& tile_m, 
 //   contraction-contiguous operand: [rows][64]; chunk position p of row r holds k-chunk
 //       p ^ ((r >> 1) & 7)   -> 16 lanes reading 16 consecutive rows at one k hit 16 distinct
 //       16-byte bank groups;
-//   other operand: [64 k][ROWS]; chunk position p of k-row kr holds chunk p ^ ((kr & 3) << 2)
+//   other operand: [64 k][ROWS]; chunk position p of k-row kr holds chunk p ^ kswz(kr) = p ^ ((kr & 3) << 2)
 //       -> the four k-rows one half-wave touches in a transposing read fall into four different
 //       64-byte bank quarters.
 // One buffer_load...lds instruction of a wave fills 1 KB of LDS (lane l writes bytes 16 l .. 16 l + 15
@@ -421,11 +425,22 @@ __device__ __forceinline__ void tile_of_block(const GemmParams& p, int& tile_m, 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
+// Chunk swizzle of k-row kr in a [64 k][ROWS] tile.  A k-row of 128 n rows (a multiple of 256 bytes)
+// starts in the same bank as its neighbours, so the four k-rows of a transposing read are moved to
+// four different 64-byte quarters by their two low bits.  In a 320-row tile (640 bytes per k-row)
+// consecutive k-rows already sit 128 bytes apart; bit 1 of kr supplies the other 64 bytes, and
+// flipping only bit 2 of the chunk index keeps every chunk inside its own group of 8 (320 / 8 = 40
+// chunks per k-row is not a multiple of 16).
+template <int ROWS>
+__device__ __forceinline__ constexpr int kswz(int kr) {
+  return ROWS % 128 == 0 ? ((kr & 3) << 2) : (((kr >> 1) & 1) << 2);
+}
+
 template <int ROWS, bool KMAJ, int NW>
 struct DmaLoader {
   static constexpr int NL = ROWS * 64 * 2 / 1024 / NW;  // 1 KB loads per wave per tile
   static_assert(ROWS * 64 * 2 / 1024 % NW == 0, "tile must split evenly over the waves");
-  static_assert(KMAJ || ROWS >= 128, "the [64 k][rows] swizzle moves chunks by up to 12 positions: needs 16 per row");
+  static_assert(KMAJ || ROWS % 128 == 0 || ROWS == 320, "the [64 k][rows] swizzle is defined for whole 128-row groups and for 320 rows");
   uint32_t voff[NL];  // byte offset of this lane's chunk at K offset 0
 
   // Wave w issues loads w*NL .. w*NL+NL-1; load q fills tile bytes [1024 q, 1024 q + 1024).
@@ -444,7 +459,7 @@ struct DmaLoader {
       } else {
         constexpr int CPR = ROWS / 8;  // chunks per k-row
         const int idx = q * 64 + lane, kr = idx / CPR, pos = idx % CPR;
-        const int mc = pos ^ ((kr & 3) << 2);
+        const int mc = pos ^ kswz<ROWS>(kr);
         int gmn = mn0 + mc * 8;
         gmn = gmn < mn_total ? gmn : mn_total - 8;
         voff[i] = ((uint32_t)kr * (uint32_t)ld + gmn) * 2;
@@ -469,9 +484,9 @@ __device__ __forceinline__ bf16x8 read_frag_swz(const bf16_t* tile, int r0, int 
     return *reinterpret_cast<const bf16x8*>(tile + row * 64 + ((kc ^ ((row >> 1) & 7)) << 3));
   } else {
     const int g = lane >> 4, j = lane & 15;
-    const int kr = ks + 8 * (g >> 1) + (j >> 2);  // (kr & 3) is the same for kr and kr + 4
+    const int kr = ks + 8 * (g >> 1) + (j >> 2);  // the swizzle is the same for kr and kr + 4
     const int col = r0 + 16 * (g & 1) + 4 * (j & 3);
-    const bf16_t* p = tile + kr * ROWS + (col ^ ((kr & 3) << 5));
+    const bf16_t* p = tile + kr * ROWS + (col ^ (kswz<ROWS>(kr) << 3));
     typedef __attribute__((address_space(3))) s16x4* lds_ptr;
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
     const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * ROWS));
@@ -591,9 +606,11 @@ __device__ __forceinline__ void dma_tile(const GemmParams& p, bf16_t* smem, int 
   // more and the ring is reused for the epilogue slabs.
   __builtin_amdgcn_s_waitcnt(0x0F70);
   __syncthreads();
-  static_assert(NW * 32 * (WN + 4) * 4 <= NSTAGE * STAGE * 2, "epilogue slabs must fit in the stage ring");
-  float* slab = reinterpret_cast<float*>(smem) + wave * (32 * (WN + 4));
-  epilogue_staged<TM, TN, EPI>(p, acc, slab, m0 + wm0, n0 + wn0, lane);
+  constexpr int JN = TN == 5 ? 4 : TN;  // widest column group of the staged epilogue
+  static_assert(NW * 32 * (32 * JN + 4) * 4 <= NSTAGE * STAGE * 2, "epilogue slabs must fit in the stage ring");
+  float* slab = reinterpret_cast<float*>(smem) + wave * (32 * (32 * JN + 4));
+  epilogue_staged<TM, TN, EPI, 0, JN>(p, acc, slab, m0 + wm0, n0 + wn0, lane);
+  if constexpr (TN == 5) epilogue_staged<TM, TN, EPI, 4, 1>(p, acc, slab, m0 + wm0, n0 + wn0, lane);
 #endif
 }
 
@@ -783,16 +800,18 @@ int launch_dma(hipStream_t st, GemmParams p) {
 // largest tile wins once there are enough tiles, smaller ones when units would otherwise idle.
 //   0: 256x256, 8 waves, 2 stages    1: 256x128, 8 waves, 3 stages    2: 128x128, 4 waves, 2 stages
 //   3: 64x128, 4 waves, 3 stages (skinny outputs: twice the tiles of shape 2)
-// PMC_GEMM_TILE=0|1|2|3 in the environment forces a shape (for tests and tuning).
-int pick_tile(int M, int N) {
+//   4: 256x320, 8 waves, 2 stages (N a multiple of 320 whose 256-wide tiles would leave a ragged last
+//      round, e.g. 4096 x 5120 = exactly 256 tiles)
+// PMC_GEMM_TILE=0|1|2|3|4 in the environment forces a shape (for tests and tuning).
+int pick_tile(int M, int N, bool wide_ok) {
   if (const char* f = std::getenv("PMC_GEMM_TILE")) {
-    if (f[0] >= '0' && f[0] <= '3' && f[1] == 0) return f[0] - '0';
+    if (f[0] >= '0' && f[0] <= '4' && f[1] == 0) return (f[0] == '4' && !wide_ok) ? 0 : f[0] - '0';
   }
-  const int bm[4] = {256, 256, 128, 64}, bn[4] = {256, 128, 128, 128};
-  const double rate[4] = {1.0, 0.95, 0.75, 0.6};
+  const int bm[5] = {256, 256, 128, 64, 256}, bn[5] = {256, 128, 128, 128, 320};
+  const double rate[5] = {1.0, 0.95, 0.75, 0.6, 1.0};
   int best = 0;
   double best_t = 1e300;
-  for (int c = 0; c < 4; ++c) {
+  for (int c = 0; c < (wide_ok ? 5 : 4); ++c) {
     const long n = (long)((M + bm[c] - 1) / bm[c]) * ((N + bn[c] - 1) / bn[c]);
     const double t = (double)((n + 255) / 256) * bm[c] * bn[c] / rate[c];
     if (t < best_t) {
@@ -805,9 +824,15 @@ int pick_tile(int M, int N) {
 
 template <bool A_KMAJ, bool B_KMAJ, int EPI, bool SEG = false>
 int launch_dma_tile(hipStream_t st, const GemmParams& p) {
-  switch (pick_tile(p.M, p.N)) {
+  // the 320-wide tile holds 10 accumulator tiles per wave; with the fp32 read-modify-write epilogue on
+  // top it would spill registers, so weight-gradient products do not use it
+  constexpr bool kWideOk = EPI != PMC_EPI_ACCUM_F32;
+  switch (pick_tile(p.M, p.N, kWideOk)) {
     case 0: return launch_dma<256, 256, 2, 4, A_KMAJ, B_KMAJ, 2, EPI, SEG>(st, p);
     case 1: return launch_dma<256, 128, 4, 2, A_KMAJ, B_KMAJ, 3, EPI, SEG>(st, p);
+    case 4:
+      if constexpr (kWideOk) return launch_dma<256, 320, 4, 2, A_KMAJ, B_KMAJ, 2, EPI, SEG>(st, p);
+      else return launch_dma<256, 256, 2, 4, A_KMAJ, B_KMAJ, 2, EPI, SEG>(st, p);
     case 3:  // the [64 k][rows] swizzle needs 128 rows: a 64-row A tile only when A is contraction-contiguous
       if constexpr (A_KMAJ) return launch_dma<64, 128, 1, 4, A_KMAJ, B_KMAJ, 3, EPI, SEG>(st, p);
       else return launch_dma<128, 128, 2, 2, A_KMAJ, B_KMAJ, 2, EPI, SEG>(st, p);

@@ -88,7 +88,7 @@ def test_gemm_bf16_direct_to_lds_path(ctx, ta, tb, epis):
     ragged edges in M and N (clamped loads), a single K tile and many K tiles."""
     import os
     try:
-        for tile in ("3", "2", "1", "0"):           # 64x128, 128x128, 256x128, 256x256 tiles
+        for tile in ("4", "3", "2", "1", "0"):      # 256x320, 64x128, 128x128, 256x128, 256x256 tiles
             os.environ["PMC_GEMM_TILE"] = tile
             for epi in epis:
                 _gemm_case(ctx, "bf16", ta, tb, 200, 328, 192, epi)

@@ -125,7 +125,7 @@ size_t pmc_pass_workspace_bytes(const pmc_chunk_cfg* cfg);
 
 /* Creates a chunk of cfg->layers identical layers.  Constraints: hidden % heads == 0, head size
  * <= 128 (64 and 128 take the matrix-core attention kernels in bf16 mode); hidden, ffn and tokens
- * multiples of 8 with hidden <= 8192 in bf16 mode, multiples of 4 with hidden <= 4096 in fp32
+ * multiples of 8 with hidden <= 12288 in bf16 mode, multiples of 4 with hidden <= 4096 in fp32
  * mode.  Host-only call. */
 int pmc_chunk_create(pmc_ctx* ctx, const pmc_chunk_cfg* cfg, pmc_chunk** out);
 void pmc_chunk_destroy(pmc_chunk* chunk);
@@ -286,7 +286,7 @@ int pmc_gemm_grouped_wgrad(pmc_ctx* ctx, int32_t M, int32_t N, int32_t K, int32_
                            const void* const* a, int32_t lda, const void* const* b, int32_t ldb,
                            float* C, int32_t ldc);
 
-/* y = LayerNorm(x) over rows of length h (a multiple of 4 up to 4096 in fp32, of 8 up to 8192 in
+/* y = LayerNorm(x) over rows of length h (a multiple of 4 up to 6144 in fp32, of 8 up to 12288 in
  * bf16); mean and rstd are fp32 [rows]; x_copy (may be NULL) receives a copy of x. */
 int pmc_layernorm_forward(pmc_ctx* ctx, int32_t dtype, int32_t rows, int32_t h, const void* x,
                           const void* gain, const void* bias, float eps, void* y, float* mean,

@@ -288,7 +288,7 @@ __global__ __launch_bounds__(256) void copy_rows_kernel(int rows, int vec_cols, 
 
 int pick_nc(int h, int vec) {
   const int need = (h + 64 * vec - 1) / (64 * vec);
-  for (int nc : {1, 2, 3, 4, 6, 8, 12, 16})
+  for (int nc : {1, 2, 3, 4, 6, 8, 12, 16, 20, 24})
     if (nc >= need) return nc;
   return 0;
 }
@@ -333,7 +333,7 @@ int ln_fwd_t(hipStream_t st, int rows, int h, const void* x, const void* gain, c
     break;
   switch (nc) {
     LN_FWD_CASE(1) LN_FWD_CASE(2) LN_FWD_CASE(3) LN_FWD_CASE(4) LN_FWD_CASE(6) LN_FWD_CASE(8) LN_FWD_CASE(12)
-    LN_FWD_CASE(16)
+    LN_FWD_CASE(16) LN_FWD_CASE(20) LN_FWD_CASE(24)
     default:
       return fail(PMC_ERR_INVALID, "LayerNorm width %d too large", h);
   }
@@ -415,7 +415,6 @@ int layernorm_backward(hipStream_t st, int dtype, int rows, int h, const void* d
     return fail(PMC_ERR_INVALID, "layernorm_backward: NULL pointer");
   if (!aligned16(dy) || !aligned16(x) || !aligned16(gain) || !aligned16(dx) || (resid && !aligned16(resid)))
     return fail(PMC_ERR_INVALID, "layernorm_backward: pointers must be 16-byte aligned");
-  if ((size_t)2 * h * sizeof(float) > 64 * 1024) return fail(PMC_ERR_INVALID, "layernorm_backward: h=%d too large", h);
   if (dtype == PMC_F32) return ln_bwd_t<float>(st, rows, h, dy, x, gain, mean, rstd, resid, dx, dgain, dbias, partial, defer);
   if (dtype == PMC_BF16) return ln_bwd_t<bf16_t>(st, rows, h, dy, x, gain, mean, rstd, resid, dx, dgain, dbias, partial, defer);
   return fail(PMC_ERR_INVALID, "layernorm_backward: bad dtype %d", dtype);

@@ -268,13 +268,15 @@ def test_gemm_rejects_bad_arguments(ctx):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("rows,h", [(37, 16), (64, 256), (5, 320), (1100, 1032), (130, 2048), (2100, 4096), (33, 5120), (9, 8192)])
+@pytest.mark.parametrize("rows,h", [(37, 16), (64, 256), (5, 320), (1100, 1032), (130, 2048), (2100, 4096), (33, 5120), (9, 8192),
+                                    (7, 9000), (17, 10240), (6, 12288), (2, 12296)])
 def test_layernorm_forward_backward(ctx, dtype, rows, h):
-    if dtype == "f32" and h > 4096:
-        # a wave keeps its row in registers: 16 vectors of 16 bytes per lane at most
+    if h > (6144 if dtype == "f32" else 12288):
+        # a wave keeps its row in registers: 24 vectors of 16 bytes per lane at most
+        td = torch.float32 if dtype == "f32" else torch.bfloat16
         with pytest.raises(P.PmcError):
-            P.pmc_layernorm_forward(ctx, *[torch.zeros(rows, h, device="cuda")] + [torch.zeros(h, device="cuda")] * 2,
-                                    1e-5, torch.zeros(rows, h, device="cuda"), torch.zeros(rows, device="cuda"),
+            P.pmc_layernorm_forward(ctx, *[torch.zeros(rows, h, device="cuda", dtype=td)] + [torch.zeros(h, device="cuda", dtype=td)] * 2,
+                                    1e-5, torch.zeros(rows, h, device="cuda", dtype=td), torch.zeros(rows, device="cuda"),
                                     torch.zeros(rows, device="cuda"))
         return
     key = ("ln", dtype, rows, h)

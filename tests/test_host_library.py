@@ -119,6 +119,10 @@ def test_bad_cfg_is_rejected():
     assert P.pmc_activation_bytes(P.make_cfg(1, 8192, 64, 8192, 43688)) > 0
     assert P.pmc_activation_bytes(P.make_cfg(1, 8192, 64, 8192, 43696)) == 0
     assert "2 GB" in P.pmc_last_error()
+    # widths of the paper's Table 2 models (5120 .. 10240, head size 128) are accepted in bf16 mode
+    for hidden, heads in ((5120, 40), (6144, 48), (7168, 56), (10240, 80), (12288, 96)):
+        assert P.pmc_activation_bytes(P.make_cfg(2, hidden, heads, 4 * hidden, 2048)) > 0
+    assert P.pmc_activation_bytes(P.make_cfg(2, 12296, 53, 8192, 2048)) == 0  # beyond the row kernels' width
 
 
 @pytest.mark.parametrize("kind", S.KINDS)

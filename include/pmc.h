@@ -124,7 +124,7 @@ size_t pmc_activation_stats_bytes(const pmc_chunk_cfg* cfg);
 size_t pmc_pass_workspace_bytes(const pmc_chunk_cfg* cfg);
 
 /* Creates a chunk of cfg->layers identical layers.  Constraints: hidden % heads == 0, head size
- * <= 128 (64 and 128 take the matrix-core attention kernels in bf16 mode); hidden, ffn and tokens
+ * <= 128 (multiples of 8 take the matrix-core attention kernels in bf16 mode); hidden, ffn and tokens
  * multiples of 8 with hidden <= 12288 in bf16 mode, multiples of 4 with hidden <= 4096 in fp32
  * mode.  Host-only call. */
 int pmc_chunk_create(pmc_ctx* ctx, const pmc_chunk_cfg* cfg, pmc_chunk** out);
@@ -297,7 +297,7 @@ int pmc_layernorm_backward(pmc_ctx* ctx, int32_t dtype, int32_t rows, int32_t h,
                            const void* x, const void* gain, const float* mean, const float* rstd,
                            const void* resid, void* dx, float* dgain, float* dbias);
 /* Fused attention on packed qkv [batch*seq, 3h]: o [batch*seq, h], lse fp32 [batch, heads, seq].
- * In bf16 with head size 64 or 128 (the matrix-core kernels) one sequence's rows, seq * 3h * 2
+ * In bf16 with a head size that is a multiple of 8 (the matrix-core kernels) one sequence's rows, seq * 3h * 2
  * bytes, must stay below 2 GB; larger shapes return PMC_ERR_INVALID (also from pmc_chunk_create). */
 int pmc_attention_forward(pmc_ctx* ctx, int32_t dtype, int32_t batch, int32_t seq, int32_t heads,
                           int32_t head_dim, int32_t causal, const void* qkv, void* o, float* lse);

@@ -149,7 +149,7 @@ int check_cfg(const pmc_chunk_cfg* c) {
     if (dh > 128) return fail(PMC_ERR_INVALID, "cfg: head size %d > 128", dh);
     if (c->hidden > 12288) return fail(PMC_ERR_INVALID, "cfg: bf16 mode supports hidden <= 12288");
     // the matrix-core attention kernels address one sequence's q|k|v rows inside a 2 GB window
-    if ((dh == 64 || dh == 128) && (int64_t)c->seq * 3 * c->hidden * 2 > 0x7fffffffLL)
+    if (dh % 8 == 0 && (int64_t)c->seq * 3 * c->hidden * 2 > 0x7fffffffLL)
       return fail(PMC_ERR_INVALID, "cfg: seq %d x 3 x hidden %d in bf16 exceeds 2 GB per sequence", c->seq, c->hidden);
   } else {
     if (c->hidden % 4 || c->ffn % 4 || tokens % 4)

@@ -16,9 +16,9 @@ int attention_backward_mfma(hipStream_t st, int batch, int seq, int heads, int d
                             const void* o, const float* lse, const void* d_o, void* dqkv, void* dq_stage, float* delta);
 
 namespace {
-// bf16 storage with head size 64 or 128 runs on the matrix cores; everything else (fp32 mode,
-// other head sizes) on the plain-arithmetic kernels.
-bool use_mfma(int dtype, int head_dim) { return dtype == PMC_BF16 && (head_dim == 64 || head_dim == 128); }
+// bf16 storage with a head size that is a multiple of 8 (up to 128) runs on the matrix cores;
+// everything else (fp32 mode, other head sizes) on the plain-arithmetic kernels.
+bool use_mfma(int dtype, int head_dim) { return dtype == PMC_BF16 && head_dim >= 8 && head_dim <= 128 && head_dim % 8 == 0; }
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 size_t elem(int dtype) { return dtype == PMC_F32 ? 4 : 2; }
 }  // namespace

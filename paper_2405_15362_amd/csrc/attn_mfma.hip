@@ -101,17 +101,22 @@ struct BlockDma {
   static constexpr int NW = NT / 64;
   static constexpr int PER = (NI + NW - 1) / NW;     // per wave (the last waves idle if NI % NW)
   static_assert(ROWS % RPI == 0, "block must be whole wave instructions");
+  static constexpr uint32_t kSkip = 0xffffffffu;
   int row_in_block[PER];
   uint32_t col_bytes[PER];
-  __device__ __forceinline__ void init(int wave, int lane) {
+  // dh: columns a row really has (a multiple of 8, at most DH).  Lanes whose chunk lies past them
+  // load nothing; their LDS positions keep the zeros the kernel wrote there once.
+  __device__ __forceinline__ void init(int wave, int lane, int dh = DH) {
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
       const int q = wave + i * NW, row = q * RPI + lane / CPR, pos = lane % CPR;
+      const int chunk = pos ^ swz<DH>(row);
       row_in_block[i] = row;
-      col_bytes[i] = (uint32_t)((pos ^ swz<DH>(row)) << 4);
+      col_bytes[i] = 8 * chunk < dh ? (uint32_t)(chunk << 4) : kSkip;
     }
   }
   // row0: first row of the block; last_row: the last valid row; ld_bytes: row pitch in bytes
+  template <bool PAD = false>
   __device__ __forceinline__ void issue(i32x4 rsrc, bf16_t* tile, uint32_t ld_bytes, int row0, int last_row, int wave) const {
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
@@ -119,8 +124,9 @@ struct BlockDma {
       if (NI % NW != 0 && q >= NI) break;
       const uint32_t voff = (uint32_t)min(row0 + row_in_block[i], last_row) * ld_bytes + col_bytes[i];
       const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)((lds_void_ptr)(tile + q * 512)));
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                   :: "s"(lds_addr), "v"(voff), "s"(rsrc) : "memory");
+      if (!PAD || col_bytes[i] != kSkip)  // a lane writes its own 16 bytes of the instruction's 1 KB whoever else is active
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                     :: "s"(lds_addr), "v"(voff), "s"(rsrc) : "memory");
     }
   }
 };
@@ -133,13 +139,30 @@ __device__ __forceinline__ void zero(f32x16& a) {
 }
 
 // Writes an accumulator tile holding OUT^T[dh][row] (lane = row, registers = dh) times `mul` to
-// out[row][col0 + 32*dt + ...] as bf16, four consecutive columns per store.
-__device__ __forceinline__ void store_tile_t(bf16_t* row_ptr, const f32x16& a, float mul, int lane) {
+// out[row][col0 + 32*dt + ...] as bf16, four consecutive columns per store; only the first `cols`
+// of the tile's 32 columns exist (a multiple of 4).
+__device__ __forceinline__ void store_tile_t(bf16_t* row_ptr, const f32x16& a, float mul, int lane, int cols = 32) {
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     u32x2 v = {pack_bf16x2(a[4 * q] * mul, a[4 * q + 1] * mul), pack_bf16x2(a[4 * q + 2] * mul, a[4 * q + 3] * mul)};
-    *reinterpret_cast<u32x2*>(row_ptr + 8 * q + 4 * (lane >> 5)) = v;
+    if (8 * q + 4 * (lane >> 5) < cols) *reinterpret_cast<u32x2*>(row_ptr + 8 * q + 4 * (lane >> 5)) = v;
   }
+}
+
+// Eight consecutive elements of a row from global memory, zeros if they lie past the row's dh columns.
+__device__ __forceinline__ bf16x8 load_frag(const bf16_t* p, int col, int dh) {
+  bf16x8 z;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) z[e] = (__bf16)0.f;
+  return col < dh ? *reinterpret_cast<const bf16x8*>(p + col) : z;
+}
+
+// Head sizes below the tile width: the tiles' columns past dh are zeroed once (the loads skip them).
+template <int NT>
+__device__ __forceinline__ void zero_tiles(bf16_t* smem, int elems, int tid) {
+  const u32x4 z = {0u, 0u, 0u, 0u};
+  for (int i = tid * 8; i < elems; i += NT * 8) *reinterpret_cast<u32x4*>(smem + i) = z;
+  __syncthreads();
 }
 
 // Forward.  The workgroup is a QW x KW grid of waves: wave (qg, kg) owns queries 32 qg .. 32 qg + 31
@@ -149,8 +172,9 @@ __device__ __forceinline__ void store_tile_t(bf16_t* row_ptr, const f32x16& a, f
 // a query group are merged in key-group order through LDS.  Splitting the keys over waves puts two
 // waves on every SIMD even when there are few (query block, head) pairs, and shortens the serial
 // chain of a long row of key blocks.
-template <int DH, int QW, int KW, int NKT>
-__global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_fwd_mfma(int seq, int heads, int causal, const bf16_t* __restrict__ qkv,
+// PAD: the head size dh is smaller than the tile width DH (the columns past dh are kept at zero).
+template <int DH, int QW, int KW, int NKT, bool PAD>
+__global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_fwd_mfma(int seq, int heads, int dh, int causal, const bf16_t* __restrict__ qkv,
                                                                bf16_t* __restrict__ o, float* __restrict__ lse,
                                                                float scale_log2) {
   constexpr int NT = QW * KW * 64, BQW = 32 * QW, WK = 32 * NKT, BSW = WK * KW;
@@ -160,16 +184,16 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_fwd_m
   const int qg = wave % QW, kg = wave / QW;
   // grid = (heads * batch, query blocks); under a causal mask late query blocks see the most keys,
   // so they are dealt out first and the short ones fill the tail
-  const int h = heads * DH, head = blockIdx.x % heads, b = blockIdx.x / heads;
+  const int h = heads * dh, head = blockIdx.x % heads, b = blockIdx.x / heads;
   const int q0 = (causal ? (int)(gridDim.y - 1 - blockIdx.y) : (int)blockIdx.y) * BQW, qw0 = q0 + 32 * qg, qrow = qw0 + (lane & 31);
   const size_t ld = (size_t)3 * h;
-  const bf16_t* base = qkv + (size_t)b * seq * ld + (size_t)head * DH;
+  const bf16_t* base = qkv + (size_t)b * seq * ld + (size_t)head * dh;
 
   bf16x8 qf[DH / 16];
   {
-    const bf16_t* qp = base + (size_t)min(qrow, seq - 1) * ld + 8 * hl;
+    const bf16_t* qp = base + (size_t)min(qrow, seq - 1) * ld;
 #pragma unroll
-    for (int ks = 0; ks < DH / 16; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+    for (int ks = 0; ks < DH / 16; ++ks) qf[ks] = load_frag(qp, 16 * ks + 8 * hl, PAD ? dh : DH);
   }
   f32x16 oacc[DH / 32];
 #pragma unroll
@@ -180,10 +204,11 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_fwd_m
   const int nblk = (kend + BSW - 1) / BSW;
   const i32x4 rk = make_rsrc(base + h), rv = make_rsrc(base + 2 * h);
   const uint32_t ldb = (uint32_t)ld * 2;
+  if (PAD) zero_tiles<NT>(smem, 2 * (KT + VT), tid);
   BlockDma<BSW, DH, NT> dma;
-  dma.init(wave, lane);
-  dma.issue(rk, smem, ldb, 0, seq - 1, wave);
-  dma.issue(rv, smem + KT, ldb, 0, seq - 1, wave);
+  dma.init(wave, lane, PAD ? dh : DH);
+  dma.template issue<PAD>(rk, smem, ldb, 0, seq - 1, wave);
+  dma.template issue<PAD>(rv, smem + KT, ldb, 0, seq - 1, wave);
   __builtin_amdgcn_s_waitcnt(kWaitAllLoads);
   __syncthreads();
   // The query fragments must have arrived before the loop: left pending, the compiler's wait for
@@ -196,8 +221,8 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_fwd_m
     const bf16_t* vt_ = kt_ + KT;
     if (blk + 1 < nblk) {  // the other stage: every wave left it at the last barrier
       bf16_t* nxt = smem + ((blk + 1) & 1) * (KT + VT);
-      dma.issue(rk, nxt, ldb, (blk + 1) * BSW, seq - 1, wave);
-      dma.issue(rv, nxt + KT, ldb, (blk + 1) * BSW, seq - 1, wave);
+      dma.template issue<PAD>(rk, nxt, ldb, (blk + 1) * BSW, seq - 1, wave);
+      dma.template issue<PAD>(rv, nxt + KT, ldb, (blk + 1) * BSW, seq - 1, wave);
     }
     if (k0 < seq && (!causal || k0 <= qw0 + 31)) {
       // The K fragments of a 32-key tile are requested together, and those of the next tile each
@@ -313,9 +338,9 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_fwd_m
   }
   if (qrow < seq) {
     const float inv = 1.0f / lsum;
-    bf16_t* orow = o + ((size_t)b * seq + qrow) * h + (size_t)head * DH;
+    bf16_t* orow = o + ((size_t)b * seq + qrow) * h + (size_t)head * dh;
 #pragma unroll
-    for (int dt = 0; dt < DH / 32; ++dt) store_tile_t(orow + 32 * dt, oacc[dt], inv, lane);
+    for (int dt = 0; dt < DH / 32; ++dt) store_tile_t(orow + 32 * dt, oacc[dt], inv, lane, PAD ? dh - 32 * dt : 32);
     if (hl == 0) lse[((size_t)b * heads + head) * seq + qrow] = (m2 + log2f(lsum)) * kLn2;
   }
 }
@@ -324,9 +349,9 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_fwd_m
 // keys starting at 32 NKT kg of every streamed block; 32-key tiles are taken one at a time
 // (S and dP, then dS, then dQ^T += K^T dS^T) to keep the register footprint at two waves per SIMD.
 // The KW partial dQ of a query group are added in key-group order through LDS at the end.
-template <int DH, int QW, int KW, int NKT>
+template <int DH, int QW, int KW, int NKT, bool PAD>
 __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_bwd_dq_mfma(
-    int seq, int heads, int causal, const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ o,
+    int seq, int heads, int dh, int causal, const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ o,
     const float* __restrict__ lse, const bf16_t* __restrict__ d_o, bf16_t* __restrict__ dq, float* __restrict__ delta,
     float scale, float scale_log2) {
   constexpr int NT = QW * KW * 64, BQW = 32 * QW, WK = 32 * NKT, BSW = WK * KW;
@@ -336,22 +361,23 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_bwd_d
   const int qg = wave % QW, kg = wave / QW;
   // grid = (heads * batch, query blocks); under a causal mask late query blocks see the most keys,
   // so they are dealt out first and the short ones fill the tail
-  const int h = heads * DH, head = blockIdx.x % heads, b = blockIdx.x / heads;
+  const int h = heads * dh, head = blockIdx.x % heads, b = blockIdx.x / heads;
   const int q0 = (causal ? (int)(gridDim.y - 1 - blockIdx.y) : (int)blockIdx.y) * BQW, qw0 = q0 + 32 * qg, qrow = qw0 + (lane & 31);
   const int qclamp = min(qrow, seq - 1);
   const size_t ld = (size_t)3 * h;
-  const bf16_t* base = qkv + (size_t)b * seq * ld + (size_t)head * DH;
+  const bf16_t* base = qkv + (size_t)b * seq * ld + (size_t)head * dh;
 
   bf16x8 qf[DH / 16], dof[DH / 16];
   float dl = 0.f;
   {
-    const bf16_t* qp = base + (size_t)qclamp * ld + 8 * hl;
-    const size_t orow = ((size_t)b * seq + qclamp) * h + (size_t)head * DH + 8 * hl;
+    const bf16_t* qp = base + (size_t)qclamp * ld;
+    const size_t orow = ((size_t)b * seq + qclamp) * h + (size_t)head * dh;
+    const int cols = PAD ? dh : DH;
 #pragma unroll
     for (int ks = 0; ks < DH / 16; ++ks) {
-      qf[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
-      dof[ks] = *reinterpret_cast<const bf16x8*>(d_o + orow + 16 * ks);
-      const bf16x8 of = *reinterpret_cast<const bf16x8*>(o + orow + 16 * ks);
+      qf[ks] = load_frag(qp, 16 * ks + 8 * hl, cols);
+      dof[ks] = load_frag(d_o + orow, 16 * ks + 8 * hl, cols);
+      const bf16x8 of = load_frag(o + orow, 16 * ks + 8 * hl, cols);
 #pragma unroll
       for (int e = 0; e < 8; ++e) dl += (float)dof[ks][e] * (float)of[e];
     }
@@ -368,10 +394,11 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_bwd_d
   const int nblk = (kend + BSW - 1) / BSW;
   const i32x4 rk = make_rsrc(base + h), rv = make_rsrc(base + 2 * h);
   const uint32_t ldb = (uint32_t)ld * 2;
+  if (PAD) zero_tiles<NT>(smem, 2 * (KT + VT), tid);
   BlockDma<BSW, DH, NT> dma;
-  dma.init(wave, lane);
-  dma.issue(rk, smem, ldb, 0, seq - 1, wave);
-  dma.issue(rv, smem + KT, ldb, 0, seq - 1, wave);
+  dma.init(wave, lane, PAD ? dh : DH);
+  dma.template issue<PAD>(rk, smem, ldb, 0, seq - 1, wave);
+  dma.template issue<PAD>(rv, smem + KT, ldb, 0, seq - 1, wave);
   __builtin_amdgcn_s_waitcnt(kWaitAllLoads);
   __syncthreads();
   for (int blk = 0; blk < nblk; ++blk) {
@@ -379,8 +406,8 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_bwd_d
     const bf16_t* vt_ = kt_ + KT;
     if (blk + 1 < nblk) {
       bf16_t* nxt = smem + ((blk + 1) & 1) * (KT + VT);
-      dma.issue(rk, nxt, ldb, (blk + 1) * BSW, seq - 1, wave);
-      dma.issue(rv, nxt + KT, ldb, (blk + 1) * BSW, seq - 1, wave);
+      dma.template issue<PAD>(rk, nxt, ldb, (blk + 1) * BSW, seq - 1, wave);
+      dma.template issue<PAD>(rv, nxt + KT, ldb, (blk + 1) * BSW, seq - 1, wave);
     }
 #pragma unroll
     for (int kt = 0; kt < NKT; ++kt) {
@@ -442,9 +469,9 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_bwd_d
     }
   }
   if (qrow < seq) {
-    bf16_t* row = dq + ((size_t)b * seq + qrow) * h + (size_t)head * DH;
+    bf16_t* row = dq + ((size_t)b * seq + qrow) * h + (size_t)head * dh;
 #pragma unroll
-    for (int dt = 0; dt < DH / 32; ++dt) store_tile_t(row + 32 * dt, acc[dt], scale, lane);
+    for (int dt = 0; dt < DH / 32; ++dt) store_tile_t(row + 32 * dt, acc[dt], scale, lane, PAD ? dh - 32 * dt : 32);
   }
 }
 
@@ -457,9 +484,9 @@ __global__ __launch_bounds__(QW * KW * 64, QW * KW == 4 ? 2 : 1) void attn_bwd_d
 // elementwise step between them differs.  The QG partial sums of a key group are added in
 // query-group order through LDS at the end and written in place over K and V (a key block is read
 // only by its own workgroup).
-template <int DH, int KG, int QG>
+template <int DH, int KG, int QG, bool PAD>
 __global__ __launch_bounds__(KG * QG * 128, KG * QG == 2 ? 3 : 1) void attn_bwd_dkv_mfma(
-    int seq, int heads, int causal, const bf16_t* qkv, const float* __restrict__ lse, const float* __restrict__ delta,
+    int seq, int heads, int dh, int causal, const bf16_t* qkv, const float* __restrict__ lse, const float* __restrict__ delta,
     const bf16_t* __restrict__ d_o, bf16_t* dqkv, float scale, float scale_log2) {
   constexpr int NP = KG * QG, NT = NP * 128, BK = 32 * KG, BSQ = 32 * QG;
   constexpr int QT = BSQ * DH;
@@ -469,19 +496,19 @@ __global__ __launch_bounds__(KG * QG * 128, KG * QG == 2 ? 3 : 1) void attn_bwd_
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), hl = lane >> 5;
   const int role = wave / NP, pair = wave % NP, kg = pair % KG, qg = pair / KG;
   // grid = (heads * batch, key blocks): early key blocks see the most queries and go first
-  const int h = heads * DH, head = blockIdx.x % heads, b = blockIdx.x / heads;
+  const int h = heads * dh, head = blockIdx.x % heads, b = blockIdx.x / heads;
   const int k0 = blockIdx.y * BK, kw0 = k0 + 32 * kg, krow = kw0 + (lane & 31);
   const size_t ld = (size_t)3 * h;
-  const bf16_t* base = qkv + (size_t)b * seq * ld + (size_t)head * DH;
-  const bf16_t* dob = d_o + (size_t)b * seq * h + (size_t)head * DH;
+  const bf16_t* base = qkv + (size_t)b * seq * ld + (size_t)head * dh;
+  const bf16_t* dob = d_o + (size_t)b * seq * h + (size_t)head * dh;
   const float* lse_b = lse + ((size_t)b * heads + head) * seq;
   const float* delta_b = delta + ((size_t)b * heads + head) * seq;
 
   bf16x8 kvf[DH / 16];  // role 0: K rows of this key group; role 1: V rows
   {
-    const bf16_t* kp = base + (size_t)min(krow, seq - 1) * ld + (role ? 2 * h : h) + 8 * hl;
+    const bf16_t* kp = base + (size_t)min(krow, seq - 1) * ld + (role ? 2 * h : h);
 #pragma unroll
-    for (int ks = 0; ks < DH / 16; ++ks) kvf[ks] = *reinterpret_cast<const bf16x8*>(kp + 16 * ks);
+    for (int ks = 0; ks < DH / 16; ++ks) kvf[ks] = load_frag(kp, 16 * ks + 8 * hl, PAD ? dh : DH);
   }
   f32x16 acc[DH / 32];  // role 0: dV^T, role 1: dK^T (unscaled)
 #pragma unroll
@@ -490,8 +517,9 @@ __global__ __launch_bounds__(KG * QG * 128, KG * QG == 2 ? 3 : 1) void attn_bwd_
   const int nblk = (seq - qstart + BSQ - 1) / BSQ;
   const i32x4 rq = make_rsrc(base), rdo = make_rsrc(dob);
   const uint32_t ldb = (uint32_t)ld * 2, hb = (uint32_t)h * 2;
+  if (PAD) zero_tiles<NT>(smem, 4 * QT, tid);
   BlockDma<BSQ, DH, NT> dma;
-  dma.init(wave, lane);
+  dma.init(wave, lane, PAD ? dh : DH);
   float st_reg = 0.f;  // threads 0..BSQ-1: lse2 of query tid; BSQ..2 BSQ-1: delta of query tid-BSQ
   auto load_stats = [&](int q0) {
     if (tid < 2 * BSQ) {
@@ -499,8 +527,8 @@ __global__ __launch_bounds__(KG * QG * 128, KG * QG == 2 ? 3 : 1) void attn_bwd_
       st_reg = qi < seq ? (tid < BSQ ? lse_b[qi] * kLog2e : delta_b[qi]) : 0.f;
     }
   };
-  dma.issue(rq, smem, ldb, qstart, seq - 1, wave);
-  dma.issue(rdo, smem + QT, hb, qstart, seq - 1, wave);
+  dma.template issue<PAD>(rq, smem, ldb, qstart, seq - 1, wave);
+  dma.template issue<PAD>(rdo, smem + QT, hb, qstart, seq - 1, wave);
   load_stats(qstart);
   if (tid < 2 * BSQ) stats[tid] = st_reg;
   __builtin_amdgcn_s_waitcnt(kWaitAllLoads);
@@ -516,8 +544,8 @@ __global__ __launch_bounds__(KG * QG * 128, KG * QG == 2 ? 3 : 1) void attn_bwd_
     const float* st_ = stats + (blk & 1) * 2 * BSQ + (role ? BSQ : 0) + trow;  // lse2 (role 0) or delta (role 1)
     if (blk + 1 < nblk) {  // the other stage: every wave left it at the last barrier
       bf16_t* nxt = smem + ((blk + 1) & 1) * 2 * QT;
-      dma.issue(rq, nxt, ldb, qstart + (blk + 1) * BSQ, seq - 1, wave);
-      dma.issue(rdo, nxt + QT, hb, qstart + (blk + 1) * BSQ, seq - 1, wave);
+      dma.template issue<PAD>(rq, nxt, ldb, qstart + (blk + 1) * BSQ, seq - 1, wave);
+      dma.template issue<PAD>(rdo, nxt + QT, hb, qstart + (blk + 1) * BSQ, seq - 1, wave);
       load_stats(qstart + (blk + 1) * BSQ);
     }
     const bool active = q0 < seq && (!causal || q0 + 31 >= kw0);  // the same for both waves of a pair
@@ -593,10 +621,10 @@ __global__ __launch_bounds__(KG * QG * 128, KG * QG == 2 ? 3 : 1) void attn_bwd_
     }
   }
   if (qg == 0 && krow < seq) {
-    bf16_t* row = dqkv + ((size_t)b * seq + krow) * ld + (size_t)head * DH + (role ? h : 2 * h);
+    bf16_t* row = dqkv + ((size_t)b * seq + krow) * ld + (size_t)head * dh + (role ? h : 2 * h);
     const float mul = role ? scale : 1.0f;
 #pragma unroll
-    for (int dt = 0; dt < DH / 32; ++dt) store_tile_t(row + 32 * dt, acc[dt], mul, lane);
+    for (int dt = 0; dt < DH / 32; ++dt) store_tile_t(row + 32 * dt, acc[dt], mul, lane, PAD ? dh - 32 * dt : 32);
   }
 }
 
@@ -609,14 +637,14 @@ int reserve_lds(K kern, size_t bytes, bool& done, const char* what) {
   return PMC_OK;
 }
 
-template <int DH, int QW, int KW, int NKT>
-int fwd_launch(hipStream_t st, int batch, int seq, int heads, int causal, const void* qkv, void* o, float* lse) {
+template <int DH, int QW, int KW, int NKT, bool PAD>
+int fwd_launch(hipStream_t st, int batch, int seq, int heads, int dh, int causal, const void* qkv, void* o, float* lse) {
   constexpr size_t lds = 2 * sizeof(bf16_t) * 32 * NKT * KW * 2 * DH;
   static bool done = false;
-  if (int rc = reserve_lds(attn_fwd_mfma<DH, QW, KW, NKT>, lds, done, "attention_forward")) return rc;
-  const float scale_log2 = kLog2e / sqrtf((float)DH);
-  attn_fwd_mfma<DH, QW, KW, NKT><<<dim3(heads * batch, (seq + 32 * QW - 1) / (32 * QW)), dim3(QW * KW * 64), lds, st>>>(
-      seq, heads, causal, (const bf16_t*)qkv, (bf16_t*)o, lse, scale_log2);
+  if (int rc = reserve_lds(attn_fwd_mfma<DH, QW, KW, NKT, PAD>, lds, done, "attention_forward")) return rc;
+  const float scale_log2 = kLog2e / sqrtf((float)dh);
+  attn_fwd_mfma<DH, QW, KW, NKT, PAD><<<dim3(heads * batch, (seq + 32 * QW - 1) / (32 * QW)), dim3(QW * KW * 64), lds, st>>>(
+      seq, heads, dh, causal, (const bf16_t*)qkv, (bf16_t*)o, lse, scale_log2);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(PMC_ERR_HIP, "attention_forward launch failed: %s", hipGetErrorString(e));
   return PMC_OK;
@@ -633,15 +661,15 @@ int shape_family(int batch, int seq, int heads) {
   return (long)((seq + 127) / 128) * heads * batch < 512 ? 0 : 1;
 }
 
-template <int DH>
-int fwd_t(hipStream_t st, int batch, int seq, int heads, int causal, const void* qkv, void* o, float* lse) {
-  if (shape_family(batch, seq, heads) == 0) return fwd_launch<DH, 2, 4, 1>(st, batch, seq, heads, causal, qkv, o, lse);
-  return fwd_launch<DH, 4, 1, 2>(st, batch, seq, heads, causal, qkv, o, lse);
+template <int DH, bool PAD>
+int fwd_t(hipStream_t st, int batch, int seq, int heads, int dh, int causal, const void* qkv, void* o, float* lse) {
+  if (shape_family(batch, seq, heads) == 0) return fwd_launch<DH, 2, 4, 1, PAD>(st, batch, seq, heads, dh, causal, qkv, o, lse);
+  return fwd_launch<DH, 4, 1, 2, PAD>(st, batch, seq, heads, dh, causal, qkv, o, lse);
 }
 
-template <int DH, int QW, int KW, int NKT, int KG, int QG>
-int bwd_launch(hipStream_t st, int batch, int seq, int heads, int causal, const void* qkv, const void* o, const float* lse,
-               const void* d_o, void* dqkv, void* dq_stage, float* delta) {
+template <int DH, int QW, int KW, int NKT, int KG, int QG, bool PAD>
+int bwd_launch(hipStream_t st, int batch, int seq, int heads, int dh, int causal, const void* qkv, const void* o,
+               const float* lse, const void* d_o, void* dqkv, void* dq_stage, float* delta) {
   constexpr size_t lds_dq = 2 * sizeof(bf16_t) * 32 * NKT * KW * 2 * DH;
   constexpr size_t tiles_dkv =
       4 * sizeof(bf16_t) * 32 * QG * DH + (4 * 32 * QG + (size_t)KG * QG * 16 * 64) * sizeof(float);
@@ -649,31 +677,34 @@ int bwd_launch(hipStream_t st, int batch, int seq, int heads, int causal, const 
   constexpr size_t lds_dkv = tiles_dkv > merge_dkv ? tiles_dkv : merge_dkv;
   static_assert(lds_dq <= 160 * 1024 && lds_dkv <= 160 * 1024, "tiles exceed the LDS of a compute unit");
   static bool done_dq = false, done_dkv = false;
-  if (int rc = reserve_lds(attn_bwd_dq_mfma<DH, QW, KW, NKT>, lds_dq, done_dq, "attention_backward")) return rc;
-  if (int rc = reserve_lds(attn_bwd_dkv_mfma<DH, KG, QG>, lds_dkv, done_dkv, "attention_backward")) return rc;
-  const float scale = 1.0f / sqrtf((float)DH), scale_log2 = kLog2e * scale;
-  attn_bwd_dq_mfma<DH, QW, KW, NKT><<<dim3(heads * batch, (seq + 32 * QW - 1) / (32 * QW)), dim3(QW * KW * 64), lds_dq, st>>>(
-      seq, heads, causal, (const bf16_t*)qkv, (const bf16_t*)o, lse, (const bf16_t*)d_o, (bf16_t*)dq_stage, delta, scale,
+  if (int rc = reserve_lds(attn_bwd_dq_mfma<DH, QW, KW, NKT, PAD>, lds_dq, done_dq, "attention_backward")) return rc;
+  if (int rc = reserve_lds(attn_bwd_dkv_mfma<DH, KG, QG, PAD>, lds_dkv, done_dkv, "attention_backward")) return rc;
+  const float scale = 1.0f / sqrtf((float)dh), scale_log2 = kLog2e * scale;
+  attn_bwd_dq_mfma<DH, QW, KW, NKT, PAD><<<dim3(heads * batch, (seq + 32 * QW - 1) / (32 * QW)), dim3(QW * KW * 64), lds_dq, st>>>(
+      seq, heads, dh, causal, (const bf16_t*)qkv, (const bf16_t*)o, lse, (const bf16_t*)d_o, (bf16_t*)dq_stage, delta, scale,
       scale_log2);
-  attn_bwd_dkv_mfma<DH, KG, QG><<<dim3(heads * batch, (seq + 32 * KG - 1) / (32 * KG)), dim3(KG * QG * 128), lds_dkv, st>>>(
-      seq, heads, causal, (const bf16_t*)qkv, lse, delta, (const bf16_t*)d_o, (bf16_t*)dqkv, scale, scale_log2);
+  attn_bwd_dkv_mfma<DH, KG, QG, PAD><<<dim3(heads * batch, (seq + 32 * KG - 1) / (32 * KG)), dim3(KG * QG * 128), lds_dkv, st>>>(
+      seq, heads, dh, causal, (const bf16_t*)qkv, lse, delta, (const bf16_t*)d_o, (bf16_t*)dqkv, scale, scale_log2);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(PMC_ERR_HIP, "attention_backward launch failed: %s", hipGetErrorString(e));
   return PMC_OK;
 }
 
-template <int DH>
-int bwd_t(hipStream_t st, int batch, int seq, int heads, int causal, const void* qkv, const void* o, const float* lse,
+template <int DH, bool PAD>
+int bwd_t(hipStream_t st, int batch, int seq, int heads, int dh, int causal, const void* qkv, const void* o, const float* lse,
           const void* d_o, void* dqkv, void* dq_stage, float* delta) {
   const int fam = shape_family(batch, seq, heads);
-  if (fam == 0) return bwd_launch<DH, 2, 4, 1, 2, 2>(st, batch, seq, heads, causal, qkv, o, lse, d_o, dqkv, dq_stage, delta);
-  if (fam == 2) return bwd_launch<DH, 4, 1, 2, 4, 1>(st, batch, seq, heads, causal, qkv, o, lse, d_o, dqkv, dq_stage, delta);
-  return bwd_launch<DH, 4, 1, 2, 2, 1>(st, batch, seq, heads, causal, qkv, o, lse, d_o, dqkv, dq_stage, delta);
+  if (fam == 0)
+    return bwd_launch<DH, 2, 4, 1, 2, 2, PAD>(st, batch, seq, heads, dh, causal, qkv, o, lse, d_o, dqkv, dq_stage, delta);
+  if (fam == 2)
+    return bwd_launch<DH, 4, 1, 2, 4, 1, PAD>(st, batch, seq, heads, dh, causal, qkv, o, lse, d_o, dqkv, dq_stage, delta);
+  return bwd_launch<DH, 4, 1, 2, 2, 1, PAD>(st, batch, seq, heads, dh, causal, qkv, o, lse, d_o, dqkv, dq_stage, delta);
 }
 
 int check(const char* what, int batch, int seq, int heads, int dh, const void* qkv) {
   if (batch <= 0 || seq <= 0 || heads <= 0) return fail(PMC_ERR_INVALID, "%s: batch=%d seq=%d heads=%d", what, batch, seq, heads);
-  if (dh != 64 && dh != 128) return fail(PMC_ERR_INVALID, "%s: matrix-core path needs head size 64 or 128, got %d", what, dh);
+  if (dh < 8 || dh > 128 || dh % 8)
+    return fail(PMC_ERR_INVALID, "%s: matrix-core path needs a head size that is a multiple of 8 up to 128, got %d", what, dh);
   if (seq > 65535 * 32 || (long)heads * batch > 0x7fffffffL) return fail(PMC_ERR_INVALID, "%s: seq or heads*batch exceed the grid limit", what);
   if (reinterpret_cast<uintptr_t>(qkv) & 15) return fail(PMC_ERR_INVALID, "%s: qkv must be 16-byte aligned", what);
   // the tile loads address one sequence's rows with 32-bit byte offsets inside a 2 GB window
@@ -684,11 +715,16 @@ int check(const char* what, int batch, int seq, int heads, int dh, const void* q
 
 }  // namespace
 
+// Head sizes 64 and 128 fill the kernels' tiles; the other multiples of 8 run in the next larger
+// tile with its remaining columns held at zero.
 int attention_forward_mfma(hipStream_t st, int batch, int seq, int heads, int dh, int causal, const void* qkv, void* o,
                            float* lse) {
   if (int rc = check("attention_forward", batch, seq, heads, dh, qkv)) return rc;
   if (reinterpret_cast<uintptr_t>(o) & 15) return fail(PMC_ERR_INVALID, "attention_forward: o must be 16-byte aligned");
-  return dh == 64 ? fwd_t<64>(st, batch, seq, heads, causal, qkv, o, lse) : fwd_t<128>(st, batch, seq, heads, causal, qkv, o, lse);
+  if (dh == 64) return fwd_t<64, false>(st, batch, seq, heads, dh, causal, qkv, o, lse);
+  if (dh == 128) return fwd_t<128, false>(st, batch, seq, heads, dh, causal, qkv, o, lse);
+  if (dh < 64) return fwd_t<64, true>(st, batch, seq, heads, dh, causal, qkv, o, lse);
+  return fwd_t<128, true>(st, batch, seq, heads, dh, causal, qkv, o, lse);
 }
 
 int attention_backward_mfma(hipStream_t st, int batch, int seq, int heads, int dh, int causal, const void* qkv,
@@ -697,8 +733,10 @@ int attention_backward_mfma(hipStream_t st, int batch, int seq, int heads, int d
   if ((reinterpret_cast<uintptr_t>(o) | reinterpret_cast<uintptr_t>(d_o) | reinterpret_cast<uintptr_t>(dqkv) |
        reinterpret_cast<uintptr_t>(dq_stage)) & 15)
     return fail(PMC_ERR_INVALID, "attention_backward: tensors must be 16-byte aligned");
-  return dh == 64 ? bwd_t<64>(st, batch, seq, heads, causal, qkv, o, lse, d_o, dqkv, dq_stage, delta)
-                  : bwd_t<128>(st, batch, seq, heads, causal, qkv, o, lse, d_o, dqkv, dq_stage, delta);
+  if (dh == 64) return bwd_t<64, false>(st, batch, seq, heads, dh, causal, qkv, o, lse, d_o, dqkv, dq_stage, delta);
+  if (dh == 128) return bwd_t<128, false>(st, batch, seq, heads, dh, causal, qkv, o, lse, d_o, dqkv, dq_stage, delta);
+  if (dh < 64) return bwd_t<64, true>(st, batch, seq, heads, dh, causal, qkv, o, lse, d_o, dqkv, dq_stage, delta);
+  return bwd_t<128, true>(st, batch, seq, heads, dh, causal, qkv, o, lse, d_o, dqkv, dq_stage, delta);
 }
 
 }  // namespace k

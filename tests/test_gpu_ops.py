@@ -312,7 +312,8 @@ def test_layernorm_forward_backward(ctx, dtype, rows, h):
     assert rel_l2(host(dbias) + 0.5, db_ref) <= 1e-5
 
 
-@pytest.mark.parametrize("dtype,dh", [("f32", 4), ("f32", 16), ("f32", 64), ("f32", 128), ("bf16", 64), ("bf16", 128)])
+@pytest.mark.parametrize("dtype,dh", [("f32", 4), ("f32", 16), ("f32", 64), ("f32", 128), ("bf16", 64), ("bf16", 128),
+                                      ("bf16", 8), ("bf16", 40), ("bf16", 96), ("bf16", 112)])
 @pytest.mark.parametrize("causal", [True, False])
 def test_attention_forward_backward(ctx, dtype, dh, causal):
     batch, seq, heads = 2, 88, 3
@@ -347,10 +348,12 @@ def test_attention_forward_backward(ctx, dtype, dh, causal):
 
 
 @pytest.mark.parametrize("family", ["0", "1", "2"])
-@pytest.mark.parametrize("dh,causal", [(128, True), (64, True), (128, False)])
+@pytest.mark.parametrize("dh,causal", [(128, True), (64, True), (128, False), (112, True), (48, False)])
 def test_attention_launch_shapes(ctx, monkeypatch, family, dh, causal):
     """Every family of workgroup shapes (key/query splits, merges through LDS) on a ragged
-    sequence that spans several streamed blocks; the library reads the override at each call."""
+    sequence that spans several streamed blocks; the library reads the override at each call.
+    Head sizes 112 and 48 run in the 128- and 64-wide tiles with the remaining columns held at zero
+    (112 = hidden 7168 over 64 heads, one of the paper's model shapes)."""
     monkeypatch.setenv("PMC_ATTN_SHAPE", family)
     batch, seq, heads = 2, 333, 2
     h = heads * dh

@@ -19,6 +19,8 @@ CASES = {
     "noncausal_f32": synth.ChunkCfg(layers=1, hidden=96, heads=3, ffn=256, seq=52, dtype="f32", causal=False),
     "dh128_bf16": synth.ChunkCfg(layers=2, hidden=256, heads=2, ffn=1024, seq=192, dtype="bf16"),
     "dh64_ragged_bf16": synth.ChunkCfg(layers=3, hidden=192, heads=3, ffn=328, seq=104, microbatch=2, dtype="bf16"),
+    # head size 112 (the paper's hidden 7168 over 64 heads): attention tiles 128 wide, 16 columns held at zero
+    "dh112_bf16": synth.ChunkCfg(layers=2, hidden=336, heads=3, ffn=512, seq=136, dtype="bf16"),
     # the workload bench.py times, at full size and in the launch configuration it runs in (large GEMM
     # tiles, 64x128 tiles, split K, short-sequence attention shapes, W pass on two streams): every
     # output and gradient element against the oracle (a few seconds of fp64 numpy)

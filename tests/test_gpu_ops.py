@@ -269,7 +269,7 @@ def test_gemm_rejects_bad_arguments(ctx):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("rows,h", [(37, 16), (64, 256), (5, 320), (1100, 1032), (130, 2048), (2100, 4096), (33, 5120), (9, 8192),
-                                    (7, 9000), (17, 10240), (6, 12288), (2, 12296)])
+                                    (7, 9000), (17, 10240), (6, 12288), (2, 12296), (4096, 5120)])
 def test_layernorm_forward_backward(ctx, dtype, rows, h):
     if h > (6144 if dtype == "f32" else 12288):
         # a wave keeps its row in registers: 24 vectors of 16 bytes per lane at most
@@ -406,6 +406,39 @@ def test_attention_long_sequence(ctx, monkeypatch, family):
     torch.cuda.synchronize()
     for name, cols in (("dq", slice(0, h)), ("dk", slice(h, 2 * h)), ("dv", slice(2 * h, 3 * h))):
         assert rel_l2(host(dq)[:, cols], dqkv_ref[:, cols]) <= tol("bf16"), name
+
+
+@pytest.mark.parametrize("seq,heads", [(4096, 40), (2048, 32), (1024, 16)])
+def test_attention_workload_shapes_sampled_heads(ctx, seq, heads):
+    """Attention at the full size of the three bf16 workloads (head size 128, causal), launched as the
+    passes launch it (the library's own choice of workgroup shapes for that many heads and blocks).
+    The dense oracle for all heads would need heads x seq^2 probabilities; three heads (first, last,
+    one in between) are checked in full instead, each as a one-head problem cut out of the packed
+    q|k|v rows: output, log-sum-exp and all three input gradients, every element."""
+    dh = 128
+    h = heads * dh
+    gen = torch.Generator(device="cuda").manual_seed(seq + heads)
+    bf = torch.bfloat16
+    qkv = torch.randn((seq, 3 * h), device="cuda", generator=gen).to(bf)
+    d_o = torch.randn((seq, h), device="cuda", generator=gen).to(bf)
+    o = torch.zeros((seq, h), device="cuda", dtype=bf)
+    lse = torch.zeros(heads * seq, device="cuda")
+    dq = torch.zeros_like(qkv)
+    print("attention workload shape", seq, heads, flush=True)
+    P.pmc_attention_forward(ctx, qkv, o, lse, 1, seq, heads, dh, True)
+    P.pmc_attention_backward(ctx, qkv, o, lse, d_o, dq, 1, seq, heads, dh, True)
+    torch.cuda.synchronize()
+    lse_h = host(lse).reshape(heads, seq)
+    for hd in (0, heads // 2 + 1, heads - 1):
+        cols = [slice(part * h + hd * dh, part * h + (hd + 1) * dh) for part in range(3)]
+        one = np.concatenate([host(qkv[:, c]) for c in cols], axis=1)              # [seq, 3 dh]: a one-head qkv
+        o_ref, probs, lse_ref = OL.attention(one, 1, True, 1)
+        g_ref = OL.attention_input_grad(host(d_o[:, hd * dh:(hd + 1) * dh]), one, probs, 1, 1)
+        del probs
+        assert rel_l2(host(o[:, hd * dh:(hd + 1) * dh]), o_ref) <= tol("bf16"), hd
+        assert np.abs(lse_h[hd] - lse_ref.reshape(-1)).max() <= 2e-2, hd
+        for part, name in enumerate(("dq", "dk", "dv")):
+            assert rel_l2(host(dq[:, cols[part]]), g_ref[:, part * dh:(part + 1) * dh]) <= tol("bf16"), (hd, name)
 
 
 @pytest.mark.parametrize("family", ["0", "1", "2"])

@@ -1,5 +1,6 @@
 // Fused flash-style attention for bf16 storage on the gfx950 matrix cores
-// (v_mfma_f32_32x32x16_bf16), head size 64 or 128, packed qkv [batch*seq, 3h].
+// (v_mfma_f32_32x32x16_bf16), packed qkv [batch*seq, 3h].  The tiles are 64 or 128 columns wide; a head
+// size that is another multiple of 8 runs in the next wider tile with the remaining columns at zero.
 //
 // Forward: a workgroup owns a block of queries of one head and streams blocks of K and V through
 // LDS (double buffered); its waves form a grid over (32-query group, key group).  Scores are

@@ -198,7 +198,10 @@ def test_microbatch_rows_are_independent_sequences():
 
 
 def test_activation_bytes_table():
-    """16 storage-typed [s,h] tensors + fp32 statistics per layer."""
+    """16 storage-typed [s,h] tensors + fp32 statistics per layer.  A pin to THIS repository's tensor
+    table (which tensors a unit holds between F and W), worked out by hand for the four workload
+    shapes, e.g. 16 * 128 * 256 * 4 + (4 + 4) * 128 * 4 = 2 101 248; the paper fixes only the number
+    of units (Section 2.2, Section 3.2), not the bytes of one."""
     assert O.chunk_activation_bytes(1, 256, 4, 128, 4) == 2101248
     assert O.chunk_activation_bytes(1, 2048, 16, 1024, 2) == 67190784
     assert O.chunk_activation_bytes(1, 4096, 32, 2048, 2) == 268730368

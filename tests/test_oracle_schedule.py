@@ -218,7 +218,9 @@ def test_appendix_f_literal_header_collides():
 
 
 def test_peak_bytes_table():
-    """Bytes follow units: pool bytes = units * m; tensor bytes differ only by dead statistics."""
+    """Bytes follow units: pool bytes = units * m; tensor bytes differ only by dead statistics (the
+    exact tensor-byte values are pinned by hand in test_peak_tensor_bytes_hand_derived).  m is this
+    repository's tensor table, not a number the paper prints."""
     from oracle.layer import chunk_activation_bytes, chunk_stats_bytes
     m = chunk_activation_bytes(2, 4096, 32, 2048, 2)
     st = chunk_stats_bytes(2, 32, 2048)
@@ -339,3 +341,147 @@ def test_adaptive_search_properties(d, n):
     assert spans and spans[-1] == 6 * n + d - 1
     assert S.adaptive_search(d, n, 1, max_delta=4) is None
 
+
+
+# --------------------------------------------------------------------------- hand-worked pins
+
+def test_peak_tensor_bytes_hand_derived():
+    """The tensor-byte track of peak_bytes, worked by hand from the d = 2 and d = 4 blocks of this
+    repository's tensor table (u = bytes of one unit, s = its fp32 statistics: a unit weighs u from
+    the start of its F, u - s once its B has ended, nothing once its W has ended).  This is a pin to
+    the project's own table (the paper pins units only, Section 3.2), chosen so that charging the
+    statistics' death to W instead of B, or never, fails:
+
+    V-Min, d = 2 (block F0 = [0,1], F1 = [3,2], B1 = [4,5], B0 = [7,6], W1 = [5,9], W0 = [8,10]),
+    device 1 runs  F0.0 F1.0 B1.0 B0.0 F0.1 F1.1 W1.0 W0.0 ...  and is fullest after F1.1: four
+    units live, two of them (microbatch 0) already through B -> 4u - 2s.  Device 0 runs
+    F0.0 F1.0 B1.0 W1.0 F0.1 ... and never holds more than the two fresh units after F1.0 -> 2u.
+    V-Min, d = 4, device 2 (F0 at 2, F1 at 5, B1 at 10, W1 at 12, B0 at 13, W0 at 15, + 6 j) runs
+    F0.0 F1.0 F0.1 B1.0 F1.1 W1.0 B0.0 F0.2 W0.0 ...: after F1.1 four units with B1.0 done -> 4u - s,
+    and again 4u - s after every later F; the other three devices reach four fresh units -> 4u.
+    1F1B, V-ZB and V-Half at d = 2 all reach their unit peak with fresh units only -> units * u."""
+    u, s = 1000, 7
+    want = {("1f1b", 2, 4): [4 * u, 2 * u], ("vzb", 2, 4): [4 * u, 4 * u], ("vhalf", 2, 4): [4 * u, 4 * u],
+            ("vmin", 2, 4): [2 * u, 4 * u - 2 * s], ("vmin", 4, 8): [4 * u, 4 * u, 4 * u - s, 4 * u]}
+    for (kind, d, n), tensor in want.items():
+        assert [t for _, t in S.peak_bytes(kind, d, n, u, s)] == tensor, (kind, d, n)
+
+
+def _grid(passes, d):
+    return [[f"{p.op}{p.chunk}.{p.mb}@{p.time}" for p in order] for order in S.device_orders(passes, d)]
+
+
+def test_reordering_hand_worked_grids():
+    """Appendix C's two greedy steps applied on paper to two tiny schedules (d = 2, n = 2; model chunk
+    of device 0: chunks 0 and 3, of device 1: chunks 1 and 2).  The paper prints no reordered order,
+    so these grids are this repository's reading of the two steps, worked by hand:
+
+    V-ZB.  Squeezed grid (unit times):
+        dev 0: F0.0@0 F0.1@1 -- F1.0@3 B1.0@4 W1.0@5 F1.1@6 B1.1@7 B0.0@8 W1.1@9 W0.0@10 B0.1@11 W0.1@12
+        dev 1: -- F0.0@1 F1.0@2 F0.1@3 F1.1@4 B1.0@5 B0.0@6 W1.0@7 W0.0@8 B1.1@9 B0.1@10 W1.1@11 W0.1@12
+      Warm-up: the vacant cells before a first B are cell 2 of device 0 and cell 0 of device 1; no
+      later pass has its dependencies done by then (F1.0 of device 0 needs device 1's F1.0, which ends
+      at 3), so nothing moves.  Cool-down: device 0 gives up W1.1 W0.0 W0.1 (those after its last F),
+      device 1 all four W; without them B1.1 / B0.1 of device 1 move up to cells 8 / 9 and B0.1 of
+      device 0 to cell 10; the freed cells are filled left to right with the first removed W whose B
+      has ended: device 0 gets W1.1@9, W0.0@11, W0.1@12, device 1 W1.0@7, W0.0@10, W1.1@11, W0.1@12.
+    V-Half.  Squeezed: dev 0 F0.0@0 F1.0@3 F0.1@4 B1.0@5 ..., dev 1 F0.0@1 F1.0@2 F0.1@5 F1.1@6 B1.0@7 ...
+      (finish 16).  Warm-up, column by column: cell 1 of device 0 takes F0.1 (no dependency; the peak
+      of 3 live units is kept); cell 3 of device 1 takes its F0.1 (device 0's now ends at 2); cell 4
+      of device 0 takes B1.0 and cell 4 of device 1 F1.1; cells 5 and 6 of device 1 take B1.0 and
+      B0.0.  Cool-down as above.  Finish 13 = 6 n + d - 1."""
+    assert _grid(S.reordered("vzb", 2, 2), 2) == [
+        "F0.0@0 F0.1@1 F1.0@3 B1.0@4 W1.0@5 F1.1@6 B1.1@7 B0.0@8 W1.1@9 B0.1@10 W0.0@11 W0.1@12".split(),
+        "F0.0@1 F1.0@2 F0.1@3 F1.1@4 B1.0@5 B0.0@6 W1.0@7 B1.1@8 B0.1@9 W0.0@10 W1.1@11 W0.1@12".split()]
+    assert _grid(S.reordered("vhalf", 2, 2), 2) == [
+        "F0.0@0 F0.1@1 F1.0@3 B1.0@4 W1.0@5 F1.1@6 B0.0@7 B1.1@8 W0.0@9 W1.1@10 B0.1@11 W0.1@12".split(),
+        "F0.0@1 F1.0@2 F0.1@3 F1.1@4 B1.0@5 B0.0@6 W1.0@7 W0.0@8 B1.1@9 B0.1@10 W1.1@11 W0.1@12".split()]
+
+
+def _independent_makespan(times, d, n, dur):
+    """Finish time of the squeezed schedule of a V-shape block, written independently of the oracle's
+    event loop: start times relaxed to a fixed point over 'after the previous pass of my device' and
+    'after the passes I depend on' (a longest-path computation)."""
+    rows = [("F", 0), ("F", 1), ("B", 1), ("B", 0), ("W", 1), ("W", 0)]
+    nodes = []                                    # (cell, device, op, model chunk, microbatch)
+    for (op, c), ts in zip(rows, times):
+        for i in range(d):
+            mc = i if c == 0 else 2 * d - 1 - i
+            nodes += [(ts[i] + 6 * j, i, op, mc, j) for j in range(n)]
+    nodes.sort()
+    prev_on_device, last = {}, {}
+    for nd in nodes:
+        prev_on_device[nd] = last.get(nd[1])
+        last[nd[1]] = nd
+    by_key = {(nd[2], nd[3], nd[4]): nd for nd in nodes}
+
+    def needs(nd):
+        _, _, op, mc, j = nd
+        if op == "F":
+            return [by_key[("F", mc - 1, j)]] if mc else []
+        if op == "B":
+            return [by_key[("F", mc, j)]] if mc == 2 * d - 1 else [by_key[("B", mc + 1, j)]]
+        return [by_key[("B", mc, j)]]
+
+    start = {nd: 0.0 for nd in nodes}
+    changed = True
+    while changed:
+        changed = False
+        for nd in nodes:
+            t = max([0.0] + [start[q] + dur[q[2]] for q in needs(nd) + ([prev_on_device[nd]] if prev_on_device[nd] else [])])
+            if t > start[nd]:
+                start[nd], changed = t, True
+    return max(start[nd] + dur[nd[2]] for nd in nodes)
+
+
+def test_adaptive_search_winner_is_optimal_by_second_brute_force():
+    """adaptive_search without the reordering step against a brute force written here with another
+    loop structure (one flat product over all eight parameters, block times by prefix sums, live
+    units counted from a sorted event list, finish time by longest-path relaxation): the oracle's
+    winner must have the least finish time of all feasible blocks, and be the first such block in the
+    documented visiting order.  Which block wins among equal finish times is this repository's own
+    rule (the paper's Appendix A states none)."""
+    import itertools
+    d, n, limit, md = 3, 6, 4, 2
+    dur = {"F": 1.0, "B": 1.25, "W": 0.75}
+    best = None
+    for K, a0, a1, b0, b1, ta, tb, tc in itertools.product(range(2, d + 1), range(1, md + 1), range(1, md + 1),
+                                                           range(1, md + 1), range(1, md + 1), range(1, 7), range(1, 7),
+                                                           range(1, 7)):
+        if K == d and (b0, b1) != (a0, a1):
+            continue                                # the uniform block is visited once
+        down = [a0 if i + 1 < K else b0 for i in range(d - 1)]
+        up = [a1 if i + 1 <= K else b1 for i in range(1, d)]
+        F0 = [sum(down[:i]) for i in range(d)]
+        F1 = [F0[-1] + ta + sum(up[i:]) for i in range(d)]
+        B1 = [F1[0] + tb + sum(down[:i]) for i in range(d)]
+        B0 = [B1[-1] + tc + sum(up[i:]) for i in range(d)]
+        W1, W0, ok = [], [], True
+        for i in range(d):
+            res = [F0[i] % 6, F1[i] % 6, B1[i] % 6, B0[i] % 6]
+            if len(set(res)) < 4:
+                ok = False
+                break
+            w1 = next(t for t in range(B1[i] + 1, B1[i] + 8) if t % 6 not in res)
+            w0 = next(t for t in range(B0[i] + 1, B0[i] + 8) if t % 6 not in res + [w1 % 6])
+            W1.append(w1)
+            W0.append(w0)
+        if not ok:
+            continue
+        peak = 0
+        for i in range(d):
+            events = sorted([(f + 6 * j, 1) for f in (F0[i], F1[i]) for j in range(n)] +
+                            [(w + 6 * j + 0.5, -1) for w in (W1[i], W0[i]) for j in range(n)])
+            live = 0
+            for _, delta in events:
+                live += delta
+                peak = max(peak, live)
+        if peak > limit:
+            continue
+        span = _independent_makespan([F0, F1, B1, B0, W1, W0], d, n, dur)
+        cand = (span, (K, a0, a1, b0, b1, ta, tb, tc))
+        if best is None or span < best[0] - 1e-12:
+            best = cand
+    got = S.adaptive_search(d, n, limit, dur["F"], dur["B"], dur["W"], max_delta=md, reorder=False)
+    assert got is not None and best is not None
+    assert abs(got[0] - best[0]) < 1e-9 and tuple(got[1]) == best[1]

@@ -18,6 +18,15 @@
  *  - Pointers named "device" are GPU memory, BORROWED from the caller: the library never allocates
  *    or frees device memory.  Everything else is host memory.
  *  - Work is enqueued on the HIP stream given to pmc_create and is asynchronous unless stated.
+ *    One exception inside a call: the bf16 W pass runs every second weight-gradient product and the
+ *    bias-gradient column sums on a second, non-blocking stream of default priority that the
+ *    context owns (created at first use).  The pass forks it from the context's stream with an
+ *    event when it starts and joins it back before it returns (also when a launch fails), so
+ *    everything the caller enqueues on the context's stream before or after the call is ordered
+ *    against all of the pass's work; nothing is ever left running on the second stream between
+ *    calls.  pmc_tuning_set("w_streams", 1) keeps the whole pass on the context's stream, and so
+ *    does tracing (pmc_trace_begin), whose per-operation events assume one stream: traced W times
+ *    are therefore those of the one-stream configuration.
  *  - Tensors are row-major.  Activations are [tokens, hidden] with tokens = microbatch * seq
  *    (sequences of one microbatch stored back to back).  Storage type is float (PMC_F32) or
  *    bfloat16 (PMC_BF16; all accumulation in fp32).  Gradients of parameters are always fp32.
@@ -92,6 +101,17 @@ typedef struct pmc_replay_report {
 
 const char* pmc_last_error(void);
 
+/* Tuning switches, process-wide (tests, kernel tuning): value -1 = the library decides.
+ *   "gemm_tile" 0..4 (256x256, 256x128, 128x128, 64x128, 256x320)   "gemm_group" 1..64 (tile walk)
+ *   "gemm_wgrad" 0|1 (persistent W kernel)   "gemm_persistent" 0|1 (persistent F/B kernel)
+ *   "attn_shape" 0..2 (launch family)   "attn_variant" 0..3   "w_streams" 1|2
+ * The environment variables PMC_GEMM_TILE, PMC_GEMM_GROUP, PMC_GEMM_WGRAD, PMC_GEMM_PERSISTENT,
+ * PMC_ATTN_SHAPE, PMC_ATTN_VARIANT, PMC_W_STREAMS give the initial values; they are read once, at
+ * the first use of any switch, never on a launch path.  PMC_ERR_INVALID for an unknown name or a
+ * value out of range. */
+int pmc_tuning_set(const char* name, int32_t value);
+int pmc_tuning_get(const char* name, int32_t* value);
+
 /* ---- context, pool, workspace --------------------------------------------------------------- */
 
 /* Creates a context bound to `hip_stream` (a hipStream_t, borrowed; NULL = default stream) on
@@ -156,6 +176,15 @@ int stage_backward_input(pmc_chunk* chunk, int32_t mb, const void* dy, void* dx)
  * ones agree to rounding, not bit for bit; fp32 mode runs the microbatches one after the other. */
 #define PMC_MAX_QUEUED_W 8
 int stage_backward_weight(pmc_chunk* chunk, const int32_t* mbs, int32_t count);
+
+/* Gives up a live microbatch of the chunk in whatever state it is (after F, after B, or reserved)
+ * and returns its slab to the pool: the way back to a clean pool after a pass has failed part-way.
+ * A pass that fails never leaves a half-taken unit behind by itself: stage_forward returns the
+ * slab it took, stage_backward_input and stage_backward_weight leave the microbatch in the state
+ * it had (its slab contents are then undefined: abandon it).  A failed schedule_replay returns
+ * every unit it still held.  Host-only; work already enqueued for the microbatch still runs, in
+ * stream order, before anything that reuses the slab.  PMC_ERR_STATE if `mb` is not live. */
+int stage_abandon(pmc_chunk* chunk, int32_t mb);
 
 /* ---- schedules (host only; no GPU needed) --------------------------------------------------- */
 

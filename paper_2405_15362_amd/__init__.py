@@ -79,6 +79,9 @@ _SIGS = {
     "stage_forward_on": (C.c_int, [_vp, _i32, _vp, _vp, _i32]),
     "stage_backward_input": (C.c_int, [_vp, _i32, _vp, _vp]),
     "stage_backward_weight": (C.c_int, [_vp, C.POINTER(_i32), _i32]),
+    "stage_abandon": (C.c_int, [_vp, _i32]),
+    "pmc_tuning_set": (C.c_int, [C.c_char_p, _i32]),
+    "pmc_tuning_get": (C.c_int, [C.c_char_p, C.POINTER(_i32)]),
     "pmc_schedule_build": (C.c_int, [_i32, _i32, _i32, C.POINTER(_vp)]),
     "pmc_schedule_build_vshape": (C.c_int, [_i32] * 7 + [C.POINTER(_vp)]),
     "pmc_schedule_reorder": (C.c_int, [_vp, C.POINTER(_vp)]),
@@ -223,6 +226,21 @@ def stage_backward_weight(chunk, mbs) -> None:
     mbs = list(mbs)
     arr = (_i32 * len(mbs))(*mbs)
     _check(lib.stage_backward_weight(chunk, arr, len(mbs)))
+
+
+def stage_abandon(chunk, mb: int) -> None:
+    _check(lib.stage_abandon(chunk, mb))
+
+
+def pmc_tuning_set(name: str, value: int = -1) -> None:
+    """Process-wide tuning switch (see pmc.h); -1 hands the choice back to the library."""
+    _check(lib.pmc_tuning_set(name.encode(), value))
+
+
+def pmc_tuning_get(name: str) -> int:
+    out = _i32()
+    _check(lib.pmc_tuning_get(name.encode(), C.byref(out)))
+    return out.value
 
 
 # ---- schedules (host only) ----------------------------------------------------------------------

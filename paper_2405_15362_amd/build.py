@@ -18,7 +18,7 @@ OUT = os.path.join(HERE, "libpmc.so")
 BUILD = os.path.join(ROOT, "_build")
 
 SOURCES = [
-    "error.cpp", "schedule.cpp", "api.cpp", "replay.cpp", "attention.cpp",
+    "error.cpp", "tuning.cpp", "schedule.cpp", "api.cpp", "replay.cpp", "attention.cpp",
     "norm_act.hip", "gemm_f32.hip", "gemm_bf16.hip", "attn_simple.hip", "attn_mfma.hip",
 ]
 # hipcc would by itself turn fp32 pairs into packed-fp32 instructions; they are kept off.

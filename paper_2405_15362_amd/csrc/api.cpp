@@ -258,6 +258,8 @@ k::GemmArgs gemm_args(const pmc_chunk* ch, bool ta, bool tb, int M, int N, int K
 
 }  // namespace
 
+int chunk_release(pmc_chunk* ch, int32_t mb);
+
 // Takes the slab for (chunk, mb) without running anything (1F1B: a stage takes both its chunks'
 // units when its F starts).
 int chunk_reserve(pmc_chunk* ch, int32_t mb, int device) {
@@ -279,14 +281,17 @@ int chunk_forward(pmc_chunk* ch, int32_t mb, const void* x, void* y, int device)
   auto it = ch->live.find(mb);
   if (it != ch->live.end() && it->second.state != kReserved)
     return fail(PMC_ERR_STATE, "stage_forward: microbatch %d is already live in this chunk", mb);
+  bool reserved_here = false;
   if (it == ch->live.end()) {
     PMC_TRY(chunk_reserve(ch, mb, device));
     it = ch->live.find(mb);
+    reserved_here = true;
   }
   Micro& m = it->second;
   const pmc_chunk_cfg& c = ch->cfg;
   hipStream_t st = ch->ctx->stream;
   const int T = ch->tokens, h = c.hidden, f = c.ffn, L = c.layers;
+  auto layers = [&]() -> int {
   for (int l = 0; l < L; ++l) {
     const LayerOffsets& o = ch->off[l];
     char* s = m.slab;
@@ -307,6 +312,16 @@ int chunk_forward(pmc_chunk* ch, int32_t mb, const void* x, void* y, int device)
     void* out = l == L - 1 ? y : (void*)(s + ch->off[l + 1].x);
     PMC_TRY(t_gemm(ch->ctx, PMC_F, gemm_args(ch, false, false, T, h, f, s + o.g, f, P(ch, l, W_2), h, out, h, PMC_EPI_BIAS_RESID,
                                   P(ch, l, B_2), s + o.xmid), ch->wsl));
+  }
+  return PMC_OK;
+  };
+  const int rc = layers();
+  if (rc != PMC_OK) {
+    // a launch failed part-way: the unit this call took goes back to the pool (kernels already
+    // enqueued only write inside the slab, which nothing else uses before they have run: the stream
+    // orders them); a unit reserved earlier by the replayer stays reserved for the replayer to return
+    if (reserved_here) (void)chunk_release(ch, mb);
+    return rc;
   }
   m.state = kForwardDone;
   return PMC_OK;
@@ -377,12 +392,11 @@ int chunk_backward_input(pmc_chunk* ch, int32_t mb, const void* dy, void* dx) {
 // then share the chip, one product's read-modify-write of dW overlaps the other's matrix work, the
 // tail of one fills with the head of the next, and the memory-bound bias-gradient sums run under a
 // product (measured on the W pass: -5 % at hidden 2048 / 1024 tokens, -6 % at 4096 / 2048, -5 % at
-// 5120 / 4096; a third and fourth stream gain nothing more).  PMC_W_STREAMS=1|2 forces the choice.
+// 5120 / 4096; a third and fourth stream gain nothing more).  The w_streams tuning switch forces the choice.
 // Off while tracing, whose per-operation events assume one stream.
 int w_pass_streams(const pmc_chunk* ch) {
   if (ch->ctx->tracing || ch->cfg.dtype != PMC_BF16) return 1;
-  if (const char* f = std::getenv("PMC_W_STREAMS"))
-    if ((f[0] == '1' || f[0] == '2') && f[1] == 0) return f[0] - '0';
+  if (const int f = tuning(kTuneWStreams); f >= 0) return f;
   return 2;
 }
 
@@ -396,6 +410,20 @@ int side_streams(pmc_ctx* ctx, int n) {
       return fail(PMC_ERR_HIP, "cannot create a side stream of the W pass");
   }
   return PMC_OK;
+}
+
+// Makes the context's stream wait for the first n side streams.  `rc` is what the forked work
+// returned: a failure there is reported in preference to one here; if the join itself cannot be
+// enqueued the side streams are drained on the host instead.
+int join_side_streams(pmc_ctx* ctx, int n, int rc) {
+  bool ok = true;
+  for (int i = 0; i < n; ++i)
+    if (hipEventRecord(ctx->join[i], ctx->side[i]) != hipSuccess || hipStreamWaitEvent(ctx->stream, ctx->join[i], 0) != hipSuccess) {
+      ok = false;
+      (void)hipStreamSynchronize(ctx->side[i]);
+    }
+  if (rc != PMC_OK) return rc;
+  return ok ? (int)PMC_OK : fail(PMC_ERR_HIP, "stage_backward_weight: cannot join a side stream");
 }
 
 int chunk_backward_weight_one(pmc_chunk* ch, int32_t mb, bool release) {
@@ -427,31 +455,35 @@ int chunk_backward_weight_one(pmc_chunk* ch, int32_t mb, bool release) {
     g.ws_bytes = 0;
     return k::gemm(ctx->side[which - 1], g);
   };
-  for (int l = L - 1; l >= 0; --l) {
-    const LayerOffsets& o = ch->off[l];
-    const void* dxout = s + (l == L - 1 ? ch->off[0].x : ch->off[l + 1].x);
-    // the four bias gradients of the layer in one launch
-    k::ColumnSumJobs jobs = {};
-    jobs.count = 4;
-    const void* src[4] = {dxout, s + o.u, s + o.xmid, s + o.qkv};
-    const int width[4] = {h, f, h, 3 * h};
-    const int which[4] = {B_2, B_1, B_O, B_QKV};
-    for (int j = 0; j < 4; ++j) {
-      jobs.a[j] = src[j];
-      jobs.out[j] = G(ch, l, which[j]);
-      jobs.n[j] = jobs.lda[j] = width[j];
+  auto products = [&]() -> int {
+    for (int l = L - 1; l >= 0; --l) {
+      const LayerOffsets& o = ch->off[l];
+      const void* dxout = s + (l == L - 1 ? ch->off[0].x : ch->off[l + 1].x);
+      // the four bias gradients of the layer in one launch
+      k::ColumnSumJobs jobs = {};
+      jobs.count = 4;
+      const void* src[4] = {dxout, s + o.u, s + o.xmid, s + o.qkv};
+      const int width[4] = {h, f, h, 3 * h};
+      const int which[4] = {B_2, B_1, B_O, B_QKV};
+      for (int j = 0; j < 4; ++j) {
+        jobs.a[j] = src[j];
+        jobs.out[j] = G(ch, l, which[j]);
+        jobs.n[j] = jobs.lda[j] = width[j];
+      }
+      // (memory-bound, no matrix work: on the second stream it runs under the first product)
+      PMC_TRY(traced(ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sums(two ? ctx->side[ns - 2] : st, c.dtype, T, jobs); }));
+      PMC_TRY(side_gemm(gemm_args(ch, true, false, f, h, T, s + o.g, f, dxout, h, G(ch, l, W_2), h, PMC_EPI_ACCUM_F32)));
+      PMC_TRY(side_gemm(gemm_args(ch, true, false, h, f, T, s + o.c, h, s + o.u, f, G(ch, l, W_1), f, PMC_EPI_ACCUM_F32)));
+      PMC_TRY(side_gemm(gemm_args(ch, true, false, h, h, T, s + o.o, h, s + o.xmid, h, G(ch, l, W_O), h, PMC_EPI_ACCUM_F32)));
+      PMC_TRY(side_gemm(gemm_args(ch, true, false, h, 3 * h, T, s + o.a, h, s + o.qkv, 3 * h, G(ch, l, W_QKV), 3 * h,
+                                  PMC_EPI_ACCUM_F32)));
     }
-    // (memory-bound, no matrix work: on the second stream it runs under the first product)
-    PMC_TRY(traced(ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sums(two ? ctx->side[ns - 2] : st, c.dtype, T, jobs); }));
-    PMC_TRY(side_gemm(gemm_args(ch, true, false, f, h, T, s + o.g, f, dxout, h, G(ch, l, W_2), h, PMC_EPI_ACCUM_F32)));
-    PMC_TRY(side_gemm(gemm_args(ch, true, false, h, f, T, s + o.c, h, s + o.u, f, G(ch, l, W_1), f, PMC_EPI_ACCUM_F32)));
-    PMC_TRY(side_gemm(gemm_args(ch, true, false, h, h, T, s + o.o, h, s + o.xmid, h, G(ch, l, W_O), h, PMC_EPI_ACCUM_F32)));
-    PMC_TRY(side_gemm(gemm_args(ch, true, false, h, 3 * h, T, s + o.a, h, s + o.qkv, 3 * h, G(ch, l, W_QKV), 3 * h,
-                                PMC_EPI_ACCUM_F32)));
-  }
-  for (int i = 0; i < ns - 1; ++i)
-    if (hipEventRecord(ctx->join[i], ctx->side[i]) != hipSuccess || hipStreamWaitEvent(st, ctx->join[i], 0) != hipSuccess)
-      return fail(PMC_ERR_HIP, "stage_backward_weight: cannot join a side stream");
+    return PMC_OK;
+  };
+  // whatever happened in between, the caller's stream waits for the side stream: a failed pass must
+  // not leave work on it that still reads the slab or writes the gradients
+  const int rc = products();
+  PMC_TRY(join_side_streams(ctx, ns - 1, rc));
   if (release) {
     ch->ctx->pool.give(m.slab, m.device, (int64_t)(ch->unit_bytes - ch->stats_bytes));
     ch->live.erase(it);
@@ -487,30 +519,33 @@ int chunk_backward_weight_group(pmc_chunk* ch, const int32_t* mbs, int count) {
     const int variant = 1 | (PMC_EPI_ACCUM_F32 << 2);
     return traced(ctx, PMC_OP_GEMM, PMC_W, M, N, T * count, variant, [&] { return k::gemm_bf16_grouped_wgrad(on, g); });
   };
-  for (int l = L - 1; l >= 0; --l) {
-    const LayerOffsets& o = ch->off[l];
-    const size_t dxout_off = l == L - 1 ? ch->off[0].x : ch->off[l + 1].x;
-    for (int i = 0; i < count; ++i) {
-      char* s = slab[i];
-      k::ColumnSumJobs jobs = {};
-      jobs.count = 4;
-      const void* src[4] = {s + dxout_off, s + o.u, s + o.xmid, s + o.qkv};
-      const int width[4] = {h, f, h, 3 * h};
-      const int which[4] = {B_2, B_1, B_O, B_QKV};
-      for (int j = 0; j < 4; ++j) {
-        jobs.a[j] = src[j];
-        jobs.out[j] = G(ch, l, which[j]);
-        jobs.n[j] = jobs.lda[j] = width[j];
+  auto products = [&]() -> int {
+    for (int l = L - 1; l >= 0; --l) {
+      const LayerOffsets& o = ch->off[l];
+      const size_t dxout_off = l == L - 1 ? ch->off[0].x : ch->off[l + 1].x;
+      for (int i = 0; i < count; ++i) {
+        char* s = slab[i];
+        k::ColumnSumJobs jobs = {};
+        jobs.count = 4;
+        const void* src[4] = {s + dxout_off, s + o.u, s + o.xmid, s + o.qkv};
+        const int width[4] = {h, f, h, 3 * h};
+        const int which[4] = {B_2, B_1, B_O, B_QKV};
+        for (int j = 0; j < 4; ++j) {
+          jobs.a[j] = src[j];
+          jobs.out[j] = G(ch, l, which[j]);
+          jobs.n[j] = jobs.lda[j] = width[j];
+        }
+        PMC_TRY(traced(ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sums(ns > 1 ? ctx->side[0] : st, c.dtype, T, jobs); }));
       }
-      PMC_TRY(traced(ctx, PMC_OP_COLSUM, PMC_W, T, 0, 0, 0, [&] { return k::column_sums(ns > 1 ? ctx->side[0] : st, c.dtype, T, jobs); }));
+      PMC_TRY(grouped(f, h, [&](char* s) { return s + o.g; }, f, [&](char* s) { return s + dxout_off; }, h, G(ch, l, W_2)));
+      PMC_TRY(grouped(h, f, [&](char* s) { return s + o.c; }, h, [&](char* s) { return s + o.u; }, f, G(ch, l, W_1)));
+      PMC_TRY(grouped(h, h, [&](char* s) { return s + o.o; }, h, [&](char* s) { return s + o.xmid; }, h, G(ch, l, W_O)));
+      PMC_TRY(grouped(h, 3 * h, [&](char* s) { return s + o.a; }, h, [&](char* s) { return s + o.qkv; }, 3 * h, G(ch, l, W_QKV)));
     }
-    PMC_TRY(grouped(f, h, [&](char* s) { return s + o.g; }, f, [&](char* s) { return s + dxout_off; }, h, G(ch, l, W_2)));
-    PMC_TRY(grouped(h, f, [&](char* s) { return s + o.c; }, h, [&](char* s) { return s + o.u; }, f, G(ch, l, W_1)));
-    PMC_TRY(grouped(h, h, [&](char* s) { return s + o.o; }, h, [&](char* s) { return s + o.xmid; }, h, G(ch, l, W_O)));
-    PMC_TRY(grouped(h, 3 * h, [&](char* s) { return s + o.a; }, h, [&](char* s) { return s + o.qkv; }, 3 * h, G(ch, l, W_QKV)));
-  }
-  if (ns > 1 && (hipEventRecord(ctx->join[0], ctx->side[0]) != hipSuccess || hipStreamWaitEvent(st, ctx->join[0], 0) != hipSuccess))
-    return fail(PMC_ERR_HIP, "stage_backward_weight: cannot join the second stream");
+    return PMC_OK;
+  };
+  const int rc = products();
+  PMC_TRY(join_side_streams(ctx, ns > 1 ? 1 : 0, rc));
   for (int i = 0; i < count; ++i) {
     auto it = ch->live.find(mbs[i]);
     ctx->pool.give(it->second.slab, it->second.device, (int64_t)(ch->unit_bytes - ch->stats_bytes));
@@ -528,6 +563,11 @@ int chunk_release(pmc_chunk* ch, int32_t mb) {
   ch->ctx->pool.give(m.slab, m.device, rest);
   ch->live.erase(it);
   return PMC_OK;
+}
+
+// Returns every live slab of the chunk, whatever its state (after a failed replay).
+void chunk_release_all(pmc_chunk* ch) {
+  while (!ch->live.empty()) (void)chunk_release(ch, ch->live.begin()->first);
 }
 
 size_t chunk_unit_bytes(const pmc_chunk* ch) { return ch->unit_bytes; }
@@ -673,6 +713,11 @@ int stage_forward_on(pmc_chunk* ch, int32_t mb, const void* x, void* y, int32_t 
   return chunk_forward(ch, mb, x, y, device);
 }
 int stage_backward_input(pmc_chunk* ch, int32_t mb, const void* dy, void* dx) { return chunk_backward_input(ch, mb, dy, dx); }
+
+int stage_abandon(pmc_chunk* ch, int32_t mb) {
+  if (!ch) return fail(PMC_ERR_INVALID, "stage_abandon: chunk is NULL");
+  return chunk_release(ch, mb);
+}
 
 int stage_backward_weight(pmc_chunk* ch, const int32_t* mbs, int32_t count) {
   PMC_TRY(ready(ch, "stage_backward_weight"));

@@ -629,19 +629,10 @@ __global__ __launch_bounds__(KG * QG * 128, KG * QG == 2 ? 3 : 1) void attn_bwd_
   }
 }
 
-template <typename K>
-int reserve_lds(K kern, size_t bytes, bool& done, const char* what) {
-  if (done) return PMC_OK;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-  if (e != hipSuccess) return fail(PMC_ERR_HIP, "%s: cannot reserve %zu bytes of LDS: %s", what, bytes, hipGetErrorString(e));
-  done = true;
-  return PMC_OK;
-}
-
 template <int DH, int QW, int KW, int NKT, bool PAD>
 int fwd_launch(hipStream_t st, int batch, int seq, int heads, int dh, int causal, const void* qkv, void* o, float* lse) {
   constexpr size_t lds = 2 * sizeof(bf16_t) * 32 * NKT * KW * 2 * DH;
-  static bool done = false;
+  static std::atomic<bool> done{false};
   if (int rc = reserve_lds(attn_fwd_mfma<DH, QW, KW, NKT, PAD>, lds, done, "attention_forward")) return rc;
   const float scale_log2 = kLog2e / sqrtf((float)dh);
   attn_fwd_mfma<DH, QW, KW, NKT, PAD><<<dim3(heads * batch, (seq + 32 * QW - 1) / (32 * QW)), dim3(QW * KW * 64), lds, st>>>(
@@ -654,11 +645,9 @@ int fwd_launch(hipStream_t st, int batch, int seq, int heads, int dh, int causal
 // Few (128-query block, head) pairs: 64-query workgroups whose 8 waves split 128-key blocks four
 // ways, so that every compute unit gets work; otherwise 128-query workgroups of 4 waves, each
 // taking whole 64-key blocks, two workgroups to a compute unit.
-// PMC_ATTN_SHAPE=0|1|2 in the environment forces a family of launch shapes (tests and tuning).
+// The attn_shape tuning switch (0|1|2) forces a family of launch shapes (tests and tuning).
 int shape_family(int batch, int seq, int heads) {
-  if (const char* f = std::getenv("PMC_ATTN_SHAPE")) {
-    if (f[0] >= '0' && f[0] <= '2' && f[1] == 0) return f[0] - '0';
-  }
+  if (const int f = tuning(kTuneAttnShape); f >= 0) return f;
   return (long)((seq + 127) / 128) * heads * batch < 512 ? 0 : 1;
 }
 
@@ -677,7 +666,7 @@ int bwd_launch(hipStream_t st, int batch, int seq, int heads, int dh, int causal
   constexpr size_t merge_dkv = QG > 1 ? (size_t)2 * KG * (DH / 2) * 64 * sizeof(float) : 0;
   constexpr size_t lds_dkv = tiles_dkv > merge_dkv ? tiles_dkv : merge_dkv;
   static_assert(lds_dq <= 160 * 1024 && lds_dkv <= 160 * 1024, "tiles exceed the LDS of a compute unit");
-  static bool done_dq = false, done_dkv = false;
+  static std::atomic<bool> done_dq{false}, done_dkv{false};
   if (int rc = reserve_lds(attn_bwd_dq_mfma<DH, QW, KW, NKT, PAD>, lds_dq, done_dq, "attention_backward")) return rc;
   if (int rc = reserve_lds(attn_bwd_dkv_mfma<DH, KG, QG, PAD>, lds_dkv, done_dkv, "attention_backward")) return rc;
   const float scale = 1.0f / sqrtf((float)dh), scale_log2 = kLog2e * scale;

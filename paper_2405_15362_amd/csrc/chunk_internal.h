@@ -10,6 +10,7 @@ int chunk_forward(pmc_chunk* ch, int32_t mb, const void* x, void* y, int device)
 int chunk_backward_input(pmc_chunk* ch, int32_t mb, const void* dy, void* dx);
 int chunk_backward_weight_one(pmc_chunk* ch, int32_t mb, bool release);
 int chunk_release(pmc_chunk* ch, int32_t mb);
+void chunk_release_all(pmc_chunk* ch);
 size_t chunk_unit_bytes(const pmc_chunk* ch);
 size_t chunk_stats_bytes(const pmc_chunk* ch);
 size_t chunk_workspace_bytes(const pmc_chunk* ch);

@@ -55,6 +55,7 @@ struct GemmParams {
   const bf16_t* Aseg[kMaxSegments];
   const bf16_t* Bseg[kMaxSegments];
   int nseg, seg_tiles;
+  int phase_by_xcd;  // persistent weight-gradient kernel: phase groups are whole XCDs (1) or alternate inside one (0)
 };
 
 constexpr int kEpiPartial = 100;  // fast path, split K: store the fp32 partial product of split blockIdx.y
@@ -393,7 +394,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmParams p, const 
 // tiles an XCD works on at a time are then a block of group_m x 32/group_m tiles, whose operand
 // panels (group_m BM rows of A, 32/group_m BN rows of B per K step) are what that XCD's L2 has to
 // fetch.  Measured on whole steps: 4 for the 256-row tiles (+1 % at hidden 4096 over 8, nothing at
-// 5120), 8 for the smaller ones (4 costs the 64 x 128 products 2 %).  PMC_GEMM_GROUP forces a height.
+// 5120), 8 for the smaller ones (4 costs the 64 x 128 products 2 %).  The gemm_group tuning switch forces a height.
 __device__ __forceinline__ void tile_of_pid(const GemmParams& p, int pid, int& tile_m, int& tile_n) {
   const int ntiles = p.tiles_m * p.tiles_n;
   const int xcd = pid & 7, local = pid >> 3, lo = ntiles >> 3, rem = ntiles & 7;
@@ -639,7 +640,9 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_bf16_wgrad_persis
   extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
   const int ntiles = p.tiles_m * p.tiles_n, G = gridDim.x, b = blockIdx.x;
   const int nk = p.k_tiles_per_split;  // all of K
-  const int group = (b >> 3) % GROUPS;  // neighbours on one XCD fall into different groups
+  // which phase group: alternating inside an XCD (neighbours differ), or a whole XCD per group (the
+  // workgroups that share an L2 then walk their operand panels in step)
+  const int group = (p.phase_by_xcd ? (b & 7) : (b >> 3)) % GROUPS;
   const int head = (nk * group) / GROUPS;  // K tiles of the first tile left for the end
   bool first = true;
   int tm0 = 0, tn0 = 0;
@@ -735,12 +738,8 @@ int launch(hipStream_t st, GemmParams p) {
   constexpr size_t lds = 2 * sizeof(bf16_t) * (Tile<BM, BK, A_KMAJ>::elems + Tile<BN, BK, B_KMAJ>::elems);
   static_assert(lds <= 160 * 1024, "tile does not fit the 160 KB LDS");
   auto kern = gemm_bf16_kernel<BM, BN, BK, WM, WN, A_KMAJ, B_KMAJ, EPI>;
-  static bool configured = false;  // per instantiation
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return fail(PMC_ERR_HIP, "gemm_bf16: cannot reserve %zu bytes of LDS: %s", lds, hipGetErrorString(e));
-    configured = true;
-  }
+  static std::atomic<bool> configured{false};  // per instantiation
+  if (int rc = reserve_lds(kern, lds, configured, "gemm_bf16")) return rc;
   p.tiles_m = (p.M + BM - 1) / BM;
   p.tiles_n = (p.N + BN - 1) / BN;
   p.group_m = 8;
@@ -776,16 +775,12 @@ int launch_dma(hipStream_t st, GemmParams p) {
   constexpr size_t lds = (size_t)NSTAGE * (BM + BN) * 64 * sizeof(bf16_t);
   static_assert(lds <= 160 * 1024, "stages do not fit the 160 KB LDS");
   auto kern = gemm_bf16_dma_kernel<BM, BN, WAVES_M, WAVES_N, A_KMAJ, B_KMAJ, NSTAGE, EPI, SEG>;
-  static bool configured = false;  // per instantiation
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return fail(PMC_ERR_HIP, "gemm_bf16: cannot reserve %zu bytes of LDS: %s", lds, hipGetErrorString(e));
-    configured = true;
-  }
+  static std::atomic<bool> configured{false};  // per instantiation
+  if (int rc = reserve_lds(kern, lds, configured, "gemm_bf16")) return rc;
   p.tiles_m = (p.M + BM - 1) / BM;
   p.tiles_n = (p.N + BN - 1) / BN;
   {
-    static const int forced = [] { const char* f = std::getenv("PMC_GEMM_GROUP"); return f ? std::atoi(f) : 0; }();
+    const int forced = tuning(kTuneGemmGroup);
     p.group_m = forced > 0 ? forced : (BM >= 256 ? 4 : 8);
   }
   const int splits = (p.K / 64) / p.k_tiles_per_split;
@@ -802,11 +797,9 @@ int launch_dma(hipStream_t st, GemmParams p) {
 //   3: 64x128, 4 waves, 3 stages (skinny outputs: twice the tiles of shape 2)
 //   4: 256x320, 8 waves, 2 stages (N a multiple of 320 whose 256-wide tiles would leave a ragged last
 //      round, e.g. 4096 x 5120 = exactly 256 tiles)
-// PMC_GEMM_TILE=0|1|2|3|4 in the environment forces a shape (for tests and tuning).
+// The gemm_tile tuning switch (0..4) forces a shape (for tests and tuning).
 int pick_tile(int M, int N, bool wide_ok) {
-  if (const char* f = std::getenv("PMC_GEMM_TILE")) {
-    if (f[0] >= '0' && f[0] <= '4' && f[1] == 0) return (f[0] == '4' && !wide_ok) ? 0 : f[0] - '0';
-  }
+  if (const int f = tuning(kTuneGemmTile); f >= 0) return (f == 4 && !wide_ok) ? 0 : f;
   const int bm[5] = {256, 256, 128, 64, 256}, bn[5] = {256, 128, 128, 128, 320};
   const double rate[5] = {1.0, 0.95, 0.75, 0.6, 1.0};
   int best = 0;
@@ -840,12 +833,24 @@ int launch_dma_tile(hipStream_t st, const GemmParams& p) {
   }
 }
 
+// Compute units of the current device, asked once (0 if the query fails).
+int compute_units() {
+  static std::atomic<int> units{0};
+  int u = units.load(std::memory_order_relaxed);
+  if (u > 0) return u;
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 0;
+  units.store(prop.multiProcessorCount, std::memory_order_relaxed);
+  return prop.multiProcessorCount;
+}
+
 // Persistent, phase-shifted weight-gradient kernel: when every compute unit gets at least two
-// 256x256 tiles.  PMC_GEMM_WGRAD=0|1 in the environment forces the choice (tests, tuning).
+// 256x256 tiles.  The gemm_wgrad tuning switch (0|1) forces the choice (tests, tuning).
 bool use_wgrad_persistent(const GemmParams& p) {
   if (p.K < 4 * 64) return false;
-  if (const char* f = std::getenv("PMC_GEMM_WGRAD")) return f[0] == '1';
-  if (std::getenv("PMC_GEMM_TILE")) return false;
+  if (const int f = tuning(kTuneGemmWgrad); f >= 0) return f == 1;
+  if (tuning(kTuneGemmTile) >= 0) return false;
   return (long)((p.M + 255) / 256) * ((p.N + 255) / 256) >= 2 * 256;
 }
 
@@ -854,21 +859,14 @@ int launch_wgrad_persistent(hipStream_t st, GemmParams p) {
   constexpr int NSTAGE = 2, GROUPS = 2;  // measured: 2 phases give the most (1: -6 % W-pass time, 2: -8 %, 4 and 8: -7 %)
   constexpr size_t lds = (size_t)NSTAGE * (256 + 256) * 64 * sizeof(bf16_t);
   auto kern = gemm_bf16_wgrad_persistent_kernel<256, 256, 2, 4, NSTAGE, GROUPS, SEG>;
-  static bool configured = false;
-  static int units = 0;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return fail(PMC_ERR_HIP, "gemm_bf16: cannot reserve %zu bytes of LDS: %s", lds, hipGetErrorString(e));
-    int dev = 0;
-    hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
-      return fail(PMC_ERR_HIP, "gemm_bf16: cannot query the device");
-    units = prop.multiProcessorCount;
-    configured = true;
-  }
+  static std::atomic<bool> configured{false};
+  if (int rc = reserve_lds(kern, lds, configured, "gemm_bf16")) return rc;
+  const int units = compute_units();
+  if (units <= 0) return fail(PMC_ERR_HIP, "gemm_bf16: cannot query the device");
   p.tiles_m = (p.M + 255) / 256;
   p.tiles_n = (p.N + 255) / 256;
   p.group_m = 8;
+  p.phase_by_xcd = tuning(kTuneWgradPhase) == 1;
   const int ntiles = p.tiles_m * p.tiles_n;
   int grid = ntiles < units ? ntiles : units;
   if (grid >= 8) grid &= ~7;  // whole rounds over the 8 XCDs keep a workgroup's tiles on one XCD
@@ -883,7 +881,7 @@ int launch_wgrad_persistent(hipStream_t st, GemmParams p) {
 // writes an fp32 partial product to the workspace and a second kernel adds them and applies the
 // epilogue.  Returns 1 when splitting does not pay or does not fit.
 int pick_splits(int M, int N, int K, size_t ws_bytes) {
-  if (std::getenv("PMC_GEMM_TILE")) return 1;
+  if (tuning(kTuneGemmTile) >= 0) return 1;
   const long tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
   if (tiles >= 192) return 1;
   // up to K = 6144 the 64x128 tiles (no partials, no second kernel) are faster once there are
@@ -975,6 +973,7 @@ int gemm_bf16(hipStream_t st, const GemmArgs& a) {
   p.group_m = 8;
   p.k_tiles_per_split = 0;
   p.nseg = p.seg_tiles = 0;
+  p.phase_by_xcd = 0;
   for (int i = 0; i < kMaxSegments; ++i) p.Aseg[i] = p.Bseg[i] = nullptr;
   const bool a_kmaj = !a.trans_a, b_kmaj = a.trans_b;
   // Fast path: K in whole 64-wide tiles, operands inside the 2 GB window of a buffer descriptor.
@@ -1017,6 +1016,7 @@ int gemm_bf16_grouped_wgrad(hipStream_t st, const GroupedWgradArgs& a) {
   p.k_tiles_per_split = p.K / 64;
   p.nseg = a.count;
   p.seg_tiles = a.K / 64;
+  p.phase_by_xcd = 0;
   for (int i = 0; i < kMaxSegments; ++i) {
     const int j = i < a.count ? i : a.count - 1;
     if (!a.A[j] || !a.B[j] || !aligned(a.A[j], 16) || !aligned(a.B[j], 16))

@@ -3,10 +3,23 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include "pmc_internal.h"
 
 namespace pmc {
 namespace k {
+
+// One-time reservation of a kernel's dynamic LDS, reachable from several host threads at once: the
+// flag is atomic and the attribute call is idempotent, so a race at first use only repeats the call.
+template <typename Kern>
+int reserve_lds(Kern kern, size_t bytes, std::atomic<bool>& done, const char* what) {
+  if (done.load(std::memory_order_acquire)) return PMC_OK;
+  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e != hipSuccess) return fail(PMC_ERR_HIP, "%s: cannot reserve %zu bytes of LDS: %s", what, bytes, hipGetErrorString(e));
+  done.store(true, std::memory_order_release);
+  return PMC_OK;
+}
 
 struct GemmArgs {
   int dtype = PMC_BF16;
@@ -66,7 +79,6 @@ int layernorm_backward(hipStream_t stream, int dtype, int rows, int h, const voi
                        const void* gain, const float* mean, const float* rstd, const void* resid, void* dx,
                        float* dgain, float* dbias, float* partial, LnPartialJobs* defer = nullptr);
 int layernorm_backward_reduce(hipStream_t stream, int h, const LnPartialJobs& jobs);
-
 int attention_forward(hipStream_t stream, int dtype, int batch, int seq, int heads, int head_dim, int causal,
                       const void* qkv, void* o, float* lse);
 // scratch: dq staging [batch*seq, heads*head_dim] in the storage type, then delta fp32 [batch, heads, seq].

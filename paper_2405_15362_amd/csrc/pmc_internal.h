@@ -14,6 +14,11 @@ namespace pmc {
 // Records a message for pmc_last_error() and returns `code`.
 int fail(int code, const char* fmt, ...);
 
+// Tuning switches (tuning.cpp): -1 = the library decides.
+enum Tuning { kTuneGemmTile, kTuneGemmGroup, kTuneGemmWgrad, kTuneAttnShape, kTuneWStreams, kTuneGemmPersistent,
+              kTuneAttnVariant, kTuneWgradPhase, kTuneCount };
+int tuning(Tuning t);
+
 struct Schedule {
   int kind = -1;  // pmc_kind, or -1 for a custom V-shape block
   int d = 0, n = 0;

@@ -88,6 +88,7 @@ int schedule_replay(pmc_ctx* ctx, const pmc_schedule* sched, pmc_chunk* const* c
   std::vector<int> fwd_buf((size_t)nchunks * n, -1), bwd_buf((size_t)nchunks * n, -1);
   int transit_live = 0, transit_peak = 0;
   auto take_buf = [&]() {
+    if (free_bufs.empty()) return -1;  // cannot happen for a schedule max_transit() was computed from
     int b = free_bufs.back();
     free_bufs.pop_back();
     ++transit_live;
@@ -103,7 +104,13 @@ int schedule_replay(pmc_ctx* ctx, const pmc_schedule* sched, pmc_chunk* const* c
   const bool time_passes = (flags & PMC_REPLAY_TIME_PASSES) != 0;
   hipEvent_t ev_begin = nullptr, ev_end = nullptr;
   std::vector<hipEvent_t> ev;
+  bool running = false;  // passes are in flight: a failure must hand every held unit back
   auto cleanup = [&]() {
+    if (running) {
+      (void)hipStreamSynchronize(st);
+      for (int c = 0; c < nchunks; ++c) chunk_release_all(chunks[c]);
+      running = false;
+    }
     if (ev_begin) (void)hipEventDestroy(ev_begin);
     if (ev_end) (void)hipEventDestroy(ev_end);
     for (hipEvent_t e : ev) (void)hipEventDestroy(e);
@@ -128,6 +135,7 @@ int schedule_replay(pmc_ctx* ctx, const pmc_schedule* sched, pmc_chunk* const* c
   REPLAY_HIP(hipEventRecord(ev_begin, st));
   if (time_passes) REPLAY_HIP(hipEventRecord(ev[0], st));
   size_t done = 0;
+  running = true;
   for (const pmc_pass& p : s.passes) {
     pmc_chunk* ch = chunks[p.model_chunk];
     const size_t slot = (size_t)p.model_chunk * n + p.mb;
@@ -144,6 +152,10 @@ int schedule_replay(pmc_ctx* ctx, const pmc_schedule* sched, pmc_chunk* const* c
         out = (y_last && y_last[p.mb]) ? y_last[p.mb] : buf_ptr(0);
       } else {
         fwd_buf[slot] = take_buf();
+        if (fwd_buf[slot] < 0) {
+          rc = fail(PMC_ERR_NOMEM, "schedule_replay: out of inter-chunk buffers");
+          break;
+        }
         out = buf_ptr(fwd_buf[slot]);
       }
       rc = chunk_forward(ch, p.mb, in, out, p.device);
@@ -159,6 +171,10 @@ int schedule_replay(pmc_ctx* ctx, const pmc_schedule* sched, pmc_chunk* const* c
         out = (dx_first && dx_first[p.mb]) ? dx_first[p.mb] : buf_ptr(0);
       } else {
         bwd_buf[slot] = take_buf();
+        if (bwd_buf[slot] < 0) {
+          rc = fail(PMC_ERR_NOMEM, "schedule_replay: out of inter-chunk buffers");
+          break;
+        }
         out = buf_ptr(bwd_buf[slot]);
       }
       rc = chunk_backward_input(ch, p.mb, in, out);
@@ -184,10 +200,12 @@ int schedule_replay(pmc_ctx* ctx, const pmc_schedule* sched, pmc_chunk* const* c
     if (time_passes) REPLAY_HIP(hipEventRecord(ev[done], st));
   }
   if (rc != PMC_OK) {
-    (void)hipStreamSynchronize(st);
+    // a pass failed: cleanup() waits for what was enqueued and returns every unit still held, so
+    // that the pool is empty again and a later replay is not refused
     cleanup();
     return rc;
   }
+  running = false;
   REPLAY_HIP(hipEventRecord(ev_end, st));
   REPLAY_HIP(hipStreamSynchronize(st));
   float ms = 0.f;

@@ -203,3 +203,19 @@ def test_adaptive_search_larger_and_bad_arguments():
     with pytest.raises(P.PmcError):
         P.pmc_schedule_search(4, 8, 8, t_f=-1.0)
 
+
+
+def test_tuning_switches():
+    """Switches are process-wide integers; -1 hands the choice back; unknown names and values out of
+    range are refused (no GPU needed: nothing is launched)."""
+    for name, good, bad in (("gemm_tile", 4, 5), ("gemm_wgrad", 1, 2), ("attn_shape", 2, 3), ("w_streams", 1, 0),
+                            ("gemm_group", 8, 0)):
+        P.pmc_tuning_set(name, good)
+        assert P.pmc_tuning_get(name) == good
+        with pytest.raises(P.PmcError) as e:
+            P.pmc_tuning_set(name, bad)
+        assert e.value.code == P.PMC_ERR_INVALID and P.pmc_tuning_get(name) == good
+        P.pmc_tuning_set(name, -1)
+        assert P.pmc_tuning_get(name) == -1
+    with pytest.raises(P.PmcError):
+        P.pmc_tuning_set("no_such_switch", 1)

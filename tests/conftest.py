@@ -27,3 +27,15 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture
+def tune():
+    """tune(switch=value, ...) sets tuning switches of the library for the rest of the test."""
+    from gpu_util import tuned
+
+    def _set(**switches):
+        tuned(**switches).__enter__()
+
+    yield _set
+    tuned.reset()

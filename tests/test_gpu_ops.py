@@ -6,7 +6,7 @@ import torch
 import paper_2405_15362_amd as P
 import synth
 from oracle import layer as OL
-from gpu_util import dev, host, mat, rel_l2, tol
+from gpu_util import assert_close, dev, host, mat, rel_l2, tol
 
 pytestmark = pytest.mark.gpu
 
@@ -57,9 +57,9 @@ def _gemm_case(ctx, dtype, ta, tb, M, N, K, epi):
                dev(bias, dtype) if epi in (P.EPI_BIAS, P.EPI_BIAS_RESID, P.EPI_BIAS_GELU, P.EPI_BIAS_GELU_GRAD) else None,
                dev(resid, dtype) if epi == P.EPI_BIAS_RESID else None, aux)
     torch.cuda.synchronize()
-    assert rel_l2(host(c), ref) <= tol(dtype), key
+    assert_close(host(c), ref, dtype, str(key))
     if want_aux is not None:
-        assert rel_l2(host(aux), want_aux) <= tol(dtype), key
+        assert_close(host(aux), want_aux, dtype, str(key))
 
 
 @pytest.mark.parametrize("ta", [False, True])
@@ -86,17 +86,16 @@ def test_gemm_bf16_small_tiles_ragged(ctx, ta, tb):
 def test_gemm_bf16_direct_to_lds_path(ctx, ta, tb, epis):
     """K in whole 64-wide tiles takes the direct-to-LDS kernel: each of its three tile shapes, with
     ragged edges in M and N (clamped loads), a single K tile and many K tiles."""
-    import os
     try:
-        for tile in ("4", "3", "2", "1", "0"):      # 256x320, 64x128, 128x128, 256x128, 256x256 tiles
-            os.environ["PMC_GEMM_TILE"] = tile
+        for tile in (4, 3, 2, 1, 0):      # 256x320, 64x128, 128x128, 256x128, 256x256 tiles
+            P.pmc_tuning_set("gemm_tile", tile)
             for epi in epis:
                 _gemm_case(ctx, "bf16", ta, tb, 200, 328, 192, epi)
                 _gemm_case(ctx, "bf16", ta, tb, 1000, 1544, 64, epi)
             _gemm_case(ctx, "bf16", ta, tb, 8, 8, 64, epis[0])
             _gemm_case(ctx, "bf16", ta, tb, 264, 136, 2048, epis[-1])
     finally:
-        os.environ.pop("PMC_GEMM_TILE", None)
+        P.pmc_tuning_set("gemm_tile", -1)
     _gemm_case(ctx, "bf16", ta, tb, 3848, 4104, 320, epis[-1])   # heuristic choice, many tiles
 
 
@@ -120,20 +119,20 @@ def test_gemm_bf16_split_k(ctx, ta, tb, epis):
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
 
 
-def test_gemm_bf16_weight_gradient_persistent(ctx, monkeypatch):
+def test_gemm_bf16_weight_gradient_persistent(ctx, tune):
     """The persistent W-pass kernel (fp32 C += A^T B; one workgroup per compute unit walks its
     256x256 tiles, its first tile cut in two along K to put the workgroups out of phase): fewer tiles
     than workgroups, more tiles than workgroups with ragged edges, short and long K; and the same
     result from run to run."""
-    monkeypatch.setenv("PMC_GEMM_WGRAD", "1")
+    tune(gemm_wgrad=1)
     for M, N, K in ((512, 256, 256), (264, 136, 1024), (4104, 4360, 256), (4096, 4608, 576), (3848, 4872, 1280)):
         _gemm_case(ctx, "bf16", True, False, M, N, K, P.EPI_ACCUM_F32)
     a = dev(mat(("wg", "a"), (1024, 4104), "bf16"), "bf16")
     b = dev(mat(("wg", "b"), (1024, 4360), "bf16", 0.05), "bf16")
     c0 = dev(mat(("wg", "c"), (4104, 4360), "f32"), "f32")
     outs = []
-    for flag in ("1", "1", "0"):
-        monkeypatch.setenv("PMC_GEMM_WGRAD", flag)
+    for flag in (1, 1, 0):
+        tune(gemm_wgrad=flag)
         c = c0.clone()
         P.pmc_gemm(ctx, a, b, c, True, False, P.EPI_ACCUM_F32)
         outs.append(c)
@@ -142,21 +141,18 @@ def test_gemm_bf16_weight_gradient_persistent(ctx, monkeypatch):
     assert rel_l2(host(outs[0]), host(outs[2])) <= 1e-6     # the plain kernel adds K in one piece
 
 
-@pytest.mark.parametrize("wgrad", ["0", "1"])
-def test_gemm_bf16_grouped_weight_gradient(ctx, monkeypatch, wgrad):
+@pytest.mark.parametrize("wgrad", [0, 1])
+def test_gemm_bf16_grouped_weight_gradient(ctx, tune, wgrad):
     """Queued weight gradients as one product: C += sum_i A_i^T B_i over pieces that live in separate
     buffers.  Every tile shape of the plain kernel and the persistent one; one piece, several pieces,
     the maximum; pieces of a single 64-wide K tile (a piece boundary at every tile) and of many;
     ragged M and N; and the same bits from run to run.  Against the fp64 sum of the pieces' products;
     the result must also agree with adding the pieces one product at a time."""
-    monkeypatch.setenv("PMC_GEMM_WGRAD", wgrad)
+    tune(gemm_wgrad=wgrad)
     cases = [(512, 256, 64, 3), (264, 136, 192, 2), (1000, 1544, 128, 8), (2048, 2304, 256, 4), (4104, 4360, 64, 5),
              (128, 128, 1024, 1)]
-    for tile in (None, "0", "1", "2"):
-        if tile is None:
-            monkeypatch.delenv("PMC_GEMM_TILE", raising=False)
-        else:
-            monkeypatch.setenv("PMC_GEMM_TILE", tile)
+    for tile in (None, 0, 1, 2):
+        tune(gemm_tile=tile)
         for M, N, K, count in (cases if tile is None else cases[:3]):
             key = ("grouped", M, N, K, count)
             print("grouped wgrad case", key, "tile", tile, "persistent", wgrad, flush=True)
@@ -181,15 +177,15 @@ def test_gemm_bf16_grouped_weight_gradient(ctx, monkeypatch, wgrad):
             assert rel_l2(host(outs[0]), host(one_by_one)) <= 1e-5, key
 
 
-def test_gemm_bf16_largest_workload_shapes_sampled(ctx):
+@pytest.mark.timeout(600)
+def test_gemm_bf16_largest_workload_shapes(ctx):
     """The twelve products of a layer at the largest workload (hidden 5120, FFN 20480, 4096 tokens), at
     full size and in the launch configuration the passes use (heuristic tile choice, persistent W
     kernel).  Operands are drawn on the GPU from a seeded generator (2e8 elements per product);
-    a few thousand output elements, rows and columns sampled over all tiles including the last,
-    are checked against fp64 dot products with the epilogue's definition applied."""
+    EVERY output element is checked against the fp64 product with the epilogue's definition applied
+    (whole tensor, every 32 x 128 block, every element)."""
     T, h, f = 4096, 5120, 20480
     gen = torch.Generator(device="cuda").manual_seed(4)
-    rng = np.random.default_rng(4)
     bf = torch.bfloat16
 
     def rnd(shape, scale):
@@ -216,26 +212,25 @@ def test_gemm_bf16_largest_workload_shapes_sampled(ctx):
         P.pmc_gemm(ctx, a, b, c, ta, tb, epi, bias if epi in (P.EPI_BIAS, P.EPI_BIAS_RESID, P.EPI_BIAS_GELU_GRAD) else None,
                    extra if epi == P.EPI_BIAS_RESID else None, aux)
         torch.cuda.synchronize()
-        ms = np.unique(np.concatenate([rng.integers(0, M, 46), [0, M - 1]]))
-        ns = np.unique(np.concatenate([rng.integers(0, N, 46), [0, N - 1]]))
-        mi, ni = torch.from_numpy(ms).cuda(), torch.from_numpy(ns).cuda()
-        A = f64(a[:, mi]).T if ta else f64(a[mi])                 # [len(ms), K]
-        B = f64(b[ni]).T if tb else f64(b[:, ni])                 # [K, len(ns)]
+        A = f64(a).T if ta else f64(a)
+        B = f64(b).T if tb else f64(b)
         ref = A @ B
-        sub = lambda t: f64(t[mi][:, ni])
+        del A, B
         if epi in (P.EPI_BIAS, P.EPI_BIAS_RESID, P.EPI_BIAS_GELU_GRAD):
-            ref = ref + f64(bias[ni])
+            ref += f64(bias)
         if epi == P.EPI_BIAS_RESID:
-            ref = ref + sub(extra)
+            ref += f64(extra)
         if epi == P.EPI_MUL:
-            ref = ref * sub(extra)
+            ref *= f64(extra)
         if epi == P.EPI_ACCUM_F32:
-            ref = ref + sub(c0)
+            ref += f64(c0)
         if epi == P.EPI_BIAS_GELU_GRAD:
-            assert rel_l2(sub(aux), OL.gelu(ref)) <= tol("bf16"), name
+            assert_close(f64(aux), OL.gelu(ref), "bf16", name + " gelu")
             ref = OL.gelu_grad(ref)
-        assert rel_l2(sub(c), ref) <= tol("bf16"), (name, rel_l2(sub(c), ref))
-        del a, b, c, c0, aux, extra
+        # fp32 sums of exact bf16 products: the fp32 accumulate is held to the fp32 bounds
+        assert_close(f64(c), ref, "f32" if epi == P.EPI_ACCUM_F32 else "bf16", name,
+                     whole_tol=1e-5 if epi == P.EPI_ACCUM_F32 else None)
+        del a, b, c, c0, aux, extra, ref
 
 
 def test_gemm_grouped_weight_gradient_rejects_bad_arguments(ctx):
@@ -298,7 +293,7 @@ def test_layernorm_forward_backward(ctx, dtype, rows, h):
     rs = torch.zeros(rows, device="cuda")
     P.pmc_layernorm_forward(ctx, xd, dev(g, dtype), dev(b, dtype), eps, y, mean, rs, xc)
     torch.cuda.synchronize()
-    assert rel_l2(host(y), y_ref) <= tol(dtype)
+    assert_close(host(y), y_ref, dtype, "")
     assert np.abs(host(mean) - x.astype(np.float64).mean(-1)).max() <= 1e-5
     assert rel_l2(host(rs), rstd[:, 0]) <= 1e-5
     assert torch.equal(xc, xd)
@@ -307,9 +302,9 @@ def test_layernorm_forward_backward(ctx, dtype, rows, h):
     dx = xd.clone()                      # in place over x, as the B pass does
     P.pmc_layernorm_backward(ctx, dev(dy, dtype), dx, dev(g, dtype), mean, rs, dev(resid, dtype), dx, dgain, dbias)
     torch.cuda.synchronize()
-    assert rel_l2(host(dx), dx_ref) <= tol(dtype)
-    assert rel_l2(host(dgain) - 0.25, dg_ref) <= (5e-3 if dtype == "bf16" else 1e-5)
-    assert rel_l2(host(dbias) + 0.5, db_ref) <= 1e-5
+    assert_close(host(dx), dx_ref, dtype, "")
+    assert_close(host(dgain) - 0.25, dg_ref, dtype, "dgain", whole_tol=5e-3 if dtype == "bf16" else 1e-5)
+    assert_close(host(dbias) + 0.5, db_ref, "f32", "dbias")
 
 
 @pytest.mark.parametrize("dtype,dh", [("f32", 4), ("f32", 16), ("f32", 64), ("f32", 128), ("bf16", 64), ("bf16", 128),
@@ -332,14 +327,14 @@ def test_attention_forward_backward(ctx, dtype, dh, causal):
     lse = torch.zeros(batch * heads * seq, device="cuda")
     P.pmc_attention_forward(ctx, qd, o, lse, batch, seq, heads, dh, causal)
     torch.cuda.synchronize()
-    assert rel_l2(host(o), o_ref) <= tol(dtype)
+    assert_close(host(o), o_ref, dtype, "")
     assert np.abs(host(lse) - lse_ref.reshape(-1)).max() <= (2e-2 if dtype == "bf16" else 2e-5)
     # separate output buffer
     dq = dev(np.zeros_like(qkv), dtype)
     P.pmc_attention_backward(ctx, qd, o, lse, dev(d_o, dtype), dq, batch, seq, heads, dh, causal)
     torch.cuda.synchronize()
     for name, cols in (("dq", slice(0, h)), ("dk", slice(h, 2 * h)), ("dv", slice(2 * h, 3 * h))):
-        assert rel_l2(host(dq)[:, cols], dqkv_ref[:, cols]) <= tol(dtype), name
+        assert_close(host(dq)[:, cols], dqkv_ref[:, cols], dtype, str(name), scale=np.sqrt(np.mean(dqkv_ref ** 2)))
     # in place over qkv, as the B pass does
     inplace = qd.clone()
     P.pmc_attention_backward(ctx, inplace, o, lse, dev(d_o, dtype), inplace, batch, seq, heads, dh, causal)
@@ -347,14 +342,14 @@ def test_attention_forward_backward(ctx, dtype, dh, causal):
     assert torch.equal(inplace, dq)
 
 
-@pytest.mark.parametrize("family", ["0", "1", "2"])
+@pytest.mark.parametrize("family", [0, 1, 2])
 @pytest.mark.parametrize("dh,causal", [(128, True), (64, True), (128, False), (112, True), (48, False)])
-def test_attention_launch_shapes(ctx, monkeypatch, family, dh, causal):
+def test_attention_launch_shapes(ctx, tune, family, dh, causal):
     """Every family of workgroup shapes (key/query splits, merges through LDS) on a ragged
     sequence that spans several streamed blocks; the library reads the override at each call.
     Head sizes 112 and 48 run in the 128- and 64-wide tiles with the remaining columns held at zero
     (112 = hidden 7168 over 64 heads, one of the paper's model shapes)."""
-    monkeypatch.setenv("PMC_ATTN_SHAPE", family)
+    tune(attn_shape=family)
     batch, seq, heads = 2, 333, 2
     h = heads * dh
     key = ("attn-shape", dh, causal)
@@ -369,21 +364,21 @@ def test_attention_launch_shapes(ctx, monkeypatch, family, dh, causal):
     lse = torch.zeros(batch * heads * seq, device="cuda")
     P.pmc_attention_forward(ctx, qd, o, lse, batch, seq, heads, dh, causal)
     torch.cuda.synchronize()
-    assert rel_l2(host(o), o_ref) <= tol("bf16")
+    assert_close(host(o), o_ref, "bf16", "")
     assert np.abs(host(lse) - lse_ref.reshape(-1)).max() <= 2e-2
     dq = dev(np.zeros_like(qkv), "bf16")
     P.pmc_attention_backward(ctx, qd, o, lse, dev(d_o, "bf16"), dq, batch, seq, heads, dh, causal)
     torch.cuda.synchronize()
     for name, cols in (("dq", slice(0, h)), ("dk", slice(h, 2 * h)), ("dv", slice(2 * h, 3 * h))):
-        assert rel_l2(host(dq)[:, cols], dqkv_ref[:, cols]) <= tol("bf16"), name
+        assert_close(host(dq)[:, cols], dqkv_ref[:, cols], "bf16", str(name), scale=np.sqrt(np.mean(dqkv_ref ** 2)))
 
 
-@pytest.mark.parametrize("family", ["0", "1"])
-def test_attention_long_sequence(ctx, monkeypatch, family):
+@pytest.mark.parametrize("family", [0, 1])
+def test_attention_long_sequence(ctx, tune, family):
     """Sequence length 4096 at head size 128 (the longest workload shape), four heads so that the
     oracle's probabilities fit in host memory: 32 to 64 streamed blocks per query block, the
     heaviest-first block order, both families of launch shapes."""
-    monkeypatch.setenv("PMC_ATTN_SHAPE", family)
+    tune(attn_shape=family)
     batch, seq, heads, dh = 1, 4096, 4, 128
     h = heads * dh
     key = ("attn-long",)
@@ -399,22 +394,24 @@ def test_attention_long_sequence(ctx, monkeypatch, family):
     lse = torch.zeros(heads * seq, device="cuda")
     P.pmc_attention_forward(ctx, qd, o, lse, batch, seq, heads, dh, True)
     torch.cuda.synchronize()
-    assert rel_l2(host(o), o_ref) <= tol("bf16")
+    assert_close(host(o), o_ref, "bf16", "")
     assert np.abs(host(lse) - lse_ref.reshape(-1)).max() <= 2e-2
     dq = dev(np.zeros_like(qkv), "bf16")
     P.pmc_attention_backward(ctx, qd, o, lse, dev(d_o, "bf16"), dq, batch, seq, heads, dh, True)
     torch.cuda.synchronize()
     for name, cols in (("dq", slice(0, h)), ("dk", slice(h, 2 * h)), ("dv", slice(2 * h, 3 * h))):
-        assert rel_l2(host(dq)[:, cols], dqkv_ref[:, cols]) <= tol("bf16"), name
+        assert_close(host(dq)[:, cols], dqkv_ref[:, cols], "bf16", str(name), scale=np.sqrt(np.mean(dqkv_ref ** 2)))
 
 
+@pytest.mark.timeout(600)
 @pytest.mark.parametrize("seq,heads", [(4096, 40), (2048, 32), (1024, 16)])
-def test_attention_workload_shapes_sampled_heads(ctx, seq, heads):
+def test_attention_workload_shapes(ctx, seq, heads):
     """Attention at the full size of the three bf16 workloads (head size 128, causal), launched as the
     passes launch it (the library's own choice of workgroup shapes for that many heads and blocks).
-    The dense oracle for all heads would need heads x seq^2 probabilities; three heads (first, last,
-    one in between) are checked in full instead, each as a one-head problem cut out of the packed
-    q|k|v rows: output, log-sum-exp and all three input gradients, every element."""
+    The dense oracle for all heads at once would need heads x seq^2 probabilities, so heads are checked
+    one at a time, each as a one-head problem cut out of the packed q|k|v rows: output, log-sum-exp and
+    all three input gradients, every element.  At the longest shape (4096 tokens, 40 heads) EVERY head
+    is checked; at the two shorter ones the first, the last and one in between."""
     dh = 128
     h = heads * dh
     gen = torch.Generator(device="cuda").manual_seed(seq + heads)
@@ -429,24 +426,24 @@ def test_attention_workload_shapes_sampled_heads(ctx, seq, heads):
     P.pmc_attention_backward(ctx, qkv, o, lse, d_o, dq, 1, seq, heads, dh, True)
     torch.cuda.synchronize()
     lse_h = host(lse).reshape(heads, seq)
-    for hd in (0, heads // 2 + 1, heads - 1):
+    for hd in (range(heads) if seq == 4096 else (0, heads // 2 + 1, heads - 1)):
         cols = [slice(part * h + hd * dh, part * h + (hd + 1) * dh) for part in range(3)]
         one = np.concatenate([host(qkv[:, c]) for c in cols], axis=1)              # [seq, 3 dh]: a one-head qkv
         o_ref, probs, lse_ref = OL.attention(one, 1, True, 1)
         g_ref = OL.attention_input_grad(host(d_o[:, hd * dh:(hd + 1) * dh]), one, probs, 1, 1)
         del probs
-        assert rel_l2(host(o[:, hd * dh:(hd + 1) * dh]), o_ref) <= tol("bf16"), hd
+        assert_close(host(o[:, hd * dh:(hd + 1) * dh]), o_ref, "bf16", str(hd))
         assert np.abs(lse_h[hd] - lse_ref.reshape(-1)).max() <= 2e-2, hd
         for part, name in enumerate(("dq", "dk", "dv")):
-            assert rel_l2(host(dq[:, cols[part]]), g_ref[:, part * dh:(part + 1) * dh]) <= tol("bf16"), (hd, name)
+            assert_close(host(dq[:, cols[part]]), g_ref[:, part * dh:(part + 1) * dh], "bf16", str((hd, name)), scale=np.sqrt(np.mean(g_ref ** 2)))
 
 
-@pytest.mark.parametrize("family", ["0", "1", "2"])
+@pytest.mark.parametrize("family", [0, 1, 2])
 @pytest.mark.parametrize("dh", [64, 128])
-def test_attention_short_sequences(ctx, monkeypatch, family, dh):
+def test_attention_short_sequences(ctx, tune, family, dh):
     """Sequences shorter than one streamed block (a single query, a few, one 32-row tile plus
     one): every tile row past the end is a clamped copy of the last row and must be masked out."""
-    monkeypatch.setenv("PMC_ATTN_SHAPE", family)
+    tune(attn_shape=family)
     batch, heads = 2, 2
     h = heads * dh
     for seq in (1, 7, 33):
@@ -462,23 +459,23 @@ def test_attention_short_sequences(ctx, monkeypatch, family, dh):
         lse = torch.zeros(batch * heads * seq, device="cuda")
         P.pmc_attention_forward(ctx, qd, o, lse, batch, seq, heads, dh, True)
         torch.cuda.synchronize()
-        assert rel_l2(host(o), o_ref) <= tol("bf16"), seq
+        assert_close(host(o), o_ref, "bf16", str(seq))
         assert np.abs(host(lse) - lse_ref.reshape(-1)).max() <= 2e-2, seq
         dq = dev(np.zeros_like(qkv), "bf16")
         P.pmc_attention_backward(ctx, qd, o, lse, dev(d_o, "bf16"), dq, batch, seq, heads, dh, True)
         torch.cuda.synchronize()
         for name, cols in (("dq", slice(0, h)), ("dk", slice(h, 2 * h)), ("dv", slice(2 * h, 3 * h))):
-            assert rel_l2(host(dq)[:, cols], dqkv_ref[:, cols]) <= tol("bf16"), (seq, name)
+            assert_close(host(dq)[:, cols], dqkv_ref[:, cols], "bf16", str((seq, name)), scale=np.sqrt(np.mean(dqkv_ref ** 2)))
 
 
-@pytest.mark.parametrize("family", ["0", "1"])
+@pytest.mark.parametrize("family", [0, 1])
 @pytest.mark.parametrize("causal", [True, False])
-def test_attention_sharp_softmax(ctx, monkeypatch, family, causal):
+def test_attention_sharp_softmax(ctx, tune, family, causal):
     """Queries and keys three times larger (scores with a standard deviation of 9, 13 in log2
     units): row maxima keep rising from block to block by more and by less than the slack the
     forward kernel allows before it moves its softmax reference, so both branches of the online
     softmax and their mix inside one wave are exercised."""
-    monkeypatch.setenv("PMC_ATTN_SHAPE", family)
+    tune(attn_shape=family)
     batch, seq, heads, dh = 1, 700, 2, 128
     h = heads * dh
     key = ("attn-sharp", causal)
@@ -495,13 +492,13 @@ def test_attention_sharp_softmax(ctx, monkeypatch, family, causal):
     lse = torch.zeros(batch * heads * seq, device="cuda")
     P.pmc_attention_forward(ctx, qd, o, lse, batch, seq, heads, dh, causal)
     torch.cuda.synchronize()
-    assert rel_l2(host(o), o_ref) <= tol("bf16")
+    assert_close(host(o), o_ref, "bf16", "")
     assert np.abs(host(lse) - lse_ref.reshape(-1)).max() <= 2e-2
     dq = dev(np.zeros_like(qkv), "bf16")
     P.pmc_attention_backward(ctx, qd, o, lse, dev(d_o, "bf16"), dq, batch, seq, heads, dh, causal)
     torch.cuda.synchronize()
     for name, cols in (("dq", slice(0, h)), ("dk", slice(h, 2 * h)), ("dv", slice(2 * h, 3 * h))):
-        assert rel_l2(host(dq)[:, cols], dqkv_ref[:, cols]) <= tol("bf16"), name
+        assert_close(host(dq)[:, cols], dqkv_ref[:, cols], "bf16", str(name), scale=np.sqrt(np.mean(dqkv_ref ** 2)))
 
 
 def test_attention_rejects_rows_beyond_the_load_window(ctx):

@@ -8,7 +8,7 @@ import synth
 from oracle import layer as OL
 from oracle import schedule as OS
 from paper_2405_15362_amd import runtime as R
-from gpu_util import dev, host, oracle_chunk, rel_l2, tol
+from gpu_util import assert_close, dev, host, oracle_chunk, rel_l2, tol
 
 pytestmark = pytest.mark.gpu
 
@@ -28,6 +28,10 @@ CASES = {
     # one layer of the hidden-4096, 2048-token shape: the many-block attention shapes and GEMMs that are
     # neither split nor skinny
     "c3_one_layer_bf16": synth.ChunkCfg(layers=1, hidden=4096, heads=32, ffn=16384, seq=2048, dtype="bf16"),
+    # the attention-heavy workload at full size: 2 layers, hidden 5120, 40 heads, FFN 20480, 4096 tokens,
+    # causal; the 256x320 tiles, the persistent W kernel, the many-block attention shapes.  Every output
+    # and gradient element (all 40 heads through the chunk oracle; about a minute of fp64 numpy)
+    "c4_full_bf16": synth.CONFIGS["C4"],
 }
 
 
@@ -58,18 +62,43 @@ def _run_fbw(cfg, tag, n_mb=1, defer=False):
     return params, xs, dys, res
 
 
+@pytest.mark.timeout(900)
 @pytest.mark.parametrize("name", list(CASES))
 def test_f_b_w_match_oracle(name):
     cfg = CASES[name]
     print("pass parity case", name, cfg, flush=True)
     params, xs, dys, (ys, dxs, grads) = _run_fbw(cfg, name)
     y, dx, ln, wg = oracle_chunk(cfg, params, xs[0], dys[0])
-    t = tol(cfg.dtype)
-    assert rel_l2(ys[0], y) <= t
-    assert rel_l2(dxs[0], dx) <= t
+    assert_close(ys[0], y, cfg.dtype, f"{name} y")
+    assert_close(dxs[0], dx, cfg.dtype, f"{name} dx")
     for l in range(cfg.layers):
         for k, v in {**ln[l], **wg[l]}.items():
-            assert rel_l2(grads[l][k], v) <= t, (l, k, rel_l2(grads[l][k], v))
+            assert_close(grads[l][k], v, cfg.dtype, f"{name} L{l}.{k}")
+
+
+@pytest.mark.timeout(900)
+def test_config3_four_layers_four_queued_w():
+    """The third workload as stated: one chunk of 4 layers (hidden 4096, 32 heads, FFN 16384, 2048
+    tokens, bf16); F and B of 4 microbatches, then ONE stage_backward_weight call for the 4 queued
+    microbatches into zero-initialised fp32 gradients (each weight gradient one product over the four
+    microbatches' concatenated token axis).  Outputs and input gradients of every microbatch and the
+    accumulated gradient of every parameter, every element, against the oracle's sum over the
+    microbatches (about two minutes of fp64 numpy; one microbatch at a time, only the sums are kept)."""
+    cfg, n_mb = synth.CONFIGS["C3"], 4
+    params, xs, dys, (ys, dxs, grads) = _run_fbw(cfg, "C3", n_mb, defer=True)
+    p64 = OL.cast_params(params)
+    total = OL.zero_grads(p64)
+    for j in range(n_mb):
+        print("config 3 oracle microbatch", j, flush=True)
+        y, saved = OL.chunk_forward(xs[j].astype(np.float64), p64, cfg.heads, cfg.causal, cfg.ln_eps, cfg.microbatch)
+        dx, stash, ln = OL.chunk_backward_input(dys[j].astype(np.float64), p64, saved, cfg.heads, cfg.microbatch)
+        OL.accumulate(total, ln, OL.chunk_backward_weight(saved, stash))
+        del saved, stash
+        assert_close(ys[j], y, "bf16", f"C3 y[{j}]")
+        assert_close(dxs[j], dx, "bf16", f"C3 dx[{j}]")
+    for l in range(cfg.layers):
+        for k in OL.PARAM_NAMES:
+            assert_close(grads[l][k], total[l][k], "bf16", f"C3 L{l}.{k}")
 
 
 @pytest.mark.parametrize("name", ["multi_f32", "dh128_bf16"])
@@ -81,10 +110,11 @@ def test_deferred_w_accumulates_over_microbatches(name):
     for j in range(n_mb):
         y, dx, ln, wg = oracle_chunk(cfg, params, xs[j], dys[j])
         OL.accumulate(total, ln, wg)
-        assert rel_l2(ys[j], y) <= tol(cfg.dtype) and rel_l2(dxs[j], dx) <= tol(cfg.dtype)
+        assert_close(ys[j], y, cfg.dtype, f"{name} y[{j}]")
+        assert_close(dxs[j], dx, cfg.dtype, f"{name} dx[{j}]")
     for l in range(cfg.layers):
         for k in OL.PARAM_NAMES:
-            assert rel_l2(grads[l][k], total[l][k]) <= tol(cfg.dtype), (l, k)
+            assert_close(grads[l][k], total[l][k], cfg.dtype, f"{name} L{l}.{k}")
     # immediate W per microbatch: in fp32 mode the queued pass runs the same products in the same
     # order (same bits); in bf16 mode it contracts the queued microbatches in one product per weight
     # (same sum up to fp32 summation order), LayerNorm and bias gradients keep their order
@@ -109,7 +139,7 @@ def test_queued_w_groups_larger_than_the_maximum():
             OL.accumulate(total, ln, wg)
         for l in range(cfg.layers):
             for k in OL.PARAM_NAMES:
-                assert rel_l2(grads[l][k], total[l][k]) <= tol(cfg.dtype), (name, l, k)
+                assert_close(grads[l][k], total[l][k], cfg.dtype, f"{name} L{l}.{k}")
 
 
 def test_pass_order_errors():
@@ -201,10 +231,11 @@ def test_replay_config1_all_schedules():
         print("replay", kind, flush=True)
         ys, dxs, grads, report, peaks = _replay(cfg, "C1", kind, d, n, chunk_params, xs, dys)
         for j in range(n):
-            assert rel_l2(ys[j], ys_ref[j]) <= 1e-5 and rel_l2(dxs[j], dxs_ref[j]) <= 1e-5
+            assert_close(ys[j], ys_ref[j], "f32", f"{kind} y[{j}]")
+            assert_close(dxs[j], dxs_ref[j], "f32", f"{kind} dx[{j}]")
         for c in range(2 * d):
             for k in OL.PARAM_NAMES:
-                assert rel_l2(grads[c][0][k], grads_ref[c][0][k]) <= 1e-5, (kind, c, k)
+                assert_close(grads[c][0][k], grads_ref[c][0][k], "f32", f"{kind} chunk {c} {k}")
         units = OS.peak_units(kind, d, n)
         want = OS.peak_bytes(kind, d, n, m, st)
         assert [p[0] for p in peaks] == units
@@ -231,11 +262,14 @@ def test_replay_bf16_d4_reduced_width():
         print("replay", kind, flush=True)
         ys, dxs, grads, report, peaks = _replay(cfg, "C5r", kind, d, n, chunk_params, xs, dys)
         for j in range(n):
-            assert rel_l2(ys[j], ys_ref[j]) <= 2e-2 and rel_l2(dxs[j], dxs_ref[j]) <= 2e-2
+            # 16 layers deep: the bf16 roundings of 8 chunks add up, so the element and block bounds
+            # are doubled here (the whole-tensor bound stays at 2e-2)
+            assert_close(ys[j], ys_ref[j], "bf16", f"{kind} y[{j}]", atol_scale=2.0)
+            assert_close(dxs[j], dxs_ref[j], "bf16", f"{kind} dx[{j}]", atol_scale=2.0)
         for c in range(2 * d):
             for l in range(cfg.layers):
                 for k in OL.PARAM_NAMES:
-                    assert rel_l2(grads[c][l][k], grads_ref[c][l][k]) <= 2e-2, (kind, c, l, k)
+                    assert_close(grads[c][l][k], grads_ref[c][l][k], "bf16", f"{kind} chunk {c} L{l}.{k}", atol_scale=2.0)
         assert [p[0] for p in peaks] == OS.peak_units(kind, d, n)
         if first is None:
             first = grads
@@ -261,7 +295,8 @@ def test_replay_reordered_schedules():
         print("replay reordered", kind, flush=True)
         ys, dxs, grads, report, peaks = _replay(cfg, "C5o", kind, d, n, chunk_params, xs, dys, reorder=True)
         for j in range(n):
-            assert rel_l2(ys[j], ys_ref[j]) <= 2e-2 and rel_l2(dxs[j], dxs_ref[j]) <= 2e-2
+            assert_close(ys[j], ys_ref[j], "bf16", f"{kind} y[{j}]", atol_scale=2.0)
+            assert_close(dxs[j], dxs_ref[j], "bf16", f"{kind} dx[{j}]", atol_scale=2.0)
         assert [p[0] for p in peaks] == OS.peak_units(kind, d, n)
         assert report["passes"] == 6 * d * n
         for c in range(2 * d):
@@ -289,3 +324,116 @@ def test_replay_adaptive_schedule():
         for k in OL.PARAM_NAMES:
             assert np.array_equal(grads[c][0][k], first[c][0][k]), (c, k)
 
+
+
+def _gpu_chunks(ctx, cfg, count, seed):
+    """`count` chunks of one shape with weights drawn on the GPU from a seeded generator (too many
+    parameters to draw on the host in reasonable time): N(0, 0.02^2), LayerNorm gains 1 + N(0, 0.02^2)."""
+    gen = torch.Generator(device="cuda").manual_seed(seed)
+    shapes = synth.param_shapes(cfg)
+    chunks = []
+    for _ in range(count):
+        ch = R.Chunk.__new__(R.Chunk)
+        ch.context = ctx
+        ch.params, ch.grads = [], []
+        for _l in range(cfg.layers):
+            p = {}
+            for k, shp in shapes.items():
+                t = torch.randn(shp, device="cuda", generator=gen) * 0.02
+                if k in ("ln1_g", "ln2_g"):
+                    t += 1.0
+                p[k] = t.to(torch.bfloat16)
+            ch.params.append(p)
+            ch.grads.append({k: torch.zeros(shp, dtype=torch.float32, device="cuda") for k, shp in shapes.items()})
+        ch.handle = P.pmc_chunk_create(ctx.ctx, ctx.cfg)
+        P.pmc_chunk_bind(ch.handle, [p[k] for p in ch.params for k in R.PARAM_NAMES],
+                         [g[k] for g in ch.grads for k in R.PARAM_NAMES])
+        ctx.chunks.append(ch)
+        chunks.append(ch)
+    return chunks, gen
+
+
+@pytest.mark.timeout(900)
+def test_replay_config5_full_size():
+    """The full schedule replay at its stated size: 4 simulated devices, 8 two-layer chunks (hidden 4096,
+    32 heads, FFN 16384, 2048 tokens, bf16), 16 microbatches, as 1F1B, V-ZB, V-Half and V-Min.
+    The fp64 oracle of a whole iteration would take hours, so the chain is:
+      (i)   a naive run on the GPU (F through all chunks, B back, W at once, microbatch after
+            microbatch) in which ONE chunk's pass for microbatch 0 is compared with the oracle in
+            full: its output, its input gradient and every parameter gradient, every element;
+      (ii)  every schedule's replay must give the naive run's outputs, input gradients and accumulated
+            gradients BIT FOR BIT (every chunk's W and B passes run in microbatch order in all of them);
+      (iii) the machine's measured peaks per simulated device equal the oracle's accounting, units and
+            bytes, and V-Half / V-Min hold 3/4 and 1/2 of 1F1B's worst device (the exact values at
+            d = 4 of the paper's Section 3.2)."""
+    cfg, d, n = synth.CONFIGS["C5"], 4, 16
+    pcfg = R.cfg_from_synth(cfg)
+    probe = 3                                            # the chunk checked against the oracle
+    scheds = {k: P.pmc_schedule_build(k, d, n) for k in ("1f1b", "vzb", "vhalf", "vmin")}
+    ws = max(P.pmc_replay_workspace_bytes(s, pcfg) for s in scheds.values())
+    ctx = R.Context(pcfg, slabs=2 * d * d, workspace_bytes=ws)
+    chunks, gen = _gpu_chunks(ctx, cfg, 2 * d, seed=5)
+    bf = torch.bfloat16
+    xs = [torch.randn(cfg.tokens, cfg.hidden, device="cuda", generator=gen).to(bf) for _ in range(n)]
+    dys = [torch.randn(cfg.tokens, cfg.hidden, device="cuda", generator=gen).to(bf) for _ in range(n)]
+    handles = [c.handle for c in chunks]
+
+    # (i) naive run
+    print("config 5: naive run", flush=True)
+    acts = [torch.empty_like(xs[0]) for _ in range(2 * d + 1)]
+    grs = [torch.empty_like(xs[0]) for _ in range(2 * d + 1)]
+    y_naive, dx_naive, probe_io, probe_grads = [], [], None, None
+    for j in range(n):
+        acts[0].copy_(xs[j])
+        for c in range(2 * d):
+            P.stage_forward(handles[c], j, acts[c], acts[c + 1])
+        grs[2 * d].copy_(dys[j])
+        for c in reversed(range(2 * d)):
+            P.stage_backward_input(handles[c], j, grs[c + 1], grs[c])
+            P.stage_backward_weight(handles[c], [j])
+        y_naive.append(acts[2 * d].clone())
+        dx_naive.append(grs[0].clone())
+        if j == 0:
+            probe_io = [t.clone() for t in (acts[probe], acts[probe + 1], grs[probe + 1], grs[probe])]
+            probe_grads = [{k: v.clone() for k, v in g.items()} for g in chunks[probe].grads]
+    torch.cuda.synchronize()
+    assert P.pmc_pool_live_slabs(ctx.ctx) == 0
+    naive = [[{k: v.clone() for k, v in g.items()} for g in ch.grads] for ch in chunks]
+
+    print("config 5: oracle on chunk", probe, flush=True)
+    params = [{k: v.float().cpu().numpy() for k, v in p.items()} for p in chunks[probe].params]
+    x3, y3, dy3, dx3 = (host(t) for t in probe_io)
+    y, dx, ln, wg = oracle_chunk(cfg, params, x3, dy3)
+    assert_close(y3, y, "bf16", "C5 probe y")
+    assert_close(dx3, dx, "bf16", "C5 probe dx")
+    for l in range(cfg.layers):
+        for k, v in {**ln[l], **wg[l]}.items():
+            assert_close(host(probe_grads[l][k]), v, "bf16", f"C5 probe L{l}.{k}")
+    del params, y, dx, ln, wg, probe_grads
+
+    # (ii), (iii) the four schedules
+    m = OL.chunk_activation_bytes(cfg.layers, cfg.hidden, cfg.heads, cfg.seq, 2, cfg.microbatch, cfg.ffn)
+    st = OL.chunk_stats_bytes(cfg.layers, cfg.heads, cfg.seq, cfg.microbatch)
+    assert m == P.pmc_activation_bytes(pcfg) == 537460736
+    worst = {}
+    for kind, s in scheds.items():
+        print("config 5: replay", kind, flush=True)
+        for ch in chunks:
+            ch.zero_grads()
+        yl = [torch.empty_like(t) for t in xs]
+        dxf = [torch.empty_like(t) for t in xs]
+        report, peaks = P.schedule_replay(ctx.ctx, s, handles, xs, dys, yl, dxf)
+        assert report["passes"] == 6 * d * n and P.pmc_pool_live_slabs(ctx.ctx) == 0
+        assert [p[0] for p in peaks] == OS.peak_units(kind, d, n)
+        assert [(p[1], p[2]) for p in peaks] == OS.peak_bytes(kind, d, n, m, st)
+        worst[kind] = max(p[1] for p in peaks)
+        for j in range(n):
+            assert torch.equal(yl[j], y_naive[j]) and torch.equal(dxf[j], dx_naive[j]), (kind, j)
+        for c, ch in enumerate(chunks):
+            for l in range(cfg.layers):
+                for k in OL.PARAM_NAMES:
+                    assert torch.equal(ch.grads[l][k], naive[c][l][k]), (kind, c, l, k)
+        P.pmc_schedule_destroy(s)
+    assert worst["1f1b"] == worst["vzb"] == 8 * m
+    assert worst["vhalf"] * 4 == worst["1f1b"] * 3 and worst["vmin"] * 2 == worst["1f1b"]
+    ctx.close()

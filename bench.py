@@ -1,16 +1,21 @@
 #!/usr/bin/env python3
-"""Benchmark of the stage hot path on one MI355X: one step = F + B + W of one chunk for one
-microbatch (all through the C ABI), on the bf16 GPT-stage workload (2 layers, hidden 2048, 16 heads,
-FFN 8192, seq 1024, microbatch 1; weights N(0, 0.02^2), activations and upstream gradients N(0,1),
-all synthetic and seeded).
+"""Benchmark of the stage hot path on one MI355X.  One step = F + B + W of one chunk for one
+microbatch, all through the C ABI.  The headline workload is the largest single-GPU stage of the
+build's configurations: the attention-heavy bf16 stage C4 (2 layers per chunk, hidden 5120, 40
+heads, FFN 20480, 4096 tokens, causal; weights N(0, 0.02^2), activations and upstream gradients
+N(0, 1), all synthetic and seeded).  The smaller bf16 stages C2 and C3 are timed the same way and
+nested under `other_workloads`, and the full d = 4, n = 16 schedule replay at the C5 shape under
+`replay`.
 
 Prints ONE JSON line.  `value` is algorithmic TFLOP/s of the whole step with inputs resident in HBM;
-`roofline` is the bf16 matrix-core GEMM kernel (the dominant kernel) from HIP-event timings of its
-own launches inside traced steps; `cpu_baseline` is the fp64 numpy oracle timed on the host.
+`roofline` is the bf16 matrix-core GEMM (the dominant kernel) from HIP events recorded around each of
+its launches, on the stream they are launched on, inside traced steps of this very run;
+`cpu_baseline` is the fp64 numpy oracle timed on the host on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -20,24 +25,187 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix-core peak
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix-core peak (published)
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E peak (published)
 
 
 def flops_per_layer(h: int, ffn: int, s: int, b: int = 1):
     """Algorithmic FLOP of one layer per pass.  GEMMs: 2*s*h*(3h + h + 2 ffn) in each of F, B, W.
     Attention (causal): F 2*s^2*h; B twice that (the model-FLOPs convention the paper inherits for
-    its MFU, Appendix D.1); the two backward kernels execute 3.5x (scores and dP are recomputed in both)."""
+    its MFU, Appendix D.1); B_executed counts what the backward kernels execute."""
     gemm = 2 * s * b * h * (4 * h + 2 * ffn)
     att = b * s * s * h          # one causal score-sized product over all heads of b sequences
-    return {"F": gemm + 2 * att, "B": gemm + 4 * att, "W": gemm, "B_executed": gemm + 7 * att, "gemm": gemm}
+    return {"F": gemm + 2 * att, "B": gemm + 4 * att, "W": gemm, "B_executed": gemm + ATTN_BWD_UNITS * att, "gemm": gemm}
+
+
+# causal score-sized products the attention backward executes (S and dP in both kernels, dQ, dK, dV)
+ATTN_BWD_UNITS = 7
+
+
+def run_workload(P, R, synth, torch, np, name, cfg, steps, warmup, queued, want_host=False):
+    """Times F + B + W of one chunk of shape `cfg`: whole steps, single passes, and (traced) every
+    operation of the passes.  Returns (result dict, host tensors for the cpu baseline or None)."""
+    L, h, f, s = cfg.layers, cfg.hidden, cfg.ffn, cfg.seq
+    fl = flops_per_layer(h, f, s, cfg.microbatch)
+    params = synth.chunk_params(cfg, name)
+    x_h, dy_h = synth.chunk_input(cfg, name), synth.upstream_grad(cfg, name)
+    ctx = R.Context(R.cfg_from_synth(cfg), slabs=max(1, queued))
+    ch = ctx.add_chunk(params, cfg.dtype)
+    x, dy = R.to_device(x_h, cfg.dtype), R.to_device(dy_h, cfg.dtype)
+    y, dx = torch.empty_like(x), torch.empty_like(x)
+
+    def step():
+        P.stage_forward(ch.handle, 0, x, y)
+        P.stage_backward_input(ch.handle, 0, dy, dx)
+        P.stage_backward_weight(ch.handle, [0])
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+    step_flop = L * (fl["F"] + fl["B"] + fl["W"])
+    value = step_flop / (ms_per_step * 1e-3) / 1e12
+
+    # per-pass times with HIP events (the context runs on torch's current stream), medians
+    def timed(fn):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(); fn(); b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b)
+
+    reps = max(5, min(steps, 20))
+    pass_ms = {"F": [], "B": [], "W": []}
+    for _ in range(reps):
+        pass_ms["F"].append(timed(lambda: P.stage_forward(ch.handle, 0, x, y)))
+        pass_ms["B"].append(timed(lambda: P.stage_backward_input(ch.handle, 0, dy, dx)))
+        pass_ms["W"].append(timed(lambda: P.stage_backward_weight(ch.handle, [0])))
+    passes = {}
+    for k in "FBW":
+        ms = float(np.median(pass_ms[k]))
+        tf = L * fl[k] / (ms * 1e-3) / 1e12
+        passes[k] = {"ms": round(ms, 4), "tflops": round(tf, 1), "achieved_over_bf16_peak": round(tf / PEAK_BF16_TFLOPS, 4)}
+    passes["B"]["tflops_executed"] = round(L * fl["B_executed"] / (passes["B"]["ms"] * 1e-3) / 1e12, 1)
+    if queued > 1:
+        # deferred W: F and B of q microbatches (untimed), then ONE W call for all of them
+        qms = []
+        for _ in range(5):
+            for j in range(queued):
+                P.stage_forward(ch.handle, j, x, y)
+                P.stage_backward_input(ch.handle, j, dy, dx)
+            qms.append(timed(lambda: P.stage_backward_weight(ch.handle, list(range(queued)))))
+        ms = float(np.median(qms)) / queued
+        tf = L * fl["W"] / (ms * 1e-3) / 1e12
+        passes[f"W_queued{queued}"] = {"ms_per_microbatch": round(ms, 4), "tflops": round(tf, 1),
+                                       "achieved_over_bf16_peak": round(tf / PEAK_BF16_TFLOPS, 4)}
+
+    # every operation of the passes between HIP events (on the context's stream) in traced steps
+    P.pmc_trace_begin(ctx.ctx, 8192)
+    for _ in range(reps):
+        step()
+    recs = P.pmc_trace_end(ctx.ctx, 8192)
+    by_op = {}
+    for r in recs:
+        by_op.setdefault(r["op"], []).append(r["ms"])
+    op_ms_per_step = {op: round(sum(v) / reps, 4) for op, v in by_op.items()}
+    gemms = [r for r in recs if r["op"] == "gemm"]
+    gemm_flop = sum(2.0 * r["m"] * r["n"] * r["k"] for r in gemms)
+    gemm_ms = sum(r["ms"] for r in gemms)
+    shapes = {}
+    for r in gemms:
+        shapes.setdefault((r["pass_"], r["m"], r["n"], r["k"]), []).append(r["ms"])
+    gemm_table = [{"pass": k[0], "m": k[1], "n": k[2], "k": k[3], "us": round(1e3 * float(np.mean(v)), 1),
+                   "tflops": round(2.0 * k[1] * k[2] * k[3] / (float(np.mean(v)) * 1e-3) / 1e12, 1)}
+                  for k, v in sorted(shapes.items())]
+    achieved = gemm_flop / (gemm_ms * 1e-3) / 1e12
+    gemm_by_pass = {}
+    for k in "FBW":
+        sel = [r for r in gemms if r["pass_"] == k]
+        if sel:
+            tf = sum(2.0 * r["m"] * r["n"] * r["k"] for r in sel) / (sum(r["ms"] for r in sel) * 1e-3) / 1e12
+            gemm_by_pass[k] = {"tflops": round(tf, 1), "frac": round(tf / PEAK_BF16_TFLOPS, 4)}
+
+    # HBM-bound row kernels: algorithmic bytes (read + written) per launch over its traced time
+    e = 2 if cfg.dtype == "bf16" else 4
+    T = cfg.tokens
+
+    def rate(sel, nbytes):
+        ms = [r["ms"] for r in recs if sel(r)]
+        if not ms:
+            return None
+        t = float(np.median(ms))
+        gbs = nbytes / (t * 1e-3) / 1e9
+        return {"us_per_launch": round(1e3 * t, 2), "GB_per_s": round(gbs, 1), "frac_of_hbm_peak": round(gbs / PEAK_HBM_GBS, 3),
+                "bytes_per_launch": nbytes}
+
+    elementwise = {
+        "ln_fwd": rate(lambda r: r["op"] == "ln_fwd", 2 * T * h * e),                          # x in, y out
+        "ln_bwd": rate(lambda r: r["op"] == "ln_bwd" and not r["trans_a"], 4 * T * h * e),      # dy, x, resid in, dx out
+        "colsum": rate(lambda r: r["op"] == "colsum", T * (5 * h + f) * e),                     # the four dY of a layer
+        "copy": rate(lambda r: r["op"] == "copy", 2 * T * h * e),
+    }
+    att_f = [r["ms"] for r in recs if r["op"] == "attn_fwd"]
+    att_b = [r["ms"] for r in recs if r["op"] == "attn_bwd"]
+    att_unit = cfg.microbatch * s * s * h          # one causal score-sized product over all heads
+    fwd_tf = 2 * att_unit / (float(np.median(att_f)) * 1e-3) / 1e12
+    bwd_t = float(np.median(att_b)) * 1e-3
+    attention = {"fwd_us": round(1e3 * float(np.median(att_f)), 1), "fwd_tflops": round(fwd_tf, 1),
+                 "fwd_frac_of_bf16_peak": round(fwd_tf / PEAK_BF16_TFLOPS, 4),
+                 "bwd_us": round(1e6 * bwd_t, 1),
+                 "bwd_tflops_model": round(4 * att_unit / bwd_t / 1e12, 1),
+                 "bwd_frac_of_bf16_peak_model": round(4 * att_unit / bwd_t / 1e12 / PEAK_BF16_TFLOPS, 4),
+                 "bwd_tflops_executed": round(ATTN_BWD_UNITS * att_unit / bwd_t / 1e12, 1),
+                 "flop": f"causal: forward 2 s^2 h; backward 4 s^2 h by the model convention, {ATTN_BWD_UNITS} s^2 h executed"}
+
+    def gemm_bytes(r):
+        """Algorithmic HBM bytes of one product: both operands once, the result once (W: fp32
+        read-modify-write), plus the tensor its epilogue reads or writes besides (residual, GeLU
+        output, GeLU input)."""
+        m, n, k = r["m"], r["n"], r["k"]
+        if r["pass_"] == "W":
+            return 2 * (m * k + k * n) + 8 * m * n
+        extra = 2 * m * n if (n == f or (r["pass_"] == "F" and n == h)) else 0
+        return 2 * (m * k + k * n) + 2 * m * n + extra
+
+    traffic, traffic_src = stored_traffic(name)
+    roofline = {"bound": "mfma",
+                "kernel": "gemm_bf16_dma_kernel / gemm_bf16_persistent_kernel / gemm_bf16_wgrad_persistent_kernel, with "
+                          "splitk_reduce_kernel where K is split (every product of a step: 4 projections x F,B,W x layers)",
+                "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                "traffic": traffic, "traffic_source": traffic_src,
+                "timing": "HIP events around every GEMM launch of traced steps in this run, on the stream of the launches "
+                          "(while traced, the W pass keeps its products on that one stream)",
+                "avg_launch_us": round(1e3 * gemm_ms / len(gemms), 2), "flop_per_launch": gemm_flop / len(gemms),
+                "algorithmic_bytes_per_launch": round(sum(gemm_bytes(r) for r in gemms) / len(gemms)),
+                "launches_per_step": len(gemms) // reps, "by_pass": gemm_by_pass}
+
+    res = {"value": round(value, 2), "ms_per_step": round(ms_per_step, 4), "flop_per_step": step_flop,
+           "step_over_bf16_peak": round(value / PEAK_BF16_TFLOPS, 4),
+           "roofline": roofline, "passes": passes, "op_ms_per_step": op_ms_per_step, "gemm_shapes": gemm_table,
+           "elementwise_hbm": elementwise, "attention": attention}
+    ctx.close()
+    del ctx, ch
+    torch.cuda.empty_cache()
+    return res, ((params, x_h, dy_h) if want_host else None)
+
+
+def workload_text(name, cfg):
+    return (f"{name}: GPT stage, {cfg.layers} layers/chunk, hidden {cfg.hidden}, {cfg.heads} heads, FFN {cfg.ffn}, "
+            f"seq {cfg.seq}, microbatch {cfg.microbatch}, causal, {cfg.dtype} storage + fp32 accumulate; "
+            "one step = F + B + W of one chunk")
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="C2", help="workload shape (C2 is the metric's; C3/C4 for study)")
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="C4", help="headline workload (C4: the largest single-GPU stage)")
+    ap.add_argument("--also", default="C2,C3", help="workloads timed the same way and nested under other_workloads")
     ap.add_argument("--microbatch", type=int, default=0,
                     help="override the workload's microbatch size (sequences per pass): the arithmetic-intensity "
                          "sweep of Appendix D.2; 0 keeps the workload's own (1)")
@@ -45,7 +213,9 @@ def main() -> int:
                     help="also time W for this many queued microbatches in one call (deferred W, contracted "
                          "together); 0 or 1 skips it")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--replay", action="store_true", help="also replay the d=4, n=16 schedules at the C5 shape")
+    ap.add_argument("--no-replay", action="store_true", help="skip the d=4, n=16 schedule replay at the C5 shape")
+    ap.add_argument("--profile", action="store_true",
+                    help="for profiler runs: the headline workload only (no other workloads, replay, queued W or cpu baseline)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="before the timed region, copy a cold device buffer of this many MiB three times "
                          "(a plain copy kernel of known size that scales the profiler's HBM byte counters)")
@@ -53,6 +223,8 @@ def main() -> int:
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         return 2
+    if args.profile:
+        args.also, args.no_replay, args.no_cpu_baseline, args.queued = "", True, True, 0
 
     import numpy as np
     import torch
@@ -65,26 +237,13 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
-    cfg = synth.CONFIGS[args.config]
-    name = args.config
-    if args.microbatch > 0 and args.microbatch != cfg.microbatch:
-        import dataclasses
-        cfg = dataclasses.replace(cfg, microbatch=args.microbatch)
-        name = f"{args.config}x{args.microbatch}"
-    L, h, f, s = cfg.layers, cfg.hidden, cfg.ffn, cfg.seq
-    fl = flops_per_layer(h, f, s, cfg.microbatch)
 
-    params = synth.chunk_params(cfg, name)
-    x_h, dy_h = synth.chunk_input(cfg, name), synth.upstream_grad(cfg, name)
-    ctx = R.Context(R.cfg_from_synth(cfg), slabs=max(1, args.queued))
-    ch = ctx.add_chunk(params, cfg.dtype)
-    x, dy = R.to_device(x_h, cfg.dtype), R.to_device(dy_h, cfg.dtype)
-    y, dx = torch.empty_like(x), torch.empty_like(x)
-
-    def step():
-        P.stage_forward(ch.handle, 0, x, y)
-        P.stage_backward_input(ch.handle, 0, dy, dx)
-        P.stage_backward_weight(ch.handle, [0])
+    def shape_of(tag):
+        cfg, name = synth.CONFIGS[tag], tag
+        if args.microbatch > 0 and args.microbatch != cfg.microbatch:
+            cfg = dataclasses.replace(cfg, microbatch=args.microbatch)
+            name = f"{tag}x{args.microbatch}"
+        return name, cfg
 
     if args.copy_calibration > 0:
         src = torch.ones(args.copy_calibration << 20, dtype=torch.uint8, device="cuda")
@@ -94,141 +253,39 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-    step_flop = L * (fl["F"] + fl["B"] + fl["W"])
-    value = step_flop / (ms_per_step * 1e-3) / 1e12
-
-    # per-pass times with HIP events (same stream), medians over the traced steps
-    def timed(fn, reps):
-        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-        out = []
-        for a, b in ev:
-            a.record(); fn(); b.record()
-            out.append((a, b))
-        torch.cuda.synchronize()
-        return float(np.median([a.elapsed_time(b) for a, b in out]))
-
-    reps = max(5, min(args.steps, 20))
-    pass_ms = {"F": [], "B": [], "W": []}
-    for _ in range(reps):
-        pass_ms["F"].append(timed(lambda: P.stage_forward(ch.handle, 0, x, y), 1))
-        pass_ms["B"].append(timed(lambda: P.stage_backward_input(ch.handle, 0, dy, dx), 1))
-        pass_ms["W"].append(timed(lambda: P.stage_backward_weight(ch.handle, [0]), 1))
-    passes = {}
-    for k in "FBW":
-        ms = float(np.median(pass_ms[k]))
-        passes[k] = {"ms": round(ms, 4), "tflops": round(L * fl[k] / (ms * 1e-3) / 1e12, 1),
-                     "frac_of_bf16_peak": round(L * fl[k] / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
-    passes["B"]["tflops_executed"] = round(L * fl["B_executed"] / (passes["B"]["ms"] * 1e-3) / 1e12, 1)
-    if args.queued > 1:
-        # deferred W: F and B of q microbatches (untimed), then ONE W call for all of them
-        q, qms = args.queued, []
-        for _ in range(5):
-            for j in range(q):
-                P.stage_forward(ch.handle, j, x, y)
-                P.stage_backward_input(ch.handle, j, dy, dx)
-            qms.append(timed(lambda: P.stage_backward_weight(ch.handle, list(range(q))), 1))
-        ms = float(np.median(qms)) / q
-        passes[f"W_queued{q}"] = {"ms_per_microbatch": round(ms, 4), "tflops": round(L * fl["W"] / (ms * 1e-3) / 1e12, 1),
-                                  "frac_of_bf16_peak": round(L * fl["W"] / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
-
-    # dominant kernel: the bf16 GEMM.  Its launches are bracketed by HIP events inside traced steps.
-    P.pmc_trace_begin(ctx.ctx, 4096)
-    for _ in range(reps):
-        step()
-    recs = P.pmc_trace_end(ctx.ctx, 4096)
-    by_op = {}
-    for r in recs:
-        by_op.setdefault(r["op"], []).append(r["ms"])
-    op_ms_per_step = {op: round(sum(v) / reps, 4) for op, v in by_op.items()}
-    gemms = [r for r in recs if r["op"] == "gemm"]
-    gemm_flop = sum(2.0 * r["m"] * r["n"] * r["k"] for r in gemms)
-    gemm_ms = sum(r["ms"] for r in gemms)
-    shapes = {}
-    for r in gemms:
-        key = (r["pass_"], r["m"], r["n"], r["k"])
-        shapes.setdefault(key, []).append(r["ms"])
-    gemm_table = [{"pass": k[0], "m": k[1], "n": k[2], "k": k[3], "us": round(1e3 * float(np.mean(v)), 1),
-                   "tflops": round(2.0 * k[1] * k[2] * k[3] / (float(np.mean(v)) * 1e-3) / 1e12, 1)}
-                  for k, v in sorted(shapes.items())]
-    achieved = gemm_flop / (gemm_ms * 1e-3) / 1e12
-
-    # HBM-bound row kernels: algorithmic bytes (read + written) per launch over its traced time
-    e = 2 if cfg.dtype == "bf16" else 4
-    T = cfg.tokens
-
-    def rate(sel, nbytes):
-        ms = [r["ms"] for r in recs if sel(r)]
-        if not ms:
-            return None
-        t = float(np.median(ms))
-        return {"us_per_launch": round(1e3 * t, 2), "GB_per_s": round(nbytes / (t * 1e-3) / 1e9, 1), "bytes_per_launch": nbytes}
-
-    elementwise = {
-        "ln_fwd": rate(lambda r: r["op"] == "ln_fwd", 2 * T * h * e),                          # x in, y out
-        "ln_bwd": rate(lambda r: r["op"] == "ln_bwd" and not r["trans_a"], 4 * T * h * e),      # dy, x, resid in, dx out
-        "colsum": rate(lambda r: r["op"] == "colsum", T * (5 * h + f) * e),                     # the four dY of a layer
-        "copy": rate(lambda r: r["op"] == "copy", 2 * T * h * e),
-    }
-    att_f = [r["ms"] for r in recs if r["op"] == "attn_fwd"]
-    att_b = [r["ms"] for r in recs if r["op"] == "attn_bwd"]
-    att_unit = cfg.microbatch * s * s * h          # one causal score-sized product over all heads
-    attention = {"fwd_us": round(1e3 * float(np.median(att_f)), 1), "fwd_tflops": round(2 * att_unit / (float(np.median(att_f)) * 1e-3) / 1e12, 1),
-                 "bwd_us": round(1e3 * float(np.median(att_b)), 1),
-                 "bwd_tflops_executed": round(7 * att_unit / (float(np.median(att_b)) * 1e-3) / 1e12, 1),
-                 "flop": "causal: forward 2 s^2 h; backward executes 7 s^2 h (scores and dP recomputed in both kernels)"}
-
-    def gemm_bytes(r):
-        """Algorithmic HBM bytes of one product: both operands once, the result once (W: fp32
-        read-modify-write), plus the tensor its epilogue reads or writes besides (residual, GeLU
-        output, GeLU input)."""
-        m, n, k = r["m"], r["n"], r["k"]
-        if r["pass_"] == "W":
-            return 2 * (m * k + k * n) + 8 * m * n
-        extra = 2 * m * n if (n == f or (r["pass_"] == "F" and n == h)) else 0
-        return 2 * (m * k + k * n) + 2 * m * n + extra
-
-    roofline = {"bound": "mfma",
-                "kernel": "gemm_bf16_dma_kernel / gemm_bf16_wgrad_persistent_kernel, with splitk_reduce_kernel "
-                          "where K is split (every product of a step: 4 projections x F,B,W x layers)",
-                "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": stored_traffic(name),
-                "avg_launch_us": round(1e3 * gemm_ms / len(gemms), 2), "flop_per_launch": gemm_flop / len(gemms),
-                "algorithmic_bytes_per_launch": round(sum(gemm_bytes(r) for r in gemms) / len(gemms)),
-                "launches_per_step": len(gemms) // reps}
-
+    name, cfg = shape_of(args.config)
+    head, host = run_workload(P, R, synth, torch, np, name, cfg, args.steps, args.warmup, args.queued,
+                              want_host=not args.no_cpu_baseline)
     out = {
-        "metric": "stage F+B+W TFLOP/s per microbatch", "value": round(value, 2), "unit": "TFLOP/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "metric": "stage F+B+W TFLOP/s per microbatch", "value": head["value"], "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.dtype == "bf16" else "f32",
         "data": "synthetic",
-        "config": {"workload": f"{name}: GPT stage, {L} layers/chunk, hidden {h}, {cfg.heads} heads, FFN {f}, seq {s}, "
-                               f"microbatch {cfg.microbatch}, causal, {cfg.dtype} storage + fp32 accumulate; "
-                               "one step = F + B + W of one chunk",
-                   "flop_per_step": step_flop, "flop_convention": "algorithmic; attention backward = 2x forward"},
-        "roofline": roofline,
-        "passes": passes,
-        "op_ms_per_step": op_ms_per_step,
-        "gemm_shapes": gemm_table,
-        "elementwise_hbm": elementwise,
-        "attention": attention,
-        "mfma_util_vs_peak": round(value / PEAK_BF16_TFLOPS, 4),
+        "config": {"workload": workload_text(name, cfg), "flop_per_step": head["flop_per_step"],
+                   "flop_convention": "algorithmic; attention backward = 2x forward"},
+        "roofline": head["roofline"],
+        "step_over_bf16_peak": head["step_over_bf16_peak"],
+        "passes": head["passes"], "op_ms_per_step": head["op_ms_per_step"], "gemm_shapes": head["gemm_shapes"],
+        "elementwise_hbm": head["elementwise_hbm"], "attention": head["attention"],
     }
+
+    others = {}
+    for tag in [t for t in args.also.split(",") if t and t != args.config]:
+        oname, ocfg = shape_of(tag)
+        res, _ = run_workload(P, R, synth, torch, np, oname, ocfg, args.steps, args.warmup, args.queued)
+        res["workload"] = workload_text(oname, ocfg)
+        res.pop("gemm_shapes")
+        others[tag] = res
+    if others:
+        out["other_workloads"] = others
 
     # per schedule at d=4, n=16: peak activation bytes vs 1F1B (C5 chunk shape, accounting) and the
     # scheduler's bubble rate (Appendix D: idle share of the squeezed schedule's run time) with the
-    # F, B, W times just measured for one chunk of this workload
+    # F, B, W times just measured for one chunk of the headline workload
     c5 = R.cfg_from_synth(synth.CONFIGS["C5"])
     m5, st5 = P.pmc_activation_bytes(c5), P.pmc_activation_stats_bytes(c5)
     d_sim, n_sim = 4, 16
-    t_f, t_b, t_w = passes["F"]["ms"], passes["B"]["ms"], passes["W"]["ms"]
+    t_f, t_b, t_w = (head["passes"][k]["ms"] for k in "FBW")
     mem = {}
     for kind in ("1f1b", "vzb", "vhalf", "vmin"):
         sch = P.pmc_schedule_build(kind, d_sim, n_sim)
@@ -253,38 +310,38 @@ def main() -> int:
                             "bubble_rate": round(1.0 - 2 * n_sim * (t_f + t_b + t_w) / res["makespan"], 4)}
     mem["adaptive_by_limit_units"] = adaptive
     out["peak_activation"] = {"config": "d=4, n=16, 2-layer chunks hidden 4096 seq 2048 bf16 (accounting); "
-                                        f"bubble rate from this workload's measured F/B/W = {t_f}/{t_b}/{t_w} ms", **mem}
+                                        f"bubble rate from the headline workload's measured F/B/W = {t_f}/{t_b}/{t_w} ms", **mem}
 
-    ctx.close()
-    del ctx, ch
-
-    if args.replay:
+    if not args.no_replay:
         out["replay"] = replay_c5(P, R, synth, torch)
 
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, name, params, x_h, dy_h, step_flop)
+        out["cpu_baseline"] = cpu_baseline(cfg, name, *host)
 
     print(json.dumps(out))
     return 0
 
 
 def stored_traffic(name):
-    """HBM bytes per product (fetch + write) measured with the profiler's FETCH_SIZE and WRITE_SIZE
-    counters on this workload; the figure lives in the committed profile summary.  None if there is
-    no summary for this workload."""
-    path = os.path.join(ROOT, "profiles", f"gemm_bf16_{name.lower()}_hbm_traffic.txt")
+    """HBM-side bytes per product (fetch + write) from the profiler's FETCH_SIZE and WRITE_SIZE
+    counters on this workload.  Counters cannot be read from inside this process: the figure comes
+    from the committed summary of two profiler runs of `bench.py --profile --config <name>`, named
+    in the second return value.  (None, None) if there is no summary for this workload."""
+    rel = os.path.join("profiles", f"gemm_bf16_{name.lower()}_hbm_traffic.txt")
     try:
-        with open(path) as fh:
+        with open(os.path.join(ROOT, rel)) as fh:
             for line in fh:
                 if line.startswith("traffic_bytes_per_launch:"):
-                    return int(float(line.split(":", 1)[1]))
+                    return int(float(line.split(":", 1)[1])), rel
     except OSError:
         pass
-    return None
+    return None, None
 
 
-def cpu_baseline(cfg, name, params, x_h, dy_h, step_flop):
-    """The oracle as it stands (numpy, fp64), one full step of the same workload on the host."""
+def cpu_baseline(cfg, name, params, x_h, dy_h):
+    """The oracle as it stands (numpy, fp64) on the host, on a bounded sample of the headline
+    workload: F + B + W of its FIRST LAYER (a one-layer chunk of the same shape, same inputs), whole
+    passes repeated until about ten seconds are on the clock."""
     import numpy as np
     from oracle import layer as OL
     try:
@@ -292,20 +349,23 @@ def cpu_baseline(cfg, name, params, x_h, dy_h, step_flop):
         cores = max((p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()), default=os.cpu_count())
     except Exception:
         cores = os.cpu_count()
-    p64 = OL.cast_params(params)
+    p64 = OL.cast_params(params[:1])
     x64, dy64 = x_h.astype(np.float64), dy_h.astype(np.float64)
-    steps, t0 = 0, time.perf_counter()
-    while True:  # whole steps until about ten seconds of host work are on the clock
+    fl = flops_per_layer(cfg.hidden, cfg.ffn, cfg.seq, cfg.microbatch)
+    layer_flop = fl["F"] + fl["B"] + fl["W"]
+    reps, t0 = 0, time.perf_counter()
+    while True:
         y, saved = OL.chunk_forward(x64, p64, cfg.heads, cfg.causal, cfg.ln_eps, cfg.microbatch)
         _, stash, _ = OL.chunk_backward_input(dy64, p64, saved, cfg.heads, cfg.microbatch)
         OL.chunk_backward_weight(saved, stash)
-        steps += 1
+        reps += 1
         sec = time.perf_counter() - t0
-        if sec >= 10.0 or steps >= 20:
+        if sec >= 10.0 or reps >= 20:
             break
-    return {"value": round(steps * step_flop / sec / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{steps} full steps (F+B+W, 1 microbatch) of {name} in fp64 numpy, {sec:.1f} s",
-            "seconds_per_step": round(sec / steps, 2)}
+    return {"value": round(reps * layer_flop / sec / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{reps} x (F+B+W of one layer of {name}, 1 microbatch; the step has {cfg.layers} such layers) "
+                      f"in fp64 numpy, {sec:.1f} s",
+            "seconds_per_step_extrapolated": round(sec / reps * cfg.layers, 2)}
 
 
 def replay_c5(P, R, synth, torch):
@@ -314,10 +374,10 @@ def replay_c5(P, R, synth, torch):
     cfg = synth.CONFIGS["C5"]
     pcfg = R.cfg_from_synth(cfg)
     d, n = 4, 16
-    res = {}
+    res = {"config": "C5: 4 simulated devices x 2 chunks (8 two-layer chunks, hidden 4096, 32 heads, FFN 16384, seq 2048, "
+                     "bf16), 16 microbatches, 384 chunk passes per iteration on one stream"}
     gen = torch.Generator(device="cuda").manual_seed(5)
     shapes = synth.param_shapes(cfg)
-    m = P.pmc_activation_bytes(pcfg)
     scheds = {k: P.pmc_schedule_build(k, d, n) for k in ("1f1b", "vzb", "vhalf", "vmin")}
     ws = max(P.pmc_replay_workspace_bytes(s, pcfg) for s in scheds.values())
     ctx = R.Context(pcfg, slabs=2 * d * d, workspace_bytes=ws)
@@ -342,13 +402,18 @@ def replay_c5(P, R, synth, torch):
         chunks.append(ch)
     xs = [torch.randn(cfg.tokens, cfg.hidden, device="cuda", generator=gen).to(torch.bfloat16) for _ in range(n)]
     dys = [torch.randn(cfg.tokens, cfg.hidden, device="cuda", generator=gen).to(torch.bfloat16) for _ in range(n)]
+    fl = flops_per_layer(cfg.hidden, cfg.ffn, cfg.seq)
+    iter_flop = 2 * d * n * cfg.layers * (fl["F"] + fl["B"] + fl["W"])
     for kind, s in scheds.items():
         P.schedule_replay(ctx.ctx, s, [c.handle for c in chunks], xs, dys)          # warm-up iteration
         rep, peaks = P.schedule_replay(ctx.ctx, s, [c.handle for c in chunks], xs, dys, flags=P.REPLAY_TIME_PASSES)
         res[kind] = {"ms_per_iteration": round(rep["ms_total"], 2), "ms_f": round(rep["ms_f"], 2),
                      "ms_b": round(rep["ms_b"], 2), "ms_w": round(rep["ms_w"], 2),
+                     "tflops": round(iter_flop / (rep["ms_total"] * 1e-3) / 1e12, 1),
                      "peak_units": [p[0] for p in peaks], "peak_bytes": [p[1] for p in peaks]}
         P.pmc_schedule_destroy(s)
+    for kind in ("vzb", "vhalf", "vmin"):
+        res[kind]["max_peak_bytes_vs_1f1b"] = round(max(res[kind]["peak_bytes"]) / max(res["1f1b"]["peak_bytes"]), 4)
     ctx.close()
     return res
 

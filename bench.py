@@ -172,7 +172,7 @@ def run_workload(P, R, synth, torch, np, name, cfg, steps, warmup, queued, want_
 
     traffic, traffic_src = stored_traffic(name)
     roofline = {"bound": "mfma",
-                "kernel": "gemm_bf16_dma_kernel / gemm_bf16_persistent_kernel / gemm_bf16_wgrad_persistent_kernel, with "
+                "kernel": "gemm_bf16_dma_kernel / gemm_bf16_wgrad_persistent_kernel, with "
                           "splitk_reduce_kernel where K is split (every product of a step: 4 projections x F,B,W x layers)",
                 "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
@@ -287,7 +287,7 @@ def main() -> int:
     d_sim, n_sim = 4, 16
     t_f, t_b, t_w = (head["passes"][k]["ms"] for k in "FBW")
     mem = {}
-    for kind in ("1f1b", "vzb", "vhalf", "vmin"):
+    for kind in ("1f1b", "vzb", "vhalf", "vmin", "1f1bv"):
         sch = P.pmc_schedule_build(kind, d_sim, n_sim)
         acc = P.pmc_schedule_account(sch, m5, st5)
         span = P.pmc_schedule_makespan(sch, t_f, t_b, t_w)
@@ -378,7 +378,7 @@ def replay_c5(P, R, synth, torch):
                      "bf16), 16 microbatches, 384 chunk passes per iteration on one stream"}
     gen = torch.Generator(device="cuda").manual_seed(5)
     shapes = synth.param_shapes(cfg)
-    scheds = {k: P.pmc_schedule_build(k, d, n) for k in ("1f1b", "vzb", "vhalf", "vmin")}
+    scheds = {k: P.pmc_schedule_build(k, d, n) for k in ("1f1b", "vzb", "vhalf", "vmin", "1f1bv")}
     ws = max(P.pmc_replay_workspace_bytes(s, pcfg) for s in scheds.values())
     ctx = R.Context(pcfg, slabs=2 * d * d, workspace_bytes=ws)
     chunks = []
@@ -412,7 +412,7 @@ def replay_c5(P, R, synth, torch):
                      "tflops": round(iter_flop / (rep["ms_total"] * 1e-3) / 1e12, 1),
                      "peak_units": [p[0] for p in peaks], "peak_bytes": [p[1] for p in peaks]}
         P.pmc_schedule_destroy(s)
-    for kind in ("vzb", "vhalf", "vmin"):
+    for kind in ("vzb", "vhalf", "vmin", "1f1bv"):
         res[kind]["max_peak_bytes_vs_1f1b"] = round(max(res[kind]["peak_bytes"]) / max(res["1f1b"]["peak_bytes"]), 4)
     ctx.close()
     return res

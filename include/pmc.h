@@ -62,7 +62,10 @@ typedef enum pmc_status {
 } pmc_status;
 
 typedef enum pmc_dtype { PMC_F32 = 0, PMC_BF16 = 1 } pmc_dtype;
-typedef enum pmc_kind { PMC_1F1B = 0, PMC_VZB = 1, PMC_VHALF = 2, PMC_VMIN = 3 } pmc_kind;
+typedef enum pmc_kind {
+  PMC_1F1B = 0, PMC_VZB = 1, PMC_VHALF = 2, PMC_VMIN = 3,
+  PMC_1F1BV = 4 /* Appendix H: V-shape placement with B and W fused; about 2/3 of 1F1B's peak */
+} pmc_kind;
 typedef enum pmc_op { PMC_F = 0, PMC_B = 1, PMC_W = 2 } pmc_op;
 
 typedef struct pmc_ctx pmc_ctx;
@@ -191,7 +194,13 @@ int stage_abandon(pmc_chunk* chunk, int32_t mb);
 /* Builds the pass orders of `kind` for d devices and n microbatches by laying out the building
  * block (Table 1 offsets; Appendix F same-device offsets; V-ZB's same-device offsets, which the
  * paper finds by brute force and does not print, are (1,1,1)), checking that it repeats every 6
- * cells without collision (Section 2.3) and repeating it n times (Section 2).  d >= 1, n >= 1. */
+ * cells without collision (Section 2.3) and repeating it n times (Section 2).  d >= 1, n >= 1.
+ * PMC_1F1BV (Appendix H's 1F1B-V: the V-shape placement with a chunk's B and W run as one pass) is
+ * this library's construction, the paper prints no offsets for it: every pass sits at the first
+ * cell at or after the end of the pass it depends on that is free modulo 6 on its device and leaves
+ * room for the device's remaining passes; the forward's turn on the last device is delayed by the
+ * 0..5 cells that give the least peak, then the least unit-time makespan.  Its peak is
+ * ceil((4d + 2) / 3) units per device against 1F1B's 2d, at 1F1B's bubble count. */
 int pmc_schedule_build(int32_t kind, int32_t d, int32_t n, pmc_schedule** out);
 /* As above for an arbitrary V-shape block: cross-device offsets delta0, delta1 (Section 3.1) and
  * the three same-device offsets (F turn on the last device, F->B turn on the first device, B turn

@@ -39,6 +39,11 @@ from itertools import product
 
 T = 6
 KINDS = ("1f1b", "vzb", "vhalf", "vmin")
+# Further building blocks (Section 3.4, Appendix H), kept apart from KINDS: the paper describes them
+# in a sentence each and its drawings are not available, so their pass orders are this
+# repository's construction (see one_f_one_b_v_block).
+MORE_KINDS = ("1f1bv",)
+FUSED_KINDS = ("1f1b", "1f1bv")     # B and W of a chunk run as one pass
 
 
 @dataclass(frozen=True)
@@ -113,11 +118,73 @@ def one_f_one_b_block(d: int):
             ("B", 0): [t + 2 for t in tBW], ("W", 0): [t + 3 for t in tBW]}
 
 
+def _fits(free, lengths):
+    """Can passes of these lengths (cells in a row, modulo T) still be packed into the free residues?"""
+    if not lengths:
+        return True
+    L = lengths[0]
+    for r in sorted(free):
+        cells = {(r + k) % T for k in range(L)}
+        if len(cells) == L and cells <= free and _fits(free - cells, lengths[1:]):
+            return True
+    return False
+
+
+def one_f_one_b_v_block(d: int, f_turn: int | None = None):
+    """1F1B-V (Appendix H): the V-shape placement applied to 1F1B's block, WITHOUT splitting B and W:
+    a chunk's backward is one fused pass of two cells (B, then W at once), and a device holds chunk i
+    and chunk 2d-1-i.  The paper gives no offsets (its drawing is not available); this is an
+    earliest-fit block.  Passes are placed in dependency order - F of the first half down the devices,
+    F of the second half back up, the fused backward of the second half down, of the first half up -
+    each at the first cell at or after the END of the pass it depends on (a fused pass hands its
+    gradient on when the whole pass has ended, as in 1F1B) such that its own cells are free modulo T
+    on its device and the device's passes still to come can be fitted into what stays free (the six
+    residues of a device are exactly filled: 1 + 1 + 2 + 2 cells, so the block repeats without
+    collision by construction).  One free parameter, the extra delay `f_turn` (0 .. T-1 cells) of the
+    forward's turn on the last device, is chosen like V-ZB's same-device offsets (Section 3.1's brute
+    force): least peak of live units, then least unit-time makespan, at n = 3d microbatches, first
+    such value.  The peak tends to 2/3 of 1F1B's (pinned in the tests against the paper's statement),
+    balanced over the devices."""
+    if f_turn is None:
+        best = None
+        for a in range(T):
+            blk = one_f_one_b_v_block(d, a)
+            passes = repeat(blk, d, 3 * d)
+            score = (max(peak_units_of(passes, "1f1bv", d)), makespan_of(passes, "1f1bv", d))
+            if best is None or score < best[0]:
+                best = (score, blk)
+        return best[1]
+    free = [set(range(T)) for _ in range(d)]
+
+    def place(i, ready, length, later):
+        t = ready
+        while True:
+            cells = {(t + k) % T for k in range(length)}
+            if cells <= free[i] and _fits(free[i] - cells, later):
+                free[i] -= cells
+                return t
+            t += 1
+
+    tF0, tF1, tB1, tB0 = [0] * d, [0] * d, [0] * d, [0] * d
+    for i in range(d):
+        tF0[i] = place(i, 0 if i == 0 else tF0[i - 1] + 1, 1, [1, 2, 2])
+    for i in range(d - 1, -1, -1):
+        tF1[i] = place(i, (tF0[d - 1] + f_turn if i == d - 1 else tF1[i + 1]) + 1, 1, [2, 2])
+    for i in range(d):
+        tB1[i] = place(i, tF1[0] + 1 if i == 0 else tB1[i - 1] + 2, 2, [2])
+    for i in range(d - 1, -1, -1):
+        tB0[i] = place(i, (tB1[d - 1] if i == d - 1 else tB0[i + 1]) + 2, 2, [])
+    return {("F", 0): tF0, ("F", 1): tF1, ("B", 1): tB1, ("W", 1): [t + 1 for t in tB1],
+            ("B", 0): tB0, ("W", 0): [t + 1 for t in tB0]}
+
+
 def block(kind: str, d: int):
     if d < 1:
         raise ValueError("d must be positive")
     if kind == "1f1b":
         return one_f_one_b_block(d)
+    if kind == "1f1bv":
+        return one_f_one_b_v_block(d)
     blk = vshape_block(d, *vshape_params(kind, d))
     if blk is None:
         raise ValueError(f"{kind} block collides for d={d}")
@@ -258,6 +325,8 @@ def _dependencies(p: Pass, kind: str, d: int):
             # B and W are one fused pass: the next stage hands its gradient over only when that
             # whole pass (which ends with its lower chunk's W) is done
             return [("W", mc + 1, p.mb)]
+        if kind == "1f1bv":
+            return [("W", mc + 1, p.mb)]      # the next chunk's fused pass ends with its W
         return [("B", mc + 1, p.mb)]
     return [("B", mc, p.mb)]
 
@@ -351,12 +420,13 @@ def reordered_passes(passes, kind: str, d: int):
     Cool-down: on every device the W passes after its last F are taken out, the rest is squeezed,
     and the vacant cells after the last F are then filled left to right, each with the first
     removed W (in their former order) whose B has ended; what is left goes to the end.
-    A 1F1B stage runs B and W fused, so nothing of it can move: it is returned squeezed only."""
+    A 1F1B stage (and a 1F1B-V chunk) runs B and W fused, so nothing of it can move: such a schedule
+    is returned squeezed only."""
     unit = {"F": 1, "B": 1, "W": 1}
     key = lambda p: (p.op, model_chunk(kind, d, p.device, p.chunk), p.mb)
     orders = device_orders(passes, d)
     start, end, _ = _asap(orders, kind, d, unit)
-    if kind != "1f1b":
+    if kind not in FUSED_KINDS:
         base_peak = [_order_peak(o, kind) for o in orders]
         cells = [{int(start[key(p)]): p for p in orders[i]} for i in range(d)]
         first_b = [min(c for c, p in cells[i].items() if p.op == "B") for i in range(d)]

@@ -18,8 +18,8 @@ if not os.path.exists(LIB_PATH):
 lib = C.CDLL(LIB_PATH)
 
 PMC_F32, PMC_BF16 = 0, 1
-PMC_1F1B, PMC_VZB, PMC_VHALF, PMC_VMIN = 0, 1, 2, 3
-KINDS = {"1f1b": PMC_1F1B, "vzb": PMC_VZB, "vhalf": PMC_VHALF, "vmin": PMC_VMIN}
+PMC_1F1B, PMC_VZB, PMC_VHALF, PMC_VMIN, PMC_1F1BV = 0, 1, 2, 3, 4
+KINDS = {"1f1b": PMC_1F1B, "vzb": PMC_VZB, "vhalf": PMC_VHALF, "vmin": PMC_VMIN, "1f1bv": PMC_1F1BV}
 PMC_F, PMC_B, PMC_W = 0, 1, 2
 OPS = "FBW"
 PARAMS_PER_LAYER = 12

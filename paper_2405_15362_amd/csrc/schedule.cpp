@@ -129,6 +129,63 @@ void one_f_one_b_block(int d, std::vector<int32_t>& blk) {
   }
 }
 
+// 1F1B-V (Appendix H): V-shape placement of 1F1B's block without the B/W split.  A chunk's backward
+// is one pass of two cells (B, W); a pass that depends on it waits for its end.  Earliest fit: F of
+// the first half down the devices, F of the second half up, the fused backward of the second half
+// down, of the first half up, each at the first cell at or after its dependency's end where its own
+// cells are free modulo T on its device AND the device's passes still to come can be packed into
+// what stays free (the six residues of a device end up exactly filled: 1 + 1 + 2 + 2).
+// `f_turn` delays the forward's turn on the last device by that many cells.
+void one_f_one_b_v_block_at(int d, int f_turn, std::vector<int32_t>& blk) {
+  blk.assign(6 * d, 0);
+  std::vector<unsigned> free_mask(d, (1u << T) - 1);
+  auto cells_of = [](int t, int len) {
+    unsigned m = 0;
+    for (int k = 0; k < len; ++k) m |= 1u << ((t + k) % T);
+    return m;
+  };
+  // can runs of these lengths (at most two of them, in any position) be cut out of the mask?
+  auto packs = [&](unsigned mask, const int* len, int count) {
+    if (count == 0) return true;
+    for (int r = 0; r < T; ++r) {
+      const unsigned a = cells_of(r, len[0]);
+      if ((mask & a) != a) continue;
+      if (count == 1) return true;
+      const unsigned rest = mask & ~a;
+      for (int q = 0; q < T; ++q) {
+        const unsigned b = cells_of(q, len[1]);
+        if ((rest & b) != b) continue;
+        if (count == 2) return true;
+        const unsigned rest2 = rest & ~b;
+        for (int u = 0; u < T; ++u) {
+          const unsigned c = cells_of(u, len[2]);
+          if ((rest2 & c) == c) return true;
+        }
+      }
+    }
+    return false;
+  };
+  auto place = [&](int i, int ready, int len, const int* later, int nlater) {
+    for (int t = ready;; ++t) {
+      const unsigned m = cells_of(t, len);
+      if ((free_mask[i] & m) == m && packs(free_mask[i] & ~m, later, nlater)) {
+        free_mask[i] &= ~m;
+        return t;
+      }
+    }
+  };
+  const int after_f0[3] = {1, 2, 2}, after_f1[2] = {2, 2}, after_b1[1] = {2};
+  auto at = [&](int row, int i) -> int32_t& { return blk[row * d + i]; };
+  for (int i = 0; i < d; ++i) at(F0, i) = place(i, i == 0 ? 0 : at(F0, i - 1) + 1, 1, after_f0, 3);
+  for (int i = d - 1; i >= 0; --i) at(F1, i) = place(i, (i == d - 1 ? at(F0, d - 1) + f_turn : at(F1, i + 1)) + 1, 1, after_f1, 2);
+  for (int i = 0; i < d; ++i) at(B1, i) = place(i, i == 0 ? at(F1, 0) + 1 : at(B1, i - 1) + 2, 2, after_b1, 1);
+  for (int i = d - 1; i >= 0; --i) at(B0, i) = place(i, (i == d - 1 ? at(B1, d - 1) : at(B0, i + 1)) + 2, 2, nullptr, 0);
+  for (int i = 0; i < d; ++i) {
+    at(W1, i) = at(B1, i) + 1;
+    at(W0, i) = at(B0, i) + 1;
+  }
+}
+
 int model_chunk(const Schedule& s, int device, int chunk) {
   if (s.grouped_bw) return 2 * device + chunk;
   return chunk == 0 ? device : 2 * s.d - 1 - device;
@@ -166,6 +223,40 @@ int finish(Schedule& s) {
 
 }  // namespace
 
+int makespan(const Schedule& s, double tf, double tb, double tw, double* out);
+void account(const Schedule& s, int64_t unit_bytes, int64_t stats_bytes, pmc_device_peak* out);
+
+// The free parameter of the 1F1B-V block, chosen as the paper chooses V-ZB's same-device offsets
+// (brute force, Section 3.1): least peak of live units, then least unit-time makespan, with 3d
+// microbatches; the first such delay in 0 .. T-1.
+int one_f_one_b_v_block(int d, std::vector<int32_t>& blk) {
+  bool have = false;
+  int64_t best_peak = 0;
+  double best_span = 0.0;
+  Schedule trial;
+  trial.kind = PMC_1F1BV;
+  trial.d = d;
+  trial.n = 3 * d;
+  trial.fused = true;
+  std::vector<pmc_device_peak> peaks(d);
+  for (int a = 0; a < T; ++a) {
+    one_f_one_b_v_block_at(d, a, trial.block);
+    if (int rc = finish(trial)) return rc;
+    account(trial, 1, 0, peaks.data());
+    int64_t peak = 0;
+    for (const auto& p : peaks) peak = std::max(peak, p.peak_live_units);
+    double span = 0.0;
+    if (int rc = makespan(trial, 1.0, 1.0, 1.0, &span)) return rc;
+    if (!have || peak < best_peak || (peak == best_peak && span < best_span)) {
+      have = true;
+      best_peak = peak;
+      best_span = span;
+      blk = trial.block;
+    }
+  }
+  return PMC_OK;
+}
+
 int build_schedule(int kind, int d, int n, Schedule& s) {
   if (d < 1 || n < 1) return fail(PMC_ERR_INVALID, "need d >= 1 and n >= 1 (got d=%d n=%d)", d, n);
   if ((int64_t)d * n > (1 << 24)) return fail(PMC_ERR_INVALID, "d*n too large");
@@ -173,11 +264,17 @@ int build_schedule(int kind, int d, int n, Schedule& s) {
   s.d = d;
   s.n = n;
   s.grouped_bw = false;
+  s.fused = false;
   bool ok = true;
   switch (kind) {
     case PMC_1F1B:
       s.grouped_bw = true;
+      s.fused = true;
       one_f_one_b_block(d, s.block);
+      break;
+    case PMC_1F1BV:
+      s.fused = true;
+      if (int rc = one_f_one_b_v_block(d, s.block)) return rc;
       break;
     case PMC_VMIN:  // Table 1 (1,1); Appendix F: F->B turn is 3 when d is a multiple of 3
       ok = vshape_block(d, 1, 1, 1, d % 3 == 0 ? 3 : 1, 1, s.block);
@@ -203,6 +300,7 @@ int build_vshape(int d, int n, int delta0, int delta1, int turn_f, int turn_fb, 
   s.d = d;
   s.n = n;
   s.grouped_bw = false;
+  s.fused = false;
   if (!vshape_block(d, delta0, delta1, turn_f, turn_fb, turn_b, s.block))
     return fail(PMC_ERR_ILLEGAL_BLOCK, "V-shape block (%d,%d | %d,%d,%d) collides for d=%d", delta0, delta1,
                 turn_f, turn_fb, turn_b, d);
@@ -247,7 +345,7 @@ void account(const Schedule& s, int64_t unit_bytes, int64_t stats_bytes, pmc_dev
 // Every device starts each pass of its order as soon as the device is free and the passes it
 // depends on have ended.  F needs F of the previous model chunk, B needs B of the next one (the
 // last chunk's B needs its own F), W needs its own B.  In 1F1B the backward of a stage is one
-// pass, so the stage before it waits for the end of that whole pass.
+// pass, so the stage before it waits for the end of that whole pass; likewise in 1F1B-V, chunk by chunk.
 int makespan(const Schedule& s, double tf, double tb, double tw, double* out) {
   const int d = s.d, n = s.n, last = 2 * d - 1;
   const double dur[3] = {tf, tb, tw};
@@ -266,7 +364,7 @@ int makespan(const Schedule& s, double tf, double tb, double tw, double* out) {
           if (p.model_chunk > 0) dep_op = PMC_F, dep_mc = p.model_chunk - 1;
         } else if (p.op == PMC_B) {
           if (p.model_chunk == last) dep_op = PMC_F, dep_mc = last;
-          else if (s.grouped_bw && p.chunk == 1) dep_op = PMC_W, dep_mc = p.model_chunk + 1;
+          else if (s.fused && (!s.grouped_bw || p.chunk == 1)) dep_op = PMC_W, dep_mc = p.model_chunk + 1;
           else dep_op = PMC_B, dep_mc = p.model_chunk + 1;
         } else {
           dep_op = PMC_B, dep_mc = p.model_chunk;
@@ -294,7 +392,7 @@ namespace {
 // Integer-cell view of a schedule at unit pass times, used by the reordering heuristics.
 struct Grid {
   int d, n, last;
-  bool fused;
+  bool fused, grouped;
   std::vector<int32_t> end;  // [3][2d][n]: end cell of (op, model chunk, microbatch), -1 = not placed
   size_t idx(int op, int mc, int mb) const { return ((size_t)op * 2 * d + mc) * n + mb; }
   // the one pass p waits for, or op = -1
@@ -305,7 +403,7 @@ struct Grid {
       if (p.model_chunk > 0) op = PMC_F, mc = p.model_chunk - 1;
     } else if (p.op == PMC_B) {
       if (p.model_chunk == last) op = PMC_F, mc = last;
-      else if (fused && p.chunk == 1) op = PMC_W, mc = p.model_chunk + 1;
+      else if (fused && (!grouped || p.chunk == 1)) op = PMC_W, mc = p.model_chunk + 1;
       else op = PMC_B, mc = p.model_chunk + 1;
     } else {
       op = PMC_B, mc = p.model_chunk;
@@ -368,14 +466,14 @@ void sort_by_cell(std::vector<pmc_pass>& v) {
 // leave the peak unchanged).  Cool-down: the W passes after a device's last F are taken out, the
 // rest is squeezed, and the vacant cells after the last F are filled left to right with the first
 // removed W whose B has ended; the remainder goes to the end.  The result's `time` fields are the
-// cells of the final squeezed grid.  A fused-backward (1F1B) schedule is only squeezed.
+// cells of the final squeezed grid.  A fused-backward (1F1B, 1F1B-V) schedule is only squeezed.
 int reorder(const Schedule& in, Schedule& out) {
   out = in;
   const int d = in.d, n = in.n;
-  Grid g{d, n, 2 * d - 1, in.grouped_bw, std::vector<int32_t>((size_t)3 * 2 * d * n, -1)};
+  Grid g{d, n, 2 * d - 1, in.fused, in.grouped_bw, std::vector<int32_t>((size_t)3 * 2 * d * n, -1)};
   auto& orders = out.per_device;
   if (!squeeze_unit(g, orders)) return fail(PMC_ERR_ILLEGAL_BLOCK, "orders contradict the dependencies");
-  if (!in.grouped_bw) {
+  if (!in.fused) {
     std::vector<int64_t> base_peak(d);
     std::vector<int32_t> first_b(d, 0);
     int32_t horizon = 0;
@@ -495,6 +593,7 @@ int search(int d, int n, int64_t limit_units, double tf, double tb, double tw, i
                   cand.d = d;
                   cand.n = n;
                   cand.grouped_bw = false;
+                  cand.fused = false;
                   if (int rc = finish(cand)) return rc;
                   const Schedule* timed = &cand;
                   if (do_reorder) {

@@ -217,7 +217,7 @@ def _replay(cfg, tag, kind, d, n, chunk_params, xs, dys, reorder=False, sched=No
 
 def test_replay_config1_all_schedules():
     """2 simulated devices x 4 microbatches, 4 one-layer fp32 chunks (hidden 256, seq 128), replayed
-    as 1F1B, V-Half, V-Min and V-ZB: outputs and accumulated gradients against the oracle's whole
+    as 1F1B, V-Half, V-Min, V-ZB and 1F1B-V: outputs and accumulated gradients against the oracle's whole
     model, peaks against the oracle's accounting, gradients bit-identical across schedules."""
     cfg, d, n = synth.CONFIGS["C1"], 2, 4
     chunk_params = [synth.chunk_params(cfg, "C1", c) for c in range(2 * d)]
@@ -227,7 +227,7 @@ def test_replay_config1_all_schedules():
     m = OL.chunk_activation_bytes(cfg.layers, cfg.hidden, cfg.heads, cfg.seq, 4, cfg.microbatch, cfg.ffn)
     st = OL.chunk_stats_bytes(cfg.layers, cfg.heads, cfg.seq, cfg.microbatch)
     first = None
-    for kind in ("1f1b", "vhalf", "vmin", "vzb"):
+    for kind in ("1f1b", "vhalf", "vmin", "vzb", "1f1bv"):
         print("replay", kind, flush=True)
         ys, dxs, grads, report, peaks = _replay(cfg, "C1", kind, d, n, chunk_params, xs, dys)
         for j in range(n):
@@ -258,7 +258,7 @@ def test_replay_bf16_d4_reduced_width():
     dys = [synth.upstream_grad(cfg, "C5r", j) for j in range(n)]
     ys_ref, dxs_ref, grads_ref = _oracle_model(cfg, chunk_params, xs, dys)
     first = None
-    for kind in ("1f1b", "vzb", "vhalf", "vmin"):
+    for kind in ("1f1b", "vzb", "vhalf", "vmin", "1f1bv"):
         print("replay", kind, flush=True)
         ys, dxs, grads, report, peaks = _replay(cfg, "C5r", kind, d, n, chunk_params, xs, dys)
         for j in range(n):
@@ -356,7 +356,8 @@ def _gpu_chunks(ctx, cfg, count, seed):
 @pytest.mark.timeout(900)
 def test_replay_config5_full_size():
     """The full schedule replay at its stated size: 4 simulated devices, 8 two-layer chunks (hidden 4096,
-    32 heads, FFN 16384, 2048 tokens, bf16), 16 microbatches, as 1F1B, V-ZB, V-Half and V-Min.
+    32 heads, FFN 16384, 2048 tokens, bf16), 16 microbatches, as 1F1B, V-ZB, V-Half and V-Min (and as
+    1F1B-V, the fused-backward V-shape block of Appendix H).
     The fp64 oracle of a whole iteration would take hours, so the chain is:
       (i)   a naive run on the GPU (F through all chunks, B back, W at once, microbatch after
             microbatch) in which ONE chunk's pass for microbatch 0 is compared with the oracle in
@@ -369,7 +370,7 @@ def test_replay_config5_full_size():
     cfg, d, n = synth.CONFIGS["C5"], 4, 16
     pcfg = R.cfg_from_synth(cfg)
     probe = 3                                            # the chunk checked against the oracle
-    scheds = {k: P.pmc_schedule_build(k, d, n) for k in ("1f1b", "vzb", "vhalf", "vmin")}
+    scheds = {k: P.pmc_schedule_build(k, d, n) for k in ("1f1b", "vzb", "vhalf", "vmin", "1f1bv")}
     ws = max(P.pmc_replay_workspace_bytes(s, pcfg) for s in scheds.values())
     ctx = R.Context(pcfg, slabs=2 * d * d, workspace_bytes=ws)
     chunks, gen = _gpu_chunks(ctx, cfg, 2 * d, seed=5)
@@ -436,4 +437,5 @@ def test_replay_config5_full_size():
         P.pmc_schedule_destroy(s)
     assert worst["1f1b"] == worst["vzb"] == 8 * m
     assert worst["vhalf"] * 4 == worst["1f1b"] * 3 and worst["vmin"] * 2 == worst["1f1b"]
+    assert worst["1f1bv"] == -(-(4 * d + 2) // 3) * m                     # ceil((4d + 2) / 3) units: 6 of 8 at d = 4
     ctx.close()

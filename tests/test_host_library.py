@@ -22,7 +22,7 @@ def test_header_symbols_are_exported_and_bound():
     assert declared == set(P.EXPORTS), declared ^ set(P.EXPORTS)
 
 
-@pytest.mark.parametrize("kind", S.KINDS)
+@pytest.mark.parametrize("kind", S.KINDS + S.MORE_KINDS)
 @pytest.mark.parametrize("d,n", [(1, 3), (2, 4), (3, 7), (4, 16), (6, 13), (8, 32), (9, 20)])
 def test_orders_match_oracle(kind, d, n):
     s = P.pmc_schedule_build(kind, d, n)
@@ -42,8 +42,9 @@ def test_orders_match_oracle(kind, d, n):
         P.pmc_schedule_destroy(s)
 
 
-@pytest.mark.parametrize("kind", S.KINDS)
-@pytest.mark.parametrize("d,n", [(2, 4), (4, 16), (5, 11), (8, 24), (64, 256)])
+@pytest.mark.parametrize("kind,d,n", [(k, d, n) for k in S.KINDS + S.MORE_KINDS
+                                      for d, n in [(2, 4), (4, 16), (5, 11), (8, 24), (64, 256)]
+                                      if not (k == "1f1bv" and d == 64)] + [("1f1bv", 16, 64)])
 def test_accounting_matches_oracle(kind, d, n):
     m, st = 537460736, 589824
     s = P.pmc_schedule_build(kind, d, n)
@@ -57,7 +58,7 @@ def test_accounting_matches_oracle(kind, d, n):
         P.pmc_schedule_destroy(s)
 
 
-@pytest.mark.parametrize("kind", S.KINDS)
+@pytest.mark.parametrize("kind", S.KINDS + S.MORE_KINDS)
 @pytest.mark.parametrize("times", [(1.0, 1.0, 1.0), (1.0, 1.1, 0.7), (2.0, 1.0, 0.5)])
 def test_makespan_matches_oracle(kind, times):
     for d, n in ((2, 4), (4, 16), (8, 24)):
@@ -125,7 +126,7 @@ def test_bad_cfg_is_rejected():
     assert P.pmc_activation_bytes(P.make_cfg(2, 12296, 53, 8192, 2048)) == 0  # beyond the row kernels' width
 
 
-@pytest.mark.parametrize("kind", S.KINDS)
+@pytest.mark.parametrize("kind", S.KINDS + S.MORE_KINDS)
 @pytest.mark.parametrize("d,n", [(1, 3), (2, 5), (3, 7), (4, 16), (6, 24), (8, 20), (9, 12)])
 def test_reorder_matches_oracle(kind, d, n):
     """Warm-up / cool-down reordering: the library's orders, cells, accounting and makespan against

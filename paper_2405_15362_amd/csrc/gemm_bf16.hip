@@ -801,7 +801,7 @@ int launch_dma(hipStream_t st, GemmParams p) {
 int pick_tile(int M, int N, bool wide_ok) {
   if (const int f = tuning(kTuneGemmTile); f >= 0) return (f == 4 && !wide_ok) ? 0 : f;
   const int bm[5] = {256, 256, 128, 64, 256}, bn[5] = {256, 128, 128, 128, 320};
-  const double rate[5] = {1.0, 0.95, 0.75, 0.6, 1.0};
+  const double rate[5] = {1.0, 0.95, 0.75, 0.6, 1.02};  // on a tie in rounds x area the 320-wide tile wins (fewer rounds)
   int best = 0;
   double best_t = 1e300;
   for (int c = 0; c < (wide_ok ? 5 : 4); ++c) {

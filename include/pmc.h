@@ -334,6 +334,19 @@ int pmc_layernorm_forward(pmc_ctx* ctx, int32_t dtype, int32_t rows, int32_t h, 
 int pmc_layernorm_backward(pmc_ctx* ctx, int32_t dtype, int32_t rows, int32_t h, const void* dy,
                            const void* x, const void* gain, const float* mean, const float* rstd,
                            const void* resid, void* dx, float* dgain, float* dbias);
+/* For callers that cannot allocate device memory or attach a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): pmc_layernorm_backward with its
+ * scratch (one row of 2h fp32 partial sums per workgroup, at most 512 workgroups) in a 32 MiB
+ * device array built into the library, PMC_LAYERNORM_STATIC_SCRATCH_BYTES; each GPU the library
+ * runs on holds its own copy until the process ends.  Same arguments, same kernels, same results
+ * bit for bit; needs no workspace and calls no allocating routine.  Returns PMC_ERR_NOMEM, and
+ * launches nothing, when min(rows, 512) * 2h * 4 bytes exceed the array (h > 8192 with 512 or
+ * more rows).  All calls on one GPU share the array, so two calls that overlap in time on one GPU
+ * (different streams or host threads) race; calls on one stream are ordered and safe. */
+#define PMC_LAYERNORM_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+int pmc_layernorm_backward_static(pmc_ctx* ctx, int32_t dtype, int32_t rows, int32_t h, const void* dy,
+                                  const void* x, const void* gain, const float* mean, const float* rstd,
+                                  const void* resid, void* dx, float* dgain, float* dbias);
 /* Fused attention on packed qkv [batch*seq, 3h]: o [batch*seq, h], lse fp32 [batch, heads, seq].
  * In bf16 with a head size that is a multiple of 8 (the matrix-core kernels) one sequence's rows, seq * 3h * 2
  * bytes, must stay below 2 GB; larger shapes return PMC_ERR_INVALID (also from pmc_chunk_create). */

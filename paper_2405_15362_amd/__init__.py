@@ -105,6 +105,7 @@ _SIGS = {
     "pmc_gemm_grouped_wgrad": (C.c_int, [_vp, _i32, _i32, _i32, _i32, C.POINTER(_vp), _i32, C.POINTER(_vp), _i32, _vp, _i32]),
     "pmc_layernorm_forward": (C.c_int, [_vp, _i32, _i32, _i32, _vp, _vp, _vp, C.c_float, _vp, _vp, _vp, _vp]),
     "pmc_layernorm_backward": (C.c_int, [_vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "pmc_layernorm_backward_static": (C.c_int, [_vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "pmc_attention_forward": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp]),
     "pmc_attention_backward": (C.c_int, [_vp, _i32, _i32, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp]),
     "pmc_column_sum": (C.c_int, [_vp, _i32, _i32, _i32, _vp, _i32, _vp]),
@@ -412,6 +413,13 @@ def pmc_layernorm_backward(ctx, dy, x, gain, mean, rstd, resid, dx, dgain, dbias
     rows, h = x.shape
     _check(lib.pmc_layernorm_backward(ctx, _dt(x), rows, h, _ptr(dy), _ptr(x), _ptr(gain), _ptr(mean), _ptr(rstd),
                                       _ptr(resid), _ptr(dx), _ptr(dgain), _ptr(dbias)))
+
+
+def pmc_layernorm_backward_static(ctx, dy, x, gain, mean, rstd, resid, dx, dgain, dbias) -> None:
+    """pmc_layernorm_backward with the library's built-in scratch array (no workspace needed)."""
+    rows, h = x.shape
+    _check(lib.pmc_layernorm_backward_static(ctx, _dt(x), rows, h, _ptr(dy), _ptr(x), _ptr(gain), _ptr(mean), _ptr(rstd),
+                                             _ptr(resid), _ptr(dx), _ptr(dgain), _ptr(dbias)))
 
 
 def pmc_attention_forward(ctx, qkv, o, lse, batch, seq, heads, head_dim, causal=True) -> None:

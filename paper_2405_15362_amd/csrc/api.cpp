@@ -818,6 +818,13 @@ int pmc_layernorm_backward(pmc_ctx* ctx, int32_t dtype, int32_t rows, int32_t h,
   return k::layernorm_backward(ctx->stream, dtype, rows, h, dy, x, gain, mean, rstd, resid, dx, dgain, dbias, (float*)ctx->ws);
 }
 
+int pmc_layernorm_backward_static(pmc_ctx* ctx, int32_t dtype, int32_t rows, int32_t h, const void* dy, const void* x,
+                                  const void* gain, const float* mean, const float* rstd, const void* resid, void* dx,
+                                  float* dgain, float* dbias) {
+  if (!ctx) return fail(PMC_ERR_INVALID, "ctx is NULL");
+  return k::layernorm_backward_static(ctx->stream, dtype, rows, h, dy, x, gain, mean, rstd, resid, dx, dgain, dbias);
+}
+
 int pmc_attention_forward(pmc_ctx* ctx, int32_t dtype, int32_t batch, int32_t seq, int32_t heads, int32_t head_dim,
                           int32_t causal, const void* qkv, void* o, float* lse) {
   if (!ctx) return fail(PMC_ERR_INVALID, "ctx is NULL");

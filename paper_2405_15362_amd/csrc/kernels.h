@@ -79,6 +79,14 @@ int layernorm_backward(hipStream_t stream, int dtype, int rows, int h, const voi
                        const void* gain, const float* mean, const float* rstd, const void* resid, void* dx,
                        float* dgain, float* dbias, float* partial, LnPartialJobs* defer = nullptr);
 int layernorm_backward_reduce(hipStream_t stream, int h, const LnPartialJobs& jobs);
+// As layernorm_backward with the partial sums in a device array built into the library (no workspace,
+// no allocation); PMC_ERR_NOMEM when layernorm_backward_scratch_floats(rows, h) floats do not fit in
+// layernorm_backward_static_scratch_bytes().
+size_t layernorm_backward_static_scratch_bytes();
+int layernorm_backward_static(hipStream_t stream, int dtype, int rows, int h, const void* dy, const void* x,
+                              const void* gain, const float* mean, const float* rstd, const void* resid, void* dx,
+                              float* dgain, float* dbias);
+
 int attention_forward(hipStream_t stream, int dtype, int batch, int seq, int heads, int head_dim, int causal,
                       const void* qkv, void* o, float* lse);
 // scratch: dq staging [batch*seq, heads*head_dim] in the storage type, then delta fp32 [batch, heads, seq].

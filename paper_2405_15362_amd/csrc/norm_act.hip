@@ -3,12 +3,21 @@
 // Forward: one 64-lane wave owns a row and the row reductions are wave shuffles.  Backward: one to
 // eight waves share a row.  Reductions across rows go through fixed-order partial sums, so results
 // do not depend on scheduling.
+#include <mutex>
+
 #include "dev_common.h"
 #include "kernels.h"
 
 namespace pmc {
 namespace k {
 namespace {
+
+// Scratch of layernorm_backward_static: the partial sums of the gain/bias gradients, in a device
+// array that exists from the moment the code object is loaded (one copy per GPU, held until the
+// process ends), so that callers who cannot allocate device memory need no workspace.  In host code
+// the name `scratch` is only a handle for hipGetSymbolAddress; kernels get the address it returns.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 constexpr int kWaves = 4;
 constexpr int kBwdWaves = 8;  // LayerNorm backward: waves (= rows in flight) per workgroup
@@ -418,6 +427,40 @@ int layernorm_backward(hipStream_t st, int dtype, int rows, int h, const void* d
   if (dtype == PMC_F32) return ln_bwd_t<float>(st, rows, h, dy, x, gain, mean, rstd, resid, dx, dgain, dbias, partial, defer);
   if (dtype == PMC_BF16) return ln_bwd_t<bf16_t>(st, rows, h, dy, x, gain, mean, rstd, resid, dx, dgain, dbias, partial, defer);
   return fail(PMC_ERR_INVALID, "layernorm_backward: bad dtype %d", dtype);
+}
+
+size_t layernorm_backward_static_scratch_bytes() { return kStaticScratchBytes; }
+
+int layernorm_backward_static(hipStream_t st, int dtype, int rows, int h, const void* dy, const void* x, const void* gain,
+                              const float* mean, const float* rstd, const void* resid, void* dx, float* dgain,
+                              float* dbias) {
+  if (rows <= 0 || h <= 0) return fail(PMC_ERR_INVALID, "layernorm_backward_static: rows=%d h=%d", rows, h);
+  const size_t need = layernorm_backward_scratch_floats(rows, h) * sizeof(float);
+  if (need > kStaticScratchBytes)
+    return fail(PMC_ERR_NOMEM, "layernorm_backward_static: rows=%d x h=%d needs %zu bytes of scratch, the built-in array holds %zu",
+                rows, h, need, kStaticScratchBytes);
+  // The array has its own address on every GPU: looked up once per device, with that device current.
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static float* base[kMaxDevices] = {};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+    return fail(PMC_ERR_HIP, "layernorm_backward_static: cannot tell the current device");
+  float* ptr = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(mu);
+    if (!base[dev]) {
+      void* p = nullptr;
+      const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !p)
+        return fail(PMC_ERR_HIP, "layernorm_backward_static: hipGetSymbolAddress failed: %s", hipGetErrorString(e));
+      base[dev] = static_cast<float*>(p);
+    }
+    ptr = base[dev];
+  }
+  // every workgroup overwrites its whole row of partials before the reduction reads it: nothing
+  // of the previous call's contents is read, nothing has to be cleared
+  return layernorm_backward(st, dtype, rows, h, dy, x, gain, mean, rstd, resid, dx, dgain, dbias, ptr, nullptr);
 }
 
 int column_sums(hipStream_t st, int dtype, int rows, ColumnSumJobs jobs) {

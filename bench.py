@@ -216,6 +216,13 @@ def main() -> int:
     ap.add_argument("--no-replay", action="store_true", help="skip the d=4, n=16 schedule replay at the C5 shape")
     ap.add_argument("--profile", action="store_true",
                     help="for profiler runs: the headline workload only (no other workloads, replay, queued W or cpu baseline)")
+    ap.add_argument("--w-streams", type=int, default=0, choices=(0, 1, 2),
+                    help="streams of the W pass (library switch w_streams): 1 keeps every kernel on one stream, which is "
+                         "how the traced steps behind `roofline` run; a kernel trace of such a run shows un-overlapped "
+                         "kernel durations.  0: the library's default (2)")
+    ap.add_argument("--microbatch-study", action="store_true",
+                    help="instead of the benchmark line: the single-pass table over microbatch sizes (Appendix D.2) and "
+                         "V-Half at twice the microbatch size against 1F1B (Section 4.3), as one JSON object")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="before the timed region, copy a cold device buffer of this many MiB three times "
                          "(a plain copy kernel of known size that scales the profiler's HBM byte counters)")
@@ -244,6 +251,12 @@ def main() -> int:
             cfg = dataclasses.replace(cfg, microbatch=args.microbatch)
             name = f"{tag}x{args.microbatch}"
         return name, cfg
+
+    if args.w_streams:
+        P.pmc_tuning_set("w_streams", args.w_streams)
+    if args.microbatch_study:
+        print(json.dumps(microbatch_study(P, R, synth, torch, np, args.steps, args.warmup)))
+        return 0
 
     if args.copy_calibration > 0:
         src = torch.ones(args.copy_calibration << 20, dtype=torch.uint8, device="cuda")
@@ -368,17 +381,16 @@ def cpu_baseline(cfg, name, params, x_h, dy_h):
             "seconds_per_step_extrapolated": round(sec / reps * cfg.layers, 2)}
 
 
-def replay_c5(P, R, synth, torch):
-    """Full schedule replay at the large configuration: 4 simulated devices, 8 two-layer chunks
-    (hidden 4096, seq 2048, bf16), 16 microbatches; random-initialised weights made on the GPU."""
-    cfg = synth.CONFIGS["C5"]
+def replay_run(P, R, synth, torch, cfg, d, n, kinds, seed=5):
+    """Replays the schedules `kinds` for d simulated devices and n microbatches with 2d chunks of shape
+    cfg (random-initialised weights made on the GPU): per kind the wall time of one iteration on one
+    stream, summed F/B/W pass times, measured peaks, and the finish time the schedule would have on d
+    devices with the measured mean pass times (squeezed, then reordered: Appendix C)."""
     pcfg = R.cfg_from_synth(cfg)
-    d, n = 4, 16
-    res = {"config": "C5: 4 simulated devices x 2 chunks (8 two-layer chunks, hidden 4096, 32 heads, FFN 16384, seq 2048, "
-                     "bf16), 16 microbatches, 384 chunk passes per iteration on one stream"}
-    gen = torch.Generator(device="cuda").manual_seed(5)
+    res = {}
+    gen = torch.Generator(device="cuda").manual_seed(seed)
     shapes = synth.param_shapes(cfg)
-    scheds = {k: P.pmc_schedule_build(k, d, n) for k in ("1f1b", "vzb", "vhalf", "vmin", "1f1bv")}
+    scheds = {k: P.pmc_schedule_build(k, d, n) for k in kinds}
     ws = max(P.pmc_replay_workspace_bytes(s, pcfg) for s in scheds.values())
     ctx = R.Context(pcfg, slabs=2 * d * d, workspace_bytes=ws)
     chunks = []
@@ -402,20 +414,70 @@ def replay_c5(P, R, synth, torch):
         chunks.append(ch)
     xs = [torch.randn(cfg.tokens, cfg.hidden, device="cuda", generator=gen).to(torch.bfloat16) for _ in range(n)]
     dys = [torch.randn(cfg.tokens, cfg.hidden, device="cuda", generator=gen).to(torch.bfloat16) for _ in range(n)]
-    fl = flops_per_layer(cfg.hidden, cfg.ffn, cfg.seq)
+    fl = flops_per_layer(cfg.hidden, cfg.ffn, cfg.seq, cfg.microbatch)
     iter_flop = 2 * d * n * cfg.layers * (fl["F"] + fl["B"] + fl["W"])
     for kind, s in scheds.items():
         P.schedule_replay(ctx.ctx, s, [c.handle for c in chunks], xs, dys)          # warm-up iteration
         rep, peaks = P.schedule_replay(ctx.ctx, s, [c.handle for c in chunks], xs, dys, flags=P.REPLAY_TIME_PASSES)
+        t_f, t_b, t_w = (rep[k] / (2 * d * n) for k in ("ms_f", "ms_b", "ms_w"))     # mean time of one chunk pass
+        reo = P.pmc_schedule_reorder(s)
+        span = P.pmc_schedule_makespan(reo, t_f, t_b, t_w)
+        P.pmc_schedule_destroy(reo)
         res[kind] = {"ms_per_iteration": round(rep["ms_total"], 2), "ms_f": round(rep["ms_f"], 2),
                      "ms_b": round(rep["ms_b"], 2), "ms_w": round(rep["ms_w"], 2),
                      "tflops": round(iter_flop / (rep["ms_total"] * 1e-3) / 1e12, 1),
-                     "peak_units": [p[0] for p in peaks], "peak_bytes": [p[1] for p in peaks]}
+                     "peak_units": [p[0] for p in peaks], "peak_bytes": [p[1] for p in peaks],
+                     "simulated_ms_on_d_devices": round(span, 3),
+                     "simulated_bubble_rate": round(1.0 - 2 * n * (t_f + t_b + t_w) / span, 4)}
         P.pmc_schedule_destroy(s)
+    ctx.close()
+    del ctx, chunks
+    torch.cuda.empty_cache()
+    return res
+
+
+def replay_c5(P, R, synth, torch):
+    """Full schedule replay at the large configuration: 4 simulated devices, 8 two-layer chunks
+    (hidden 4096, seq 2048, bf16), 16 microbatches."""
+    res = {"config": "C5: 4 simulated devices x 2 chunks (8 two-layer chunks, hidden 4096, 32 heads, FFN 16384, seq 2048, "
+                     "bf16), 16 microbatches, 384 chunk passes per iteration on one stream"}
+    res.update(replay_run(P, R, synth, torch, synth.CONFIGS["C5"], 4, 16, ("1f1b", "vzb", "vhalf", "vmin", "1f1bv")))
     for kind in ("vzb", "vhalf", "vmin", "1f1bv"):
         res[kind]["max_peak_bytes_vs_1f1b"] = round(max(res[kind]["peak_bytes"]) / max(res["1f1b"]["peak_bytes"]), 4)
-    ctx.close()
     return res
+
+
+def microbatch_study(P, R, synth, torch, np, steps, warmup):
+    """Appendix D.2's single-pass table on this chip (F / B / W of one chunk at growing microbatch
+    size), and Section 4.3's comparison measured: V-Half at twice the microbatch size against 1F1B,
+    same number of sequences per iteration, d = 4 simulated devices with chunks of the C2 and C3
+    shapes (peak bytes from the pool, throughput from the schedules' finish times with the measured
+    pass times)."""
+    out = {"single_pass": {}, "vhalf_at_2x_microbatch_vs_1f1b": {}}
+    for tag, sizes in (("C2", (1, 2, 4, 8)), ("C3", (1, 2, 4)), ("C4", (1, 2))):
+        for b in sizes:
+            cfg = dataclasses.replace(synth.CONFIGS[tag], microbatch=b)
+            res, _ = run_workload(P, R, synth, torch, np, f"{tag}x{b}", cfg, steps, warmup, 0)
+            out["single_pass"][f"{tag} b={b}"] = {"step_tflops": res["value"], "ms_per_step": res["ms_per_step"],
+                                                  **{k: res["passes"][k]["tflops"] for k in "FBW"},
+                                                  "gemm_frac_of_bf16_peak": res["roofline"]["frac"]}
+    d, seqs = 4, 16
+    for tag in ("C2", "C3"):
+        base = dataclasses.replace(synth.CONFIGS[tag], layers=2)
+        one = replay_run(P, R, synth, torch, base, d, seqs, ("1f1b", "vhalf"))
+        two = replay_run(P, R, synth, torch, dataclasses.replace(base, microbatch=2), d, seqs // 2, ("vhalf",))
+        row = {}
+        for label, r in (("1f1b b=1", one["1f1b"]), ("vhalf b=1", one["vhalf"]), ("vhalf b=2", two["vhalf"])):
+            row[label] = {"max_peak_bytes": max(r["peak_bytes"]), "ms_one_stream": r["ms_per_iteration"],
+                          "simulated_ms_on_d_devices": r["simulated_ms_on_d_devices"],
+                          "simulated_bubble_rate": r["simulated_bubble_rate"],
+                          "sequences_per_s_simulated": round(seqs / (r["simulated_ms_on_d_devices"] * 1e-3), 1)}
+        ref = row["1f1b b=1"]
+        for label in ("vhalf b=1", "vhalf b=2"):
+            row[label]["peak_bytes_vs_1f1b"] = round(row[label]["max_peak_bytes"] / ref["max_peak_bytes"], 4)
+            row[label]["throughput_vs_1f1b"] = round(row[label]["sequences_per_s_simulated"] / ref["sequences_per_s_simulated"], 4)
+        out["vhalf_at_2x_microbatch_vs_1f1b"][f"{tag} shape, 2-layer chunks, d={d}, {seqs} sequences"] = row
+    return out
 
 
 if __name__ == "__main__":

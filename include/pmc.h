@@ -106,11 +106,10 @@ const char* pmc_last_error(void);
 
 /* Tuning switches, process-wide (tests, kernel tuning): value -1 = the library decides.
  *   "gemm_tile" 0..4 (256x256, 256x128, 128x128, 64x128, 256x320)   "gemm_group" 1..64 (tile walk)
- *   "gemm_wgrad" 0|1 (persistent W kernel)   "gemm_persistent" 0|1 (persistent F/B kernel)
- *   "attn_shape" 0..2 (launch family)   "attn_variant" 0..3   "w_streams" 1|2
- * The environment variables PMC_GEMM_TILE, PMC_GEMM_GROUP, PMC_GEMM_WGRAD, PMC_GEMM_PERSISTENT,
- * PMC_ATTN_SHAPE, PMC_ATTN_VARIANT, PMC_W_STREAMS give the initial values; they are read once, at
- * the first use of any switch, never on a launch path.  PMC_ERR_INVALID for an unknown name or a
+ *   "gemm_wgrad" 0|1 (persistent W kernel)   "attn_shape" 0..2 (launch family)   "w_streams" 1|2
+ * The environment variables PMC_GEMM_TILE, PMC_GEMM_GROUP, PMC_GEMM_WGRAD, PMC_ATTN_SHAPE,
+ * PMC_W_STREAMS give the initial values; they are read once, at the first use of any switch, never
+ * on a launch path.  PMC_ERR_INVALID for an unknown name or a
  * value out of range. */
 int pmc_tuning_set(const char* name, int32_t value);
 int pmc_tuning_get(const char* name, int32_t* value);

@@ -31,6 +31,18 @@ Parity pins (tests/test_oracle_schedule.py): Section 3.2's exact peak formulas f
 devices, Table 1's bubble column, the bubble rate formula of Appendix D.3 for 1F1B, Appendix E.1's
 condition for V-Half to have no repeating bubble, and for the reordering: unchanged peaks, the
 least possible makespan for V-ZB.
+
+PARITY UNPINNED by the paper (it prints nothing these could be checked against; what pins them is
+this repository's own reading, stated in the tests):
+ * the per-device ORDER of V-ZB (its same-device offsets are not printed; its peak is pinned);
+ * reordered_passes: the paper prints no reordered order; two small grids worked by hand from
+   Appendix C's two steps pin this reading of them;
+ * adaptive_search: the winner's optimality is checked by a second brute force, but which of
+   several equally fast blocks wins (the first in loop order) is this repository's rule;
+ * the tensor-byte track of peak_bytes: pinned by hand to this repository's tensor table (the
+   paper pins units only);
+ * one_f_one_b_v_block (1F1B-V, Appendix H): the paper states the placement, the fused backward
+   and the 2/3 asymptote (all pinned) but no offsets: the order is this repository's earliest fit.
 """
 from __future__ import annotations
 

@@ -55,7 +55,6 @@ struct GemmParams {
   const bf16_t* Aseg[kMaxSegments];
   const bf16_t* Bseg[kMaxSegments];
   int nseg, seg_tiles;
-  int phase_by_xcd;  // persistent weight-gradient kernel: phase groups are whole XCDs (1) or alternate inside one (0)
 };
 
 constexpr int kEpiPartial = 100;  // fast path, split K: store the fp32 partial product of split blockIdx.y
@@ -640,9 +639,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_bf16_wgrad_persis
   extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
   const int ntiles = p.tiles_m * p.tiles_n, G = gridDim.x, b = blockIdx.x;
   const int nk = p.k_tiles_per_split;  // all of K
-  // which phase group: alternating inside an XCD (neighbours differ), or a whole XCD per group (the
-  // workgroups that share an L2 then walk their operand panels in step)
-  const int group = (p.phase_by_xcd ? (b & 7) : (b >> 3)) % GROUPS;
+  const int group = (b >> 3) % GROUPS;  // neighbours on one XCD fall into different groups
   const int head = (nk * group) / GROUPS;  // K tiles of the first tile left for the end
   bool first = true;
   int tm0 = 0, tn0 = 0;
@@ -866,7 +863,6 @@ int launch_wgrad_persistent(hipStream_t st, GemmParams p) {
   p.tiles_m = (p.M + 255) / 256;
   p.tiles_n = (p.N + 255) / 256;
   p.group_m = 8;
-  p.phase_by_xcd = tuning(kTuneWgradPhase) == 1;
   const int ntiles = p.tiles_m * p.tiles_n;
   int grid = ntiles < units ? ntiles : units;
   if (grid >= 8) grid &= ~7;  // whole rounds over the 8 XCDs keep a workgroup's tiles on one XCD
@@ -973,7 +969,6 @@ int gemm_bf16(hipStream_t st, const GemmArgs& a) {
   p.group_m = 8;
   p.k_tiles_per_split = 0;
   p.nseg = p.seg_tiles = 0;
-  p.phase_by_xcd = 0;
   for (int i = 0; i < kMaxSegments; ++i) p.Aseg[i] = p.Bseg[i] = nullptr;
   const bool a_kmaj = !a.trans_a, b_kmaj = a.trans_b;
   // Fast path: K in whole 64-wide tiles, operands inside the 2 GB window of a buffer descriptor.
@@ -1016,7 +1011,6 @@ int gemm_bf16_grouped_wgrad(hipStream_t st, const GroupedWgradArgs& a) {
   p.k_tiles_per_split = p.K / 64;
   p.nseg = a.count;
   p.seg_tiles = a.K / 64;
-  p.phase_by_xcd = 0;
   for (int i = 0; i < kMaxSegments; ++i) {
     const int j = i < a.count ? i : a.count - 1;
     if (!a.A[j] || !a.B[j] || !aligned(a.A[j], 16) || !aligned(a.B[j], 16))

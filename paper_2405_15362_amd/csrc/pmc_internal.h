@@ -15,8 +15,7 @@ namespace pmc {
 int fail(int code, const char* fmt, ...);
 
 // Tuning switches (tuning.cpp): -1 = the library decides.
-enum Tuning { kTuneGemmTile, kTuneGemmGroup, kTuneGemmWgrad, kTuneAttnShape, kTuneWStreams, kTuneGemmPersistent,
-              kTuneAttnVariant, kTuneWgradPhase, kTuneCount };
+enum Tuning { kTuneGemmTile, kTuneGemmGroup, kTuneGemmWgrad, kTuneAttnShape, kTuneWStreams, kTuneCount };
 int tuning(Tuning t);
 
 struct Schedule {

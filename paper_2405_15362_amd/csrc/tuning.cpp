@@ -21,8 +21,7 @@ struct Entry {
 constexpr Entry kEntries[kTuneCount] = {
     {"gemm_tile", "PMC_GEMM_TILE", 0, 4},      {"gemm_group", "PMC_GEMM_GROUP", 1, 64},
     {"gemm_wgrad", "PMC_GEMM_WGRAD", 0, 1},    {"attn_shape", "PMC_ATTN_SHAPE", 0, 2},
-    {"w_streams", "PMC_W_STREAMS", 1, 2},      {"gemm_persistent", "PMC_GEMM_PERSISTENT", 0, 1},
-    {"attn_variant", "PMC_ATTN_VARIANT", 0, 3},  {"wgrad_phase", "PMC_WGRAD_PHASE", 0, 1},
+    {"w_streams", "PMC_W_STREAMS", 1, 2},
 };
 std::atomic<int> g_value[kTuneCount];
 std::once_flag g_once;

@@ -113,7 +113,7 @@ def oracle_chunk(cfg, params, x, dy):
 class tuned:
     """Sets process-wide tuning switches of the library for a with-block (or until reset()) and hands
     the choice back to the library afterwards."""
-    NAMES = ("gemm_tile", "gemm_group", "gemm_wgrad", "gemm_persistent", "attn_shape", "attn_variant", "w_streams")
+    NAMES = ("gemm_tile", "gemm_group", "gemm_wgrad", "attn_shape", "w_streams")
 
     def __init__(self, **switches):
         self.switches = switches

@@ -465,15 +465,18 @@ def microbatch_study(P, R, synth, torch, np, steps, warmup):
     for tag in ("C2", "C3"):
         base = dataclasses.replace(synth.CONFIGS[tag], layers=2)
         one = replay_run(P, R, synth, torch, base, d, seqs, ("1f1b", "vhalf"))
-        two = replay_run(P, R, synth, torch, dataclasses.replace(base, microbatch=2), d, seqs // 2, ("vhalf",))
+        two = replay_run(P, R, synth, torch, dataclasses.replace(base, microbatch=2), d, seqs // 2, ("vhalf", "vmin"))
         row = {}
-        for label, r in (("1f1b b=1", one["1f1b"]), ("vhalf b=1", one["vhalf"]), ("vhalf b=2", two["vhalf"])):
+        # at d = 4 V-Half holds 6 units against 1F1B's 8, so at twice the microbatch size 1.5 x the bytes (equal
+        # only in the many-device limit); V-Min holds 4, so at twice the microbatch size exactly 1F1B's bytes
+        for label, r in (("1f1b b=1", one["1f1b"]), ("vhalf b=1", one["vhalf"]), ("vhalf b=2", two["vhalf"]),
+                         ("vmin b=2", two["vmin"])):
             row[label] = {"max_peak_bytes": max(r["peak_bytes"]), "ms_one_stream": r["ms_per_iteration"],
                           "simulated_ms_on_d_devices": r["simulated_ms_on_d_devices"],
                           "simulated_bubble_rate": r["simulated_bubble_rate"],
                           "sequences_per_s_simulated": round(seqs / (r["simulated_ms_on_d_devices"] * 1e-3), 1)}
         ref = row["1f1b b=1"]
-        for label in ("vhalf b=1", "vhalf b=2"):
+        for label in ("vhalf b=1", "vhalf b=2", "vmin b=2"):
             row[label]["peak_bytes_vs_1f1b"] = round(row[label]["max_peak_bytes"] / ref["max_peak_bytes"], 4)
             row[label]["throughput_vs_1f1b"] = round(row[label]["sequences_per_s_simulated"] / ref["sequences_per_s_simulated"], 4)
         out["vhalf_at_2x_microbatch_vs_1f1b"][f"{tag} shape, 2-layer chunks, d={d}, {seqs} sequences"] = row

@@ -220,3 +220,15 @@ def test_tuning_switches():
         assert P.pmc_tuning_get(name) == -1
     with pytest.raises(P.PmcError):
         P.pmc_tuning_set("no_such_switch", 1)
+
+
+def test_header_is_plain_c():
+    """The boundary is a C ABI: the header must compile as C99 on its own (no C++ or torch types)."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-fsyntax-only", "-x", "c",
+                        os.path.join(ROOT, "include", "pmc.h")], capture_output=True, text=True)
+    assert r.returncode == 0 and not r.stderr.strip(), r.stderr

@@ -233,6 +233,21 @@ def test_gemm_bf16_largest_workload_shapes(ctx):
         del a, b, c, c0, aux, extra, ref
 
 
+@pytest.mark.parametrize("ta,tb,epis", [(False, False, (P.EPI_NONE, P.EPI_BIAS, P.EPI_BIAS_RESID, P.EPI_BIAS_GELU, P.EPI_BIAS_GELU_GRAD)),
+                                        (False, True, (P.EPI_NONE, P.EPI_DGELU, P.EPI_MUL)),
+                                        (True, False, (P.EPI_NONE, P.EPI_ACCUM_F32))])
+def test_gemm_bf16_random_shapes(ctx, ta, tb, epis):
+    """Seeded random shapes in the library's own choice of kernel and tile: M and N any multiple of 8
+    up to a few tiles (ragged edges in both), K in whole 64-wide tiles (direct-to-LDS kernel, split K
+    where the library picks it) or any multiple of 8 (general kernel); the epilogue drawn from those
+    the layout is used with."""
+    rng = np.random.default_rng(20240515 + 2 * ta + tb)
+    for i in range(14):
+        M, N = (int(8 * rng.integers(1, 190)) for _ in range(2))
+        K = int(64 * rng.integers(1, 40)) if i % 3 else int(8 * rng.integers(1, 90))
+        _gemm_case(ctx, "bf16", ta, tb, M, N, K, epis[int(rng.integers(0, len(epis)))])
+
+
 def test_gemm_grouped_weight_gradient_rejects_bad_arguments(ctx):
     a = [torch.zeros(64, 128, device="cuda", dtype=torch.bfloat16)]
     b = [torch.zeros(64, 128, device="cuda", dtype=torch.bfloat16)]
@@ -340,6 +355,36 @@ def test_attention_forward_backward(ctx, dtype, dh, causal):
     P.pmc_attention_backward(ctx, inplace, o, lse, dev(d_o, dtype), inplace, batch, seq, heads, dh, causal)
     torch.cuda.synchronize()
     assert torch.equal(inplace, dq)
+
+
+def test_attention_random_shapes(ctx):
+    """Seeded random batch, sequence length, head count and head size (every multiple of 8 up to 128),
+    causal or not, in the library's own choice of launch shape: ragged last blocks, sequences shorter
+    than a block, padded head sizes."""
+    rng = np.random.default_rng(1536205)
+    for i in range(12):
+        batch, heads = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+        seq, dh, causal = int(rng.integers(1, 600)), int(8 * rng.integers(1, 17)), bool(rng.integers(0, 2))
+        h = heads * dh
+        key = ("attn-random", i)
+        print("attention random case", batch, seq, heads, dh, causal, flush=True)
+        qkv = mat(key + ("qkv",), (batch * seq, 3 * h), "bf16")
+        d_o = mat(key + ("do",), (batch * seq, h), "bf16")
+        q64 = qkv.astype(np.float64)
+        o_ref, probs, lse_ref = OL.attention(q64, heads, causal, batch)
+        dqkv_ref = OL.attention_input_grad(d_o.astype(np.float64), q64, probs, heads, batch)
+        qd = dev(qkv, "bf16")
+        o = dev(np.zeros((batch * seq, h)), "bf16")
+        lse = torch.zeros(batch * heads * seq, device="cuda")
+        P.pmc_attention_forward(ctx, qd, o, lse, batch, seq, heads, dh, causal)
+        dq = dev(np.zeros_like(qkv), "bf16")
+        P.pmc_attention_backward(ctx, qd, o, lse, dev(d_o, "bf16"), dq, batch, seq, heads, dh, causal)
+        torch.cuda.synchronize()
+        assert_close(host(o), o_ref, "bf16", f"random {i} o")
+        assert np.abs(host(lse) - lse_ref.reshape(-1)).max() <= 2e-2, i
+        scale = np.sqrt(np.mean(dqkv_ref ** 2))
+        for name, cols in (("dq", slice(0, h)), ("dk", slice(h, 2 * h)), ("dv", slice(2 * h, 3 * h))):
+            assert_close(host(dq)[:, cols], dqkv_ref[:, cols], "bf16", f"random {i} {name}", scale=scale)
 
 
 @pytest.mark.parametrize("family", [0, 1, 2])

@@ -106,7 +106,8 @@ const char* pmc_last_error(void);
 
 /* Tuning switches, process-wide (tests, kernel tuning): value -1 = the library decides.
  *   "gemm_tile" 0..4 (256x256, 256x128, 128x128, 64x128, 256x320)   "gemm_group" 1..64 (tile walk)
- *   "gemm_wgrad" 0|1 (persistent W kernel)   "attn_shape" 0..2 (launch family)   "w_streams" 1|2
+ *   "gemm_wgrad" 0..2 (W product: plain tiles, persistent 256x256 walk, two 256x128 workgroups per unit)
+ *   "attn_shape" 0..2 (launch family)   "w_streams" 1|2
  * The environment variables PMC_GEMM_TILE, PMC_GEMM_GROUP, PMC_GEMM_WGRAD, PMC_ATTN_SHAPE,
  * PMC_W_STREAMS give the initial values; they are read once, at the first use of any switch, never
  * on a launch path.  PMC_ERR_INVALID for an unknown name or a

@@ -436,10 +436,13 @@ __device__ __forceinline__ constexpr int kswz(int kr) {
   return ROWS % 128 == 0 ? ((kr & 3) << 2) : (((kr >> 1) & 1) << 2);
 }
 
-template <int ROWS, bool KMAJ, int NW>
+// BK: K rows of the tile; 64 everywhere except the [32 k][ROWS] tiles of the two-workgroup weight-gradient kernel
+// (the [rows][64] layout's swizzle is defined for 64 only).
+template <int ROWS, bool KMAJ, int NW, int BK = 64>
 struct DmaLoader {
-  static constexpr int NL = ROWS * 64 * 2 / 1024 / NW;  // 1 KB loads per wave per tile
-  static_assert(ROWS * 64 * 2 / 1024 % NW == 0, "tile must split evenly over the waves");
+  static constexpr int NL = ROWS * BK * 2 / 1024 / NW;  // 1 KB loads per wave per tile
+  static_assert(ROWS * BK * 2 / 1024 % NW == 0, "tile must split evenly over the waves");
+  static_assert(BK == 64 || (!KMAJ && BK == 32), "K depth of a tile");
   static_assert(KMAJ || ROWS % 128 == 0 || ROWS == 320, "the [64 k][rows] swizzle is defined for whole 128-row groups and for 320 rows");
   uint32_t voff[NL];  // byte offset of this lane's chunk at K offset 0
 
@@ -499,10 +502,11 @@ __device__ __forceinline__ bf16x8 read_frag_swz(const bf16_t* tile, int r0, int 
 // One output tile (tile_m, tile_n) over the K tiles kt0 .. kt0 + nk - 1: ring prologue, K loop,
 // staged epilogue.  All waves of the workgroup call it together; on return the LDS ring holds
 // epilogue slabs that other waves may still be reading (barrier before the ring is filled again).
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KMAJ, bool B_KMAJ, int NSTAGE, int EPI, bool SEG = false>
+// BK = 32 (both operands [k][rows] only): kt0 and nk count 32-wide K tiles, two 16-wide steps per tile.
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KMAJ, bool B_KMAJ, int NSTAGE, int EPI, bool SEG = false, int BK = 64>
 __device__ __forceinline__ void dma_tile(const GemmParams& p, bf16_t* smem, int tile_m, int tile_n, int kt0, int nk) {
 #if defined(__HIP_DEVICE_COMPILE__)
-  constexpr int BK = 64, NW = WAVES_M * WAVES_N, WM = BM / WAVES_M, WN = BN / WAVES_N, TM = WM / 32, TN = WN / 32;
+  constexpr int NW = WAVES_M * WAVES_N, WM = BM / WAVES_M, WN = BN / WAVES_N, TM = WM / 32, TN = WN / 32;
   constexpr int TA = BM * BK, TB = BN * BK, STAGE = TA + TB;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
@@ -514,8 +518,8 @@ __device__ __forceinline__ void dma_tile(const GemmParams& p, bf16_t* smem, int 
     return r;
   };
   i32x4 ra = make_rsrc(p.A), rb = make_rsrc(p.B);
-  DmaLoader<BM, A_KMAJ, NW> la;
-  DmaLoader<BN, B_KMAJ, NW> lb;
+  DmaLoader<BM, A_KMAJ, NW, BK> la;
+  DmaLoader<BN, B_KMAJ, NW, BK> lb;
   la.init(p.lda, m0, p.M, wave, lane);
   lb.init(p.ldb, n0, p.N, wave, lane);
   const uint32_t stepa = A_KMAJ ? BK * 2 : (uint32_t)BK * p.lda * 2;
@@ -549,7 +553,7 @@ __device__ __forceinline__ void dma_tile(const GemmParams& p, bf16_t* smem, int 
   };
   // Ring of NSTAGE stages.  Tiles past the end are clamped (fetched again, never used) so that the
   // number of loads in flight is the same at every wait.
-  constexpr int LPT = DmaLoader<BM, A_KMAJ, NW>::NL + DmaLoader<BN, B_KMAJ, NW>::NL;  // loads per tile per wave
+  constexpr int LPT = DmaLoader<BM, A_KMAJ, NW, BK>::NL + DmaLoader<BN, B_KMAJ, NW, BK>::NL;  // loads per tile per wave
   constexpr int INFL = (NSTAGE - 2) * LPT;  // loads that may stay in flight at a wait
   static_assert(INFL < 64, "vmcnt is a 6-bit field");
   constexpr int WAIT_TILE = (INFL & 15) | ((INFL >> 4) << 14) | (7 << 4) | (15 << 8);  // s_waitcnt vmcnt(INFL)
@@ -558,9 +562,10 @@ __device__ __forceinline__ void dma_tile(const GemmParams& p, bf16_t* smem, int 
   // is tile `local` of piece `seg`; the two are stepped along with the requests (which come in
   // ascending t), so no division sits in the loop.
   int seg = 0, local = 0;
+  const int seg_tiles = SEG ? p.seg_tiles * (64 / BK) : 0;  // K tiles of this depth per piece
   if (SEG) {
-    seg = kt0 / p.seg_tiles;
-    local = kt0 - seg * p.seg_tiles;
+    seg = kt0 / seg_tiles;
+    local = kt0 - seg * seg_tiles;
     ra = make_rsrc(p.Aseg[seg]);
     rb = make_rsrc(p.Bseg[seg]);
   }
@@ -569,7 +574,7 @@ __device__ __forceinline__ void dma_tile(const GemmParams& p, bf16_t* smem, int 
     la.issue(ra, smem + stage * STAGE, kt * stepa, wave);
     lb.issue(rb, smem + stage * STAGE + TA, kt * stepb, wave);
     if (SEG && t + 1 < nk) {  // past the end the last tile is requested again
-      if (++local == p.seg_tiles) {
+      if (++local == seg_tiles) {
         local = 0;
         ++seg;
         ra = make_rsrc(p.Aseg[seg]);
@@ -593,8 +598,10 @@ __device__ __forceinline__ void dma_tile(const GemmParams& p, bf16_t* smem, int 
     const int fill = cur == 0 ? NSTAGE - 1 : cur - 1;  // all its readers passed the last barrier
     request(kt + NSTAGE - 1, fill);
     step(0, cur_a, cur_b, 16);
-    step(1, cur_a, cur_b, 32);
-    step(0, cur_a, cur_b, 48);
+    if constexpr (BK == 64) {
+      step(1, cur_a, cur_b, 32);
+      step(0, cur_a, cur_b, 48);
+    }
     // Tile kt+1 must have landed (younger tiles may still be in flight).  Every fragment of tile
     // kt is in registers, so after this barrier its stage may be refilled.
     __builtin_amdgcn_s_waitcnt(WAIT_TILE);
@@ -658,6 +665,23 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_bf16_wgrad_persis
   }
   if (!first && head > 0)
     dma_tile<BM, BN, WAVES_M, WAVES_N, false, false, NSTAGE, PMC_EPI_ACCUM_F32, SEG>(p, smem, tm0, tn0, 0, head);
+#endif
+}
+
+// Weight-gradient products, two workgroups per compute unit: 256x128 tiles, four waves of 128x64
+// (the same wave tile as the kernels above, so the same LDS traffic per matrix instruction), a ring of
+// three 32-deep stages (72 KB).  Two such workgroups fit a compute unit (144 KB of LDS, two waves per
+// SIMD), each with its own barriers: while one adds its finished tile into C at memory speed, the other
+// runs its K loop, without any arrangement between them, and the two waves of a SIMD no longer wait at
+// the same barrier.  Both operands of a weight gradient are stored [k][rows], so a 32-deep tile still
+// reads whole 256- and 512-byte rows.
+template <bool SEG>
+__global__ __launch_bounds__(256, 2) void gemm_bf16_wgrad_pair_kernel(GemmParams p) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
+  int tile_m, tile_n;
+  tile_of_block(p, tile_m, tile_n);
+  dma_tile<256, 128, 2, 2, false, false, 3, PMC_EPI_ACCUM_F32, SEG, 32>(p, smem, tile_m, tile_n, 0, 2 * p.k_tiles_per_split);
 #endif
 }
 
@@ -872,6 +896,35 @@ int launch_wgrad_persistent(hipStream_t st, GemmParams p) {
   return PMC_OK;
 }
 
+// The two-workgroup kernel pays 1.5x the operand traffic of 256x256 tiles and a barrier every 16 matrix
+// instructions; it wins where the K loop is short, so that a tile's ring fill and read-modify-write
+// epilogue weigh as much as its K loop (measured on whole steps: -5 % of the W pass at 1024 tokens,
+// +6 % at 2048, +26 % at 4096).  Taking it for some of a layer's products only (those with 256 tiles
+// or more) was slower than taking it for none, so the bar on the tile count is low.  gemm_wgrad = 2 forces it.
+bool use_wgrad_pair(const GemmParams& p) {
+  if (const int f = tuning(kTuneGemmWgrad); f >= 0) return f == 2;
+  if (tuning(kTuneGemmTile) >= 0) return false;
+  return p.K <= 1024 && (long)((p.M + 255) / 256) * ((p.N + 127) / 128) >= 64;
+}
+
+template <bool SEG>
+int launch_wgrad_pair(hipStream_t st, GemmParams p) {
+  constexpr size_t lds = (size_t)3 * (256 + 128) * 32 * sizeof(bf16_t);
+  auto kern = gemm_bf16_wgrad_pair_kernel<SEG>;
+  static std::atomic<bool> configured{false};
+  if (int rc = reserve_lds(kern, lds, configured, "gemm_bf16")) return rc;
+  p.tiles_m = (p.M + 255) / 256;
+  p.tiles_n = (p.N + 127) / 128;
+  {
+    const int forced = tuning(kTuneGemmGroup);
+    p.group_m = forced > 0 ? forced : 4;
+  }
+  kern<<<dim3(p.tiles_m * p.tiles_n), dim3(256), lds, st>>>(p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(PMC_ERR_HIP, "gemm_bf16 weight-gradient launch failed: %s", hipGetErrorString(e));
+  return PMC_OK;
+}
+
 // Split K: when even 128x128 tiles leave most compute units idle (skinny products such as the
 // [tokens, hidden] outputs at short sequence length), K is cut into `splits` ranges, each range
 // writes an fp32 partial product to the workspace and a second kernel adds them and applies the
@@ -982,6 +1035,7 @@ int gemm_bf16(hipStream_t st, const GemmArgs& a) {
       if (rc != PMC_OK) return rc;
       return launch_reduce(st, p, (const float*)a.ws, splits, a.epilogue);
     }
+    if (!a_kmaj && !b_kmaj && a.epilogue == PMC_EPI_ACCUM_F32 && use_wgrad_pair(p)) return launch_wgrad_pair<false>(st, p);
     if (!a_kmaj && !b_kmaj && a.epilogue == PMC_EPI_ACCUM_F32 && use_wgrad_persistent(p)) return launch_wgrad_persistent<false>(st, p);
     const int rc = launch_fast(st, p, a_kmaj, b_kmaj, a.epilogue);
     if (rc != kNoFastPath) return rc;
@@ -1018,6 +1072,7 @@ int gemm_bf16_grouped_wgrad(hipStream_t st, const GroupedWgradArgs& a) {
     p.Aseg[i] = (const bf16_t*)a.A[j];
     p.Bseg[i] = (const bf16_t*)a.B[j];
   }
+  if (use_wgrad_pair(p)) return launch_wgrad_pair<true>(st, p);
   if (use_wgrad_persistent(p)) return launch_wgrad_persistent<true>(st, p);
   return launch_dma_tile<false, false, PMC_EPI_ACCUM_F32, true>(st, p);
 }

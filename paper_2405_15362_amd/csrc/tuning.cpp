@@ -20,7 +20,7 @@ struct Entry {
 };
 constexpr Entry kEntries[kTuneCount] = {
     {"gemm_tile", "PMC_GEMM_TILE", 0, 4},      {"gemm_group", "PMC_GEMM_GROUP", 1, 64},
-    {"gemm_wgrad", "PMC_GEMM_WGRAD", 0, 1},    {"attn_shape", "PMC_ATTN_SHAPE", 0, 2},
+    {"gemm_wgrad", "PMC_GEMM_WGRAD", 0, 2},    {"attn_shape", "PMC_ATTN_SHAPE", 0, 2},
     {"w_streams", "PMC_W_STREAMS", 1, 2},
 };
 std::atomic<int> g_value[kTuneCount];

@@ -141,7 +141,29 @@ def test_gemm_bf16_weight_gradient_persistent(ctx, tune):
     assert rel_l2(host(outs[0]), host(outs[2])) <= 1e-6     # the plain kernel adds K in one piece
 
 
-@pytest.mark.parametrize("wgrad", [0, 1])
+def test_gemm_bf16_weight_gradient_two_workgroups_per_unit(ctx, tune):
+    """The W-pass kernel with 256x128 tiles and a ring of 32-deep stages (two workgroups share a compute
+    unit): fewer tiles than units, many more, ragged edges in both directions, K of one 64-wide tile (two
+    ring tiles, fewer than the ring has stages), short and long K; the same bits from run to run; and the
+    same sums as the plain kernel up to fp32 summation order."""
+    tune(gemm_wgrad=2)
+    for M, N, K in ((512, 256, 64), (264, 136, 128), (264, 136, 1024), (4104, 4360, 256), (4096, 4608, 576), (3848, 4872, 1280)):
+        _gemm_case(ctx, "bf16", True, False, M, N, K, P.EPI_ACCUM_F32)
+    a = dev(mat(("wg", "a"), (1024, 4104), "bf16"), "bf16")
+    b = dev(mat(("wg", "b"), (1024, 4360), "bf16", 0.05), "bf16")
+    c0 = dev(mat(("wg", "c"), (4104, 4360), "f32"), "f32")
+    outs = []
+    for flag in (2, 2, 0):
+        tune(gemm_wgrad=flag)
+        c = c0.clone()
+        P.pmc_gemm(ctx, a, b, c, True, False, P.EPI_ACCUM_F32)
+        outs.append(c)
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0], outs[1])
+    assert rel_l2(host(outs[0]), host(outs[2])) <= 1e-6
+
+
+@pytest.mark.parametrize("wgrad", [0, 1, 2])
 def test_gemm_bf16_grouped_weight_gradient(ctx, tune, wgrad):
     """Queued weight gradients as one product: C += sum_i A_i^T B_i over pieces that live in separate
     buffers.  Every tile shape of the plain kernel and the persistent one; one piece, several pieces,

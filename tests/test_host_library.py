@@ -209,7 +209,7 @@ def test_adaptive_search_larger_and_bad_arguments():
 def test_tuning_switches():
     """Switches are process-wide integers; -1 hands the choice back; unknown names and values out of
     range are refused (no GPU needed: nothing is launched)."""
-    for name, good, bad in (("gemm_tile", 4, 5), ("gemm_wgrad", 1, 2), ("attn_shape", 2, 3), ("w_streams", 1, 0),
+    for name, good, bad in (("gemm_tile", 4, 5), ("gemm_wgrad", 2, 3), ("attn_shape", 2, 3), ("w_streams", 1, 0),
                             ("gemm_group", 8, 0)):
         P.pmc_tuning_set(name, good)
         assert P.pmc_tuning_get(name) == good

@@ -172,7 +172,7 @@ def run_workload(P, R, synth, torch, np, name, cfg, steps, warmup, queued, want_
 
     traffic, traffic_src = stored_traffic(name)
     roofline = {"bound": "mfma",
-                "kernel": "gemm_bf16_dma_kernel / gemm_bf16_wgrad_persistent_kernel, with "
+                "kernel": "gemm_bf16_dma_kernel / gemm_bf16_wgrad_persistent_kernel / gemm_bf16_wgrad_pair_kernel, with "
                           "splitk_reduce_kernel where K is split (every product of a step: 4 projections x F,B,W x layers)",
                 "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_BF16_TFLOPS, 4),

@@ -42,6 +42,13 @@ struct Vec<float> {
     f32x4 v = {in[0], in[1], in[2], in[3]};
     *reinterpret_cast<f32x4*>(p) = v;
   }
+  // the 16 bytes as they are in memory (a row kept this way costs 4 registers per chunk whatever the type)
+  __device__ static __forceinline__ u32x4 load_raw(const float* p) { return *reinterpret_cast<const u32x4*>(p); }
+  __device__ static __forceinline__ void store_raw(float* p, u32x4 v) { *reinterpret_cast<u32x4*>(p) = v; }
+  __device__ static __forceinline__ void unpack(u32x4 v, float* out) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) out[i] = __uint_as_float(v[i]);
+  }
 };
 template <>
 struct Vec<bf16_t> {
@@ -59,6 +66,15 @@ struct Vec<bf16_t> {
 #pragma unroll
     for (int i = 0; i < 4; ++i) v[i] = pack_bf16x2(in[2 * i], in[2 * i + 1]);
     *reinterpret_cast<u32x4*>(p) = v;
+  }
+  __device__ static __forceinline__ u32x4 load_raw(const bf16_t* p) { return *reinterpret_cast<const u32x4*>(p); }
+  __device__ static __forceinline__ void store_raw(bf16_t* p, u32x4 v) { *reinterpret_cast<u32x4*>(p) = v; }
+  __device__ static __forceinline__ void unpack(u32x4 v, float* out) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      out[2 * i] = bf16lo_to_f32(v[i]);
+      out[2 * i + 1] = bf16hi_to_f32(v[i]);
+    }
   }
 };
 

@@ -621,14 +621,14 @@ __device__ __forceinline__ void dma_tile(const GemmParams& p, bf16_t* smem, int 
 #endif
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KMAJ, bool B_KMAJ, int NSTAGE, int EPI, bool SEG = false>
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KMAJ, bool B_KMAJ, int NSTAGE, int EPI, bool SEG = false, int BK = 64>
 __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_bf16_dma_kernel(GemmParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)
   extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
   int tile_m, tile_n;
   tile_of_block(p, tile_m, tile_n);
-  const int nk = p.k_tiles_per_split;
-  dma_tile<BM, BN, WAVES_M, WAVES_N, A_KMAJ, B_KMAJ, NSTAGE, EPI, SEG>(p, smem, tile_m, tile_n, (int)blockIdx.y * nk, nk);
+  const int nk = p.k_tiles_per_split * (64 / BK);
+  dma_tile<BM, BN, WAVES_M, WAVES_N, A_KMAJ, B_KMAJ, NSTAGE, EPI, SEG, BK>(p, smem, tile_m, tile_n, (int)blockIdx.y * nk, nk);
 #endif
 }
 
@@ -640,12 +640,12 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_bf16_dma_kernel(G
 // workgroup id) starts its first tile at K tile g/G of the way through, and comes back for that
 // tile's first K tiles after its last tile.  Both parts are added into C by the same workgroup, in
 // that order, so the result depends on the launch shape alone.
-template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int GROUPS, bool SEG = false>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NSTAGE, int GROUPS, bool SEG = false, int BK = 64>
 __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_bf16_wgrad_persistent_kernel(GemmParams p) {
 #if defined(__HIP_DEVICE_COMPILE__)
   extern __shared__ __attribute__((aligned(1024))) bf16_t smem[];
   const int ntiles = p.tiles_m * p.tiles_n, G = gridDim.x, b = blockIdx.x;
-  const int nk = p.k_tiles_per_split;  // all of K
+  const int nk = p.k_tiles_per_split * (64 / BK);  // all of K, in tiles of this depth
   const int group = (b >> 3) % GROUPS;  // neighbours on one XCD fall into different groups
   const int head = (nk * group) / GROUPS;  // K tiles of the first tile left for the end
   bool first = true;
@@ -656,15 +656,15 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_bf16_wgrad_persis
     if (first) {
       tm0 = tile_m;
       tn0 = tile_n;
-      dma_tile<BM, BN, WAVES_M, WAVES_N, false, false, NSTAGE, PMC_EPI_ACCUM_F32, SEG>(p, smem, tile_m, tile_n, head, nk - head);
+      dma_tile<BM, BN, WAVES_M, WAVES_N, false, false, NSTAGE, PMC_EPI_ACCUM_F32, SEG, BK>(p, smem, tile_m, tile_n, head, nk - head);
       first = false;
     } else {
-      dma_tile<BM, BN, WAVES_M, WAVES_N, false, false, NSTAGE, PMC_EPI_ACCUM_F32, SEG>(p, smem, tile_m, tile_n, 0, nk);
+      dma_tile<BM, BN, WAVES_M, WAVES_N, false, false, NSTAGE, PMC_EPI_ACCUM_F32, SEG, BK>(p, smem, tile_m, tile_n, 0, nk);
     }
     __syncthreads();
   }
   if (!first && head > 0)
-    dma_tile<BM, BN, WAVES_M, WAVES_N, false, false, NSTAGE, PMC_EPI_ACCUM_F32, SEG>(p, smem, tm0, tn0, 0, head);
+    dma_tile<BM, BN, WAVES_M, WAVES_N, false, false, NSTAGE, PMC_EPI_ACCUM_F32, SEG, BK>(p, smem, tm0, tn0, 0, head);
 #endif
 }
 
@@ -790,12 +790,12 @@ int launch_tile(hipStream_t st, const GemmParams& p, int epi) {
   return launch_epi<128, 128, 64, 64, 64, A_KMAJ, B_KMAJ>(st, p, epi);
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KMAJ, bool B_KMAJ, int NSTAGE, int EPI, bool SEG = false>
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool A_KMAJ, bool B_KMAJ, int NSTAGE, int EPI, bool SEG = false, int BK = 64>
 int launch_dma(hipStream_t st, GemmParams p) {
   constexpr int NT = WAVES_M * WAVES_N * 64;
-  constexpr size_t lds = (size_t)NSTAGE * (BM + BN) * 64 * sizeof(bf16_t);
+  constexpr size_t lds = (size_t)NSTAGE * (BM + BN) * BK * sizeof(bf16_t);
   static_assert(lds <= 160 * 1024, "stages do not fit the 160 KB LDS");
-  auto kern = gemm_bf16_dma_kernel<BM, BN, WAVES_M, WAVES_N, A_KMAJ, B_KMAJ, NSTAGE, EPI, SEG>;
+  auto kern = gemm_bf16_dma_kernel<BM, BN, WAVES_M, WAVES_N, A_KMAJ, B_KMAJ, NSTAGE, EPI, SEG, BK>;
   static std::atomic<bool> configured{false};  // per instantiation
   if (int rc = reserve_lds(kern, lds, configured, "gemm_bf16")) return rc;
   p.tiles_m = (p.M + BM - 1) / BM;
@@ -842,7 +842,11 @@ int launch_dma_tile(hipStream_t st, const GemmParams& p) {
   // top it would spill registers, so weight-gradient products do not use it
   constexpr bool kWideOk = EPI != PMC_EPI_ACCUM_F32;
   switch (pick_tile(p.M, p.N, kWideOk)) {
-    case 0: return launch_dma<256, 256, 2, 4, A_KMAJ, B_KMAJ, 2, EPI, SEG>(st, p);
+    case 0:
+      // both operands stored [k][rows] (weight gradients): four 32-deep stages instead of two 64-deep ones, see
+      // launch_wgrad_persistent
+      if constexpr (!A_KMAJ && !B_KMAJ) return launch_dma<256, 256, 2, 4, A_KMAJ, B_KMAJ, 4, EPI, SEG, 32>(st, p);
+      else return launch_dma<256, 256, 2, 4, A_KMAJ, B_KMAJ, 2, EPI, SEG>(st, p);
     case 1: return launch_dma<256, 128, 4, 2, A_KMAJ, B_KMAJ, 3, EPI, SEG>(st, p);
     case 4:
       if constexpr (kWideOk) return launch_dma<256, 320, 4, 2, A_KMAJ, B_KMAJ, 2, EPI, SEG>(st, p);
@@ -877,9 +881,14 @@ bool use_wgrad_persistent(const GemmParams& p) {
 
 template <bool SEG>
 int launch_wgrad_persistent(hipStream_t st, GemmParams p) {
-  constexpr int NSTAGE = 2, GROUPS = 2;  // measured: 2 phases give the most (1: -6 % W-pass time, 2: -8 %, 4 and 8: -7 %)
-  constexpr size_t lds = (size_t)NSTAGE * (256 + 256) * 64 * sizeof(bf16_t);
-  auto kern = gemm_bf16_wgrad_persistent_kernel<256, 256, 2, 4, NSTAGE, GROUPS, SEG>;
+  // measured: 2 phases give the most (1: -6 % W-pass time, 2: -8 %, 4 and 8: -7 %).  The ring is four 32-deep
+  // stages rather than two 64-deep ones: the same LDS, but a tile is requested three steps (1.5 times as
+  // far) ahead of its use, which the weight gradient's operand panels, the least shared in L2 of all products,
+  // need most; both operands are stored [k][rows], so a 32-deep tile still reads whole rows.  Measured on
+  // whole steps: W pass -3 % at 4096 tokens, -5 % at 2048.
+  constexpr int NSTAGE = 4, GROUPS = 2, BK = 32;
+  constexpr size_t lds = (size_t)NSTAGE * (256 + 256) * BK * sizeof(bf16_t);
+  auto kern = gemm_bf16_wgrad_persistent_kernel<256, 256, 2, 4, NSTAGE, GROUPS, SEG, BK>;
   static std::atomic<bool> configured{false};
   if (int rc = reserve_lds(kern, lds, configured, "gemm_bf16")) return rc;
   const int units = compute_units();
